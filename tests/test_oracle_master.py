@@ -1,0 +1,353 @@
+"""Pins for the oracle's master update (no GPU).
+
+Each test checks the oracle against something the paper or the mathematics
+fixes, not against a second copy of its own loop:
+  * heavy-ball momentum (Sec. 2)                       -> matrix-power closed form
+  * no Gap without intervening updates (Sec. 4.1)      -> W = 1 makes all modes equal
+  * SA-gradient divides g by tau (Alg. 5)              -> harmonic-sum closed form
+  * SA step-size form, two-step expansion (Sec. 3.1)   -> the printed identity
+  * C coefficient (Alg. 14) and Gap = delay when all updates point the same
+    way (remark after Def. 1)                          -> constant-gradient closed form
+  * Gap penalty 1/G on the gradient (Alg. 4)           -> dyadic one-step example, fixed point
+  * Gap is scale free (Def. 1: C is a distance)        -> power-of-two rescaling is bit exact
+  * parameter-wise independence (Sec. 4.3)             -> subset runs equal the full run
+"""
+import numpy as np
+import pytest
+
+import ga_inputs
+import oracle
+from oracle import MODE_ASGD, MODE_GA, MODE_GA_HINGE, MODE_SA, MODE_SA_STEP, Hyper, Master
+
+ALL_MODES = [MODE_ASGD, MODE_SA, MODE_SA_STEP, MODE_GA, MODE_GA_HINGE]
+
+
+def quad_inputs(N, seed, dtype):
+    return ga_inputs.curvatures(N, seed).astype(dtype), ga_inputs.optimum(N, seed).astype(dtype)
+
+
+# ---------------------------------------------------------------- momentum
+@pytest.mark.parametrize("gamma", [0.9, 0.0, -0.5])
+def test_single_worker_matches_heavy_ball_closed_form(gamma):
+    # noise-free quadratic, one worker: g_k = a (theta_k - theta*), so per coordinate
+    # [e; v]_{k+1} = A [e; v]_k with e = theta - theta*, A = [[1 - eta a, -eta gamma], [a, gamma]].
+    N, T, eta = 64, 200, 0.1
+    a, ts = quad_inputs(N, 3, np.float64)
+    sched = np.zeros(T, dtype=np.uint32)
+    expect = np.empty(N)
+    for j in range(N):
+        A = np.array([[1 - eta * a[j], -eta * gamma], [a[j], gamma]])
+        e = np.linalg.matrix_power(A, T) @ np.array([0.0 - ts[j], 0.0])
+        expect[j] = ts[j] + e[0]
+    for mode in ALL_MODES:
+        M = Master(N, 1, mode, Hyper(eta, gamma, f32=False), np.float64)
+        M.run_quadratic(sched, a, ts, seed=0, sigma=0.0)
+        assert np.allclose(M.theta, expect, rtol=1e-10, atol=1e-12), mode
+    M32 = Master(N, 1, MODE_GA, Hyper(eta, gamma), np.float32)
+    M32.run_quadratic(sched, a.astype(np.float32), ts.astype(np.float32), seed=0, sigma=0.0)
+    assert np.allclose(M32.theta, expect, rtol=2e-4, atol=2e-5)
+
+
+def test_single_worker_all_modes_bit_identical():
+    # With one worker the master's parameters never move between send and
+    # receive: the Gap term is zero, tau = 1, and every penalty is exactly 1.
+    N, T = 1000, 60
+    a, ts = quad_inputs(N, 5, np.float32)
+    sched = np.zeros(T, dtype=np.uint32)
+    ref = None
+    for mode in ALL_MODES:
+        M = Master(N, 1, mode, Hyper(), np.float32)
+        tau = M.run_quadratic(sched, a, ts, seed=17, sigma=0.01)
+        assert np.all(tau == 1)
+        if ref is None:
+            ref = (M.theta.copy(), M.v.copy())
+        assert np.array_equal(M.theta, ref[0]) and np.array_equal(M.v, ref[1]), mode
+        assert np.array_equal(M.snaps[0], M.theta)
+
+
+def test_plain_sgd_sum_when_gamma_zero():
+    # Alg. 2 with gamma = 0: theta_K = theta_0 - eta * sum of the gradients received.
+    N, W, T = 50, 4, 40
+    rng = np.random.default_rng(0)
+    bufs = rng.standard_normal((W, N))
+    sched = rng.integers(0, W, T).astype(np.uint32)
+    M = Master(N, W, MODE_ASGD, Hyper(0.05, 0.0, f32=False), np.float64, theta0=rng.standard_normal(N))
+    th0 = M.theta.copy()
+    M.run_buffers(sched, bufs, pick_by_worker=True)
+    assert np.allclose(M.theta, th0 - 0.05 * bufs[sched].sum(0), rtol=1e-12, atol=1e-13)
+
+
+# ---------------------------------------------------------------- SA
+def test_sa_gradient_harmonic_closed_form():
+    # Alg. 5, gamma = 0, the same gradient c from everyone, round robin over W:
+    # tau_k = min(k, W), theta_K = -eta c sum_k 1/tau_k.
+    N, W, T, eta = 8, 6, 30, 0.1
+    c = np.linspace(-2, 2, N)
+    bufs = np.tile(c, (1, 1))
+    sched = (np.arange(T) % W).astype(np.uint32)
+    M = Master(N, W, MODE_SA, Hyper(eta, 0.0, f32=False), np.float64)
+    tau = M.run_buffers(sched, bufs)
+    assert tau.tolist() == [min(k, W) for k in range(1, T + 1)]
+    H = sum(1.0 / min(k, W) for k in range(1, T + 1))
+    assert np.allclose(M.theta, -eta * c * H, rtol=1e-13, atol=0)
+    # step-size form (Alg. 3) coincides with the gradient form when gamma = 0
+    M2 = Master(N, W, MODE_SA_STEP, Hyper(eta, 0.0, f32=False), np.float64)
+    M2.run_buffers(sched, bufs)
+    assert np.allclose(M2.theta, M.theta, rtol=1e-13, atol=0)
+    # and differs once there is momentum (the under-penalisation of Sec. 3.1)
+    Ma = Master(N, W, MODE_SA, Hyper(eta, 0.9, f32=False), np.float64)
+    Mb = Master(N, W, MODE_SA_STEP, Hyper(eta, 0.9, f32=False), np.float64)
+    Ma.run_buffers(sched, bufs)
+    Mb.run_buffers(sched, bufs)
+    assert not np.allclose(Ma.theta, Mb.theta, rtol=1e-3)
+
+
+def test_sa_step_two_step_identity():
+    # Sec. 3.1: theta_{k+2} = theta_{k+1} - (eta/tau_{k+1}) (gamma^2 v_k + gamma g_k + g_{k+1}).
+    N, W, eta, gamma = 16, 3, 0.1, 0.9
+    rng = np.random.default_rng(1)
+    M = Master(N, W, MODE_SA_STEP, Hyper(eta, gamma, f32=False), np.float64, theta0=rng.standard_normal(N))
+    M.v[:] = rng.standard_normal(N)
+    # put the master at step 7 with worker 2 last seen at 1 (tau = 7) and worker 0 at 7... (tau = 2 next)
+    M.k = 7
+    M.iter[:] = [7, 5, 1]
+    v_k, th_k = M.v.copy(), M.theta.copy()
+    g_k, g_k1 = rng.standard_normal(N), rng.standard_normal(N)
+    assert M.apply(2, g_k) == 7                    # stale gradient
+    th_k1 = M.theta.copy()
+    assert np.allclose(th_k1, th_k - (eta / 7) * (gamma * v_k + g_k), rtol=1e-13)
+    assert M.apply(0, g_k1) == 2                   # fast worker
+    expect = th_k1 - (eta / 2) * (gamma ** 2 * v_k + gamma * g_k + g_k1)
+    assert np.allclose(M.theta, expect, rtol=1e-12, atol=1e-14)
+
+
+# ---------------------------------------------------------------- C coefficient and the Gap
+@pytest.mark.parametrize("dtype,tol", [(np.float64, 1e-7), (np.float32, 2e-5)])
+def test_constant_gradient_gap_equals_delay(dtype, tol):
+    # ASGD, gamma = 0, every worker sends the same c: v = c at every step, so
+    # m_k = (1 - beta^k) c^2, m-hat = c^2 and C = eta_max (|c| + eps) for every k (Alg. 14).
+    # A worker whose snapshot is s master steps old sees |theta - theta^i| = s eta |c|,
+    # i.e. Graw = s and the paper's Gap = s + 1 = its delay at the next arrival:
+    # "E[G_k] = tau_k only if all previous updates were in the exact same direction".
+    N, W, T, eta = 32, 5, 57, 0.1
+    c = np.linspace(0.5, 3.0, N).astype(dtype) * np.where(np.arange(N) % 2, 1, -1).astype(dtype)
+    bufs = np.ascontiguousarray(c[None, :])
+    rng = np.random.default_rng(2)
+    sched = rng.integers(0, W, T).astype(np.uint32)
+    sched[-W:] = rng.permutation(W)                 # everyone has arrived at least once
+    M = Master(N, W, MODE_ASGD, Hyper(eta, 0.0, f32=(dtype == np.float32)), dtype, track_gap=True)
+    M.run_buffers(sched, bufs)
+    assert np.allclose(M.m, (1 - 0.999 ** T) * c.astype(np.float64) ** 2, rtol=50 * tol)
+    for w in range(W):
+        age = M.k - int(M.iter[w])                   # master steps since w's snapshot
+        st = M.gap_statistics(w)
+        assert abs(st["mean_graw"] - age) <= tol * max(1, age), (w, age, st)
+        assert st["frac_gt0"] == (1.0 if age > 0 else 0.0)
+        assert st["n_nonfinite"] == 0
+    # changing eta_k later must not change C: it is tied to eta_max
+    w = int(np.argmax(M.k - M.iter.astype(np.int64)))
+    before = M.gap_statistics(w)["mean_graw"]
+    M.hyper.eta_k = M.hyper.eta_k / 4
+    assert M.gap_statistics(w)["mean_graw"] == before
+    M.hyper.eta_max = M.hyper.eta_max / 4
+    assert abs(M.gap_statistics(w)["mean_graw"] - 4 * before) < 1e-4 * before
+
+
+def test_first_step_coefficient():
+    # After the first arrival the bias correction cancels: m-hat_1 = v_2^2, C_1 = eta_max (|v_2| + eps).
+    # Second arrival from another worker (snapshot still theta_0): |theta - theta^i| = eta |v_2|,
+    # so Graw = |v_2| / (|v_2| + eps) ~ 1, paper's penalty ~ 1/2, hinge penalty exactly 1.
+    N, eta = 40, 0.1
+    rng = np.random.default_rng(3)
+    g1, g2 = rng.standard_normal(N), rng.standard_normal(N)
+    for mode, pen in [(MODE_GA, 0.5), (MODE_GA_HINGE, 1.0)]:
+        M = Master(N, 2, mode, Hyper(eta, 0.9, f32=False), np.float64)
+        M.apply(0, g1)
+        assert np.allclose(M.v, g1, rtol=0, atol=0)                 # Gap is zero at k = 1
+        assert np.allclose(M.m, 0.001 * g1 ** 2, rtol=1e-12)
+        st = M.gap_statistics(1)
+        assert abs(st["mean_graw"] - 1.0) < 1e-6
+        M.apply(1, g2)
+        assert np.allclose(M.v, 0.9 * g1 + pen * g2, rtol=1e-6, atol=1e-9), mode
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+def test_dyadic_one_step_example(dtype):
+    # Alg. 4 + Alg. 14 on numbers that are exact in binary, worked by hand:
+    # beta = 1/2, k = 2: 1 - beta^(k-1) = 1/2.  m_1 = 1/32 -> m-hat = 1/16 -> sqrt = 1/4;
+    # eps = 0, eta_max = 1/2 -> C = 1/8.  theta = 1, theta^i = 1/2 -> |diff| = 1/2 -> Graw = 4.
+    # Paper: G = 5, g = 10 -> g/G = 2;  v' = 1/2 * 1/4 + 2 = 2.125;  eta_k = 1/4 -> theta' = 1 - 0.53125.
+    # m' = 1/2 * 1/32 + 1/2 * 2.125^2 = 2.2734375.
+    # Hinge: G = 4 -> g/G = 2.5; v' = 2.625; theta' = 1 - 0.65625; m' = 1/64 + 3.4453125.
+    h = Hyper(eta=0.5, gamma=0.5, beta=0.5, eps=0.0, eta_k=0.25, f32=False)
+    for mode, v1, th1, m1 in [(MODE_GA, 2.125, 0.46875, 2.2734375), (MODE_GA_HINGE, 2.625, 0.34375, 3.4609375)]:
+        th, v, m = np.array([1.0], dtype), np.array([0.25], dtype), np.array([0.03125], dtype)
+        s, g = np.array([0.5], dtype), np.array([10.0], dtype)
+        oracle.step(th, v, m, s, g, mode, k=2, tau=3, hyper=h)
+        assert (v[0], th[0], m[0], s[0]) == (v1, th1, m1, th1)
+    # negative difference and negative gradient: the Gap uses |diff|, the sign of g survives
+    th, v, m = np.array([0.5], dtype), np.array([0.25], dtype), np.array([0.03125], dtype)
+    s, g = np.array([1.0], dtype), np.array([-10.0], dtype)
+    oracle.step(th, v, m, s, g, MODE_GA, k=2, tau=3, hyper=h)
+    assert (v[0], th[0]) == (-1.875, 0.5 + 0.46875)
+    # SA on the same numbers: g / tau (Alg. 5) and eta / tau (Alg. 3), tau = 4
+    th, v, m = np.array([1.0], dtype), np.array([0.25], dtype), np.array([0.0], dtype)
+    s = np.array([0.5], dtype)
+    oracle.step(th, v, m, s, np.array([10.0], dtype), MODE_SA, k=9, tau=4, hyper=h)
+    assert (v[0], th[0], m[0]) == (2.625, 1 - 0.65625, 0.0)         # m untouched without tracking
+    th, v = np.array([1.0], dtype), np.array([0.25], dtype)
+    oracle.step(th, v, m, s, np.array([10.0], dtype), MODE_SA_STEP, k=9, tau=4, hyper=h)
+    assert (v[0], th[0]) == (10.125, 1 - 0.0625 * 10.125)
+
+
+@pytest.mark.parametrize("mode,limit", [(MODE_GA, lambda W: W), (MODE_GA_HINGE, lambda W: W - 1)])
+def test_gap_penalty_fixed_point_equals_delay(mode, limit):
+    # GA, gamma = 0, same gradient c from everyone, round robin over W workers.
+    # If every step has size c/p then C -> eta |c|/p and a snapshot W-1 steps old gives
+    # Graw = W-1, so p = W (paper: Graw + 1) or W-1 (hinge): the penalty settles at
+    # the delay tau = W, the bound the paper states for aligned updates (after Def. 1).
+    N, W, T, eta = 4, 6, 1500, 0.1
+    c = np.array([0.3, -1.0, 2.0, 5.0])
+    M = Master(N, W, mode, Hyper(eta, 0.0, beta=0.9, eps=1e-12, f32=False), np.float64)
+    M.run_buffers((np.arange(T) % W).astype(np.uint32), np.ascontiguousarray(c[None, :]))
+    assert np.allclose(M.v, c / limit(W), rtol=1e-6)
+
+
+@pytest.mark.parametrize("mode", [MODE_GA, MODE_GA_HINGE])
+def test_gap_is_scale_free(mode):
+    # Def. 1 measures distance in units of C, itself a distance: scaling the problem
+    # (theta*, noise, and the guard eps that is added to a distance) by a power of two
+    # scales the whole trajectory by it, bit for bit.
+    N, W, T = 500, 4, 300
+    a, ts = quad_inputs(N, 9, np.float32)
+    sched = oracle.simulate_schedule(W, T, seed=9)
+    out = []
+    for s in (1.0, 1024.0):
+        M = Master(N, W, mode, Hyper(eps=float(np.float32(1e-8)) * s), np.float32)
+        M.run_quadratic(sched, a, (ts * np.float32(s)), seed=4, sigma=float(np.float32(0.01)) * s)
+        out.append(M.theta / np.float32(s))
+    assert np.array_equal(out[0], out[1])
+    assert np.linalg.norm(out[0]) > 0
+
+
+@pytest.mark.parametrize("mode", [MODE_GA, MODE_GA_HINGE])
+def test_gap_zero_means_no_penalty_and_large_gap_divides(mode):
+    N = 1000
+    th, v, m, snaps = ga_inputs.random_state(N, 1, 6)
+    g = ga_inputs.rng(6, 9).standard_normal(N, dtype=np.float32)
+    h = Hyper()
+    # snapshot equal to theta: identical to the momentum step of Alg. 2
+    a = [x.copy() for x in (th, v, m)]
+    b = [x.copy() for x in (th, v, m)]
+    sa, sb = th.copy(), th.copy()
+    oracle.step(*a, sa, g, mode, 50, 7, h)
+    oracle.step(*b, sb, g, MODE_ASGD, 50, 7, h, track_gap=True)
+    for x, y in zip(a + [sa], b + [sb]):
+        assert np.array_equal(x, y)
+    # generic snapshot: v' - gamma v must equal g / G with G rebuilt in double from the
+    # state (|diff|, m, 1 - beta^(k-1)); checks the 1/G placement and the bias correction
+    t2, v2, m2, s2 = th.copy(), v.copy(), m.copy(), snaps[0].copy()
+    oracle.step(t2, v2, m2, s2, g, mode, 50, 7, h)
+    bc = 1 - np.float64(h.beta) ** 49
+    C = h.eta_max * (np.sqrt(m.astype(np.float64) / bc) + h.eps)
+    graw = np.abs(th.astype(np.float64) - snaps[0]) / C
+    G = 1 + graw if mode == MODE_GA else np.maximum(1, graw)
+    got = v2.astype(np.float64) - np.float64(h.gamma) * v
+    assert np.allclose(got, g / G, rtol=2e-5, atol=2e-7)
+    assert np.array_equal(s2, t2)
+
+
+# ---------------------------------------------------------------- structure
+def test_snapshots_and_bookkeeping():
+    N, W, T = 64, 5, 200
+    a, ts = quad_inputs(N, 2, np.float32)
+    sched = oracle.simulate_schedule(W, T, seed=8)
+    M = Master(N, W, MODE_GA, Hyper(), np.float32)
+    hist = {}
+    for k, w in enumerate(sched, start=1):
+        w = int(w)
+        others = {u: M.snaps[u].copy() for u in range(W) if u != w}
+        g = oracle.quadratic_gradient(M.snaps[w], a, ts, seed=1, k=k)
+        M.apply(w, g)
+        assert np.array_equal(M.snaps[w], M.theta)           # save and send theta_{k+1}
+        for u, s in others.items():
+            assert np.array_equal(M.snaps[u], s)
+        hist[w] = M.theta.copy()
+    tau, it = oracle.delays(W, sched)
+    assert M.tau_log == tau.tolist() and np.array_equal(M.iter, it) and M.k == T
+    for w, s in hist.items():
+        assert np.array_equal(M.snaps[w], s)
+    # the fused loop (run_quadratic) is the same trajectory as apply-by-apply
+    M2 = Master(N, W, MODE_GA, Hyper(), np.float32)
+    M2.run_quadratic(sched, a, ts, seed=1)
+    assert np.array_equal(M2.theta, M.theta) and np.array_equal(M2.snaps, M.snaps)
+
+
+def test_parameter_wise_independence():
+    # Sec. 4.3: every parameter is penalised independently, so a gathered subset
+    # (with its global indices for the noise) reproduces the full run exactly.
+    N, W, T = 3001, 6, 120
+    a, ts = quad_inputs(N, 12, np.float32)
+    sched = oracle.simulate_schedule(W, T, seed=3)
+    for mode in (MODE_GA, MODE_SA):
+        full = Master(N, W, mode, Hyper(), np.float32)
+        full.run_quadratic(sched, a, ts, seed=77)
+        idx = ga_inputs.sample_indices(N, 100, 1)[::7].copy()
+        sub = Master(idx.size, W, mode, Hyper(), np.float32)
+        sub.run_quadratic(sched, a[idx], ts[idx], seed=77, idx=idx)
+        assert np.array_equal(sub.theta, full.theta[idx])
+        assert np.array_equal(sub.snaps, full.snaps[:, idx])
+        assert np.array_equal(sub.m, full.m[idx])
+
+
+def test_quadratic_gradient_is_the_gradient():
+    # g(sigma = 0) is the gradient of f(theta) = 1/2 sum a (theta - theta*)^2: central differences.
+    N = 12
+    a, ts = quad_inputs(N, 4, np.float64)
+    x = np.random.default_rng(0).standard_normal(N)
+    f = lambda y: 0.5 * np.sum(a * (y - ts) ** 2)
+    g = oracle.quadratic_gradient(x, a, ts, seed=0, k=1, sigma=0.0)
+    for j in range(N):
+        e = np.zeros(N)
+        e[j] = 1e-6
+        assert abs((f(x + e) - f(x - e)) / 2e-6 - g[j]) < 1e-8
+    # the noise term is sigma * z(seed, k, j), added as is
+    g2 = oracle.quadratic_gradient(x, a, ts, seed=5, k=3, sigma=0.01)
+    assert np.allclose(g2 - g, 0.01 * oracle.noise_f32(5, 3, 0, N).astype(np.float64), rtol=0, atol=1e-12)
+
+
+def test_minimum_of_the_quadratic_is_reached():
+    # brute force on a tiny problem: the grid minimiser of f is theta*, and the
+    # noise-free trajectories of the stable modes go there.
+    N, W, T = 3, 3, 4000
+    a, ts = quad_inputs(N, 8, np.float64)
+    grid = np.linspace(-4, 4, 161)
+    for j in range(N):
+        assert abs(grid[np.argmin(0.5 * a[j] * (grid - ts[j]) ** 2)] - ts[j]) <= 0.025 + 1e-12
+    sched = oracle.simulate_schedule(W, T, seed=2)
+    for mode in (MODE_SA, MODE_GA, MODE_GA_HINGE):
+        M = Master(N, W, mode, Hyper(f32=False), np.float64)
+        M.run_quadratic(sched, a, ts, seed=0, sigma=0.0)
+        assert np.allclose(M.theta, ts, atol=1e-3), mode
+
+
+def test_float_tracks_double_on_a_stable_run():
+    N, W, T = 2000, 8, 400
+    a, ts = quad_inputs(N, 1, np.float32)
+    sched = oracle.simulate_schedule(W, T, seed=1)
+    for mode in (MODE_SA, MODE_GA):
+        M32 = Master(N, W, mode, Hyper(), np.float32)
+        M64 = Master(N, W, mode, Hyper(), np.float64)
+        M32.run_quadratic(sched, a, ts, seed=1)
+        M64.run_quadratic(sched, a.astype(np.float64), ts.astype(np.float64), seed=1)
+        rel = np.linalg.norm(M32.theta - M64.theta) / np.linalg.norm(M64.theta)
+        assert rel < 1e-4, (mode, rel)
+
+
+def test_bf16_widening():
+    x = ga_inputs.rng(1, 0).standard_normal(1000, dtype=np.float32)
+    b = ga_inputs.f32_to_bf16_bits(x)
+    w = oracle.bf16_to_f32(b)
+    assert np.all(np.abs(w - x) <= np.abs(x) * 2.0 ** -8)
+    assert np.array_equal(ga_inputs.f32_to_bf16_bits(w), b)        # widening is exact
+    assert oracle.bf16_to_f32(np.array([0x3F80, 0xC000, 0x0000], np.uint16)).tolist() == [1.0, -2.0, 0.0]
