@@ -91,3 +91,37 @@ def sample_indices(N, n_random, seed, boundaries=()):
         parts.append(np.arange(max(0, int(b) - 8), min(N, int(b) + 8)))
     parts.append(rng(seed, 6).integers(0, N, size=n_random))
     return np.unique(np.concatenate(parts)).astype(np.uint64)
+
+
+# ---------------------------------------------------------------- device-side generators
+# For the full-size workloads the inputs are drawn on the GPU with torch's
+# seeded generator (drawing 10^8..10^9 normals with numpy would dominate the
+# run).  They are inputs like the numpy ones above: the oracle gets the same
+# values copied back (whole, or gathered at the sampled indices).
+def device_generator(seed, stream, device="cuda:0"):
+    import torch
+    g = torch.Generator(device=device)
+    g.manual_seed(int(seed) * 1000003 + int(stream))
+    return g
+
+
+def device_curvatures(N, seed, device="cuda:0", lo=0.1, hi=1.0):
+    import torch
+    u = torch.rand(N, dtype=torch.float32, device=device, generator=device_generator(seed, 1, device))
+    return u.mul_(hi - lo).add_(lo)
+
+
+def device_optimum(N, seed, device="cuda:0"):
+    import torch
+    return torch.randn(N, dtype=torch.float32, device=device, generator=device_generator(seed, 2, device))
+
+
+def device_gradient_buffers(n_bufs, N, seed, std=1e-2, dtype="f32", device="cuda:0"):
+    """List of n_bufs device tensors of N(0, std) gradients, float32 or bfloat16."""
+    import torch
+    g = device_generator(seed, 3, device)
+    out = []
+    for _ in range(n_bufs):
+        x = torch.randn(N, dtype=torch.float32, device=device, generator=g).mul_(std)
+        out.append(x.to(torch.bfloat16) if dtype == "bf16" else x)
+    return out

@@ -1,0 +1,266 @@
+/*
+ * libga -- the parameter-server master of Gap-Aware asynchronous SGD on one
+ * AMD MI355X (gfx950).
+ *
+ * Paper: Barkai, Hakimi, Schuster, "Gap-Aware Mitigation of Gradient
+ * Staleness", ICLR 2020.  Notation: the paper writes d for the number of
+ * parameters and N for the number of workers; this header writes N for the
+ * number of parameters and n_workers (W) for the number of workers.
+ *
+ * A context is one master (App. C.1: the master is a FIFO over worker
+ * arrivals).  It owns, inside a caller-provided device workspace:
+ *   theta[N]            master parameters                     (Sec. 2)
+ *   v[N]                update (momentum) vector              (Sec. 2, Alg. 2)
+ *   m[N]                biased second moment of v             (Alg. 14)
+ *   snap[W][N]          theta^i, what was last sent to worker i (Alg. 4: "save
+ *                       and send"; App. C.1: theta^i = theta_{k - tau_k})
+ * and on the host: the step counter k and iter[W] (Alg. 3 / Alg. 5).
+ * All state is float.  Gradients are float or bfloat16.
+ *
+ * Conventions
+ *   - "dev" pointers are device (HBM) addresses, "host" pointers are host
+ *     addresses.  The library never allocates or frees device memory: every
+ *     device buffer, including the workspace, belongs to the caller and must
+ *     stay valid until ga_destroy.  The library owns only the host-side ga_ctx.
+ *   - Every call that touches the device enqueues on the HIP stream given to
+ *     ga_create and returns without waiting, unless stated otherwise.
+ *   - Every function returning int returns a ga_status.  On any error nothing
+ *     has been enqueued and no state has changed; ga_last_error(ctx) describes
+ *     the failure.  No exception crosses this boundary.
+ *   - A context is not thread safe: one master, one caller at a time.
+ *
+ * Arithmetic of one arrival (worker i, gradient g, master step k >= 1,
+ * tau_k = k - iter[i]), per parameter j, every line one IEEE float operation:
+ *   GA modes (Alg. 4, Eq. 5; C from Alg. 14 as left by arrival k-1):
+ *       diff  = theta - snap_i            delta = |diff|
+ *       mhat  = m / (1 - beta^(k-1))      (taken as 0 when k = 1)
+ *       C     = eta_max * (sqrt(mhat) + eps)
+ *       Graw  = delta / C
+ *       G     = 1 + Graw   (GA_MODE_GA)   or   max(1, Graw)   (GA_MODE_GA_HINGE)
+ *       ghat  = g / G
+ *   GA_MODE_SA (Alg. 5):      ghat = g / tau_k
+ *   otherwise:                ghat = g
+ *   v     = gamma * v + ghat                                   (Alg. 2 / 4 / 5)
+ *   theta = theta - lr * v,   lr = eta_k, or eta_k / tau_k for GA_MODE_SA_STEP (Alg. 3)
+ *   m     = beta * m + (1 - beta) * (v * v)                    (Alg. 14; GA modes, or gap tracking on)
+ *   snap_i = theta                                             (Alg. 4)
+ * then on the host iter[i] = k.  The scalars 1 - beta^(k-1) are evaluated in
+ * double and rounded once to float.
+ */
+#ifndef GA_H
+#define GA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ga_ctx ga_ctx;
+
+enum ga_mode {
+    GA_MODE_ASGD = 0,     /* Alg. 2: no penalty */
+    GA_MODE_SA = 1,       /* Alg. 5: gradient divided by the delay */
+    GA_MODE_SA_STEP = 2,  /* Alg. 3: step size divided by the delay */
+    GA_MODE_GA = 3,       /* Alg. 4: gradient divided by G = |diff|/C + 1 */
+    GA_MODE_GA_HINGE = 4  /* variant: gradient divided by max(1, |diff|/C) */
+};
+
+enum ga_dtype { GA_F32 = 0, GA_BF16 = 1 };
+
+enum ga_status {
+    GA_OK = 0,
+    GA_ERR_ARG = -1,     /* null pointer, zero size, value out of range, unknown enum */
+    GA_ERR_WORKER = -2,  /* worker id >= n_workers */
+    GA_ERR_ALIGN = -3,   /* workspace not 256-byte aligned or too small */
+    GA_ERR_STATE = -4,   /* call not valid in the context's current state */
+    GA_ERR_HIP = -5      /* a HIP runtime call failed */
+};
+
+/* Iteration-time models of the arrival-schedule simulator. */
+enum ga_time_dist {
+    GA_DIST_EXP = 0,        /* Exp(mean 1) per iteration */
+    GA_DIST_LOGNORMAL = 1,  /* exp(sigma z) per iteration, z ~ N(0,1) */
+    GA_DIST_HETERO = 2      /* worker mean exp(sigma z_w), times Exp(1) per iteration */
+};
+
+enum ga_source_kind { GA_SRC_QUADRATIC_NOISE = 0, GA_SRC_BUFFERS = 1 };
+enum ga_pick { GA_PICK_BY_WORKER = 0, GA_PICK_BY_ARRIVAL = 1 };
+
+/*
+ * Where ga_run_schedule takes the gradient of each arrival from.  The source
+ * stands in for the workers of Alg. 1.
+ *
+ * GA_SRC_QUADRATIC_NOISE: the worker holds theta_w = snap_i and returns, per
+ *   parameter j at master step k,
+ *       g = a[j] * (theta_w[j] - theta_star[j]) + sigma * z(seed, k, j)
+ *   with z the counter-based standard normal documented at ga_noise_fill.
+ *   dev_a and dev_theta_star are device arrays of N floats, 16-byte aligned.
+ *   persistent != 0: all arrivals are replayed inside one kernel per chunk of
+ *   the schedule (no per-arrival launch); persistent == 0: one gradient launch
+ *   and one update launch per arrival, through dev_scratch_g (N floats,
+ *   16-byte aligned device buffer, required in that case only).
+ *
+ * GA_SRC_BUFFERS: precomputed gradients.  host_dev_bufs is a HOST array of
+ *   n_bufs DEVICE pointers, each to N values of `dtype`.  Arrival k of worker i
+ *   uses buffer (i mod n_bufs) for GA_PICK_BY_WORKER, ((k-1) mod n_bufs) for
+ *   GA_PICK_BY_ARRIVAL.  One update launch per arrival.
+ */
+typedef struct ga_grad_source {
+    int kind; /* ga_source_kind */
+    /* GA_SRC_QUADRATIC_NOISE */
+    const float* dev_a;
+    const float* dev_theta_star;
+    uint64_t seed;
+    float sigma;
+    int persistent;
+    float* dev_scratch_g;
+    /* GA_SRC_BUFFERS */
+    const void* const* host_dev_bufs;
+    uint32_t n_bufs;
+    int dtype; /* ga_dtype */
+    int pick;  /* ga_pick */
+} ga_grad_source;
+
+/* Gap statistics of one worker against the current master state (App. C.8
+ * plots the average Gap).  Graw = |theta - snap_i| / C; the paper's Gap is
+ * Graw + 1.  Non-finite Graw values are counted and left out of the mean. */
+typedef struct ga_diag {
+    double mean_graw;      /* sum of finite Graw / N */
+    double frac_gt1;       /* #{Graw > 1} / N: parameters the hinge form penalises */
+    double frac_gt0;       /* #{Graw > 0} / N: parameters the paper's form penalises */
+    uint64_t n_nonfinite;  /* #{Graw is inf or nan} */
+} ga_diag;
+
+/* One row of the per-arrival table that the host bookkeeping produces and the
+ * kernels consume (Alg. 3 / Alg. 5 bookkeeping; Alg. 14 bias correction). */
+typedef struct ga_arrival {
+    uint32_t worker;  /* i */
+    float tau;        /* (float) tau_k */
+    float lr;         /* eta_k, or eta_k / tau_k for GA_MODE_SA_STEP */
+    float bc_prev;    /* (float)(1 - beta^(k-1)); 0 when k = 1 */
+} ga_arrival;
+
+/* ------------------------------------------------------------------ host only
+ * These three touch no device and need no context. */
+
+/* Arrival order of n_workers simulated workers (App. C.1: FIFO master).  All
+ * workers start at time 0; worker w's n-th iteration takes a time drawn from
+ * `dist` by a counter-based generator keyed (seed, w, n), in double; arrivals
+ * are served in order of finish time, ties to the lowest id; the update takes
+ * no time.  Writes T worker ids to host_schedule.  sigma is used by
+ * GA_DIST_LOGNORMAL and GA_DIST_HETERO only. */
+int ga_simulate_schedule(uint32_t n_workers, uint64_t T, int dist, double sigma, uint64_t seed,
+                         uint32_t* host_schedule);
+
+/* Delay bookkeeping of Alg. 3 / Alg. 5 for T arrivals starting after master
+ * step k0: tau_k = k - iter[i]; iter[i] = k.  host_iter (n_workers entries) is
+ * read and updated; host_tau receives T delays. */
+int ga_delays_from_schedule(uint32_t n_workers, uint64_t T, const uint32_t* host_schedule, uint64_t k0,
+                            uint64_t* host_iter, uint64_t* host_tau);
+
+/* The table rows for the same T arrivals: delays as above plus the step size
+ * and the Alg. 14 bias correction of each step.  host_iter is read and
+ * updated.  host_rows receives T rows. */
+int ga_plan_arrivals(uint32_t n_workers, uint64_t T, const uint32_t* host_schedule, uint64_t k0,
+                     uint64_t* host_iter, int mode, float eta_k, float beta, ga_arrival* host_rows);
+
+/* ------------------------------------------------------------------ context */
+
+/* Bytes of device workspace a context needs (state, W snapshots, arrival
+ * table, reduction partials).  0 if N or n_workers is 0. */
+size_t ga_workspace_bytes(uint64_t N, uint32_t n_workers);
+
+/* Create a master (Alg. 2-5 initial state): theta = v = m = 0, every snapshot
+ * = theta, iter = [0]*W, k = 0, eta_k = eta_max = eta, beta = 0.999,
+ * eps = 1e-8 (App. C.6), gap tracking off.  dev_workspace: 256-byte aligned,
+ * at least ga_workspace_bytes(N, n_workers).  hip_stream: a hipStream_t (may
+ * be null for the default stream).  Enqueues the fills of the state.
+ * Errors: GA_ERR_ARG for N = 0, n_workers = 0, eta <= 0 or non-finite,
+ * |gamma| >= 1 (negative gamma is legal, App. C.9), unknown mode, null out;
+ * GA_ERR_ALIGN for a misaligned or short workspace. */
+int ga_create(ga_ctx** out, uint64_t N, uint32_t n_workers, float eta, float gamma, int mode,
+              void* dev_workspace, size_t workspace_bytes, void* hip_stream);
+
+void ga_destroy(ga_ctx* ctx);
+
+/* Alg. 14 constants.  beta in [0,1), eps > 0 (eps = 0 would make C = 0 at the
+ * first arrival).  Only before the first arrival (GA_ERR_STATE afterwards). */
+int ga_set_beta_eps(ga_ctx* ctx, float beta, float eps);
+/* eta_max of Alg. 14 (> 0).  Only before the first arrival. */
+int ga_set_eta_max(ga_ctx* ctx, float eta_max);
+/* eta_k for the following arrivals (> 0); eta_max is unchanged. */
+int ga_set_lr(ga_ctx* ctx, float eta_k);
+/* Maintain m in the non-GA modes too, so that ga_diagnostics can report the
+ * Gap under SA / ASGD (costs 8 bytes per parameter per arrival).  Only before
+ * the first arrival. */
+int ga_set_track_gap(ga_ctx* ctx, int on);
+/* theta_0: copy N floats from dev_theta0 into theta and into every snapshot
+ * (App. C.1: theta^i = theta_0).  Only before the first arrival. */
+int ga_set_theta(ga_ctx* ctx, const float* dev_theta0);
+
+/* One arrival: worker_id delivers dev_grad (N values of grad_dtype).  Host:
+ * k += 1, tau = k - iter[i]; device: one fused launch doing the arithmetic in
+ * the header comment for all N parameters; host: iter[i] = k, tau recorded.
+ * dev_grad needs only the alignment of its element type (a pointer that is
+ * not 16-byte aligned takes a slower path).  In the non-GA modes the snapshot
+ * is written (and m maintained) only when gap tracking is on: nothing reads
+ * them otherwise, and the arrival then moves 20 instead of 36 bytes per
+ * parameter. */
+int ga_apply(ga_ctx* ctx, uint32_t worker_id, const void* dev_grad, int grad_dtype);
+
+/* T arrivals in the order of host_schedule (worker ids), gradients from src. */
+int ga_run_schedule(ga_ctx* ctx, const uint32_t* host_schedule, uint64_t T, const ga_grad_source* src);
+
+/* Write the quadratic-plus-noise gradient that worker_id would deliver at the
+ * next arrival (step k+1) to dev_g_out (N floats, 16-byte aligned).  State is
+ * not changed.  src->kind must be GA_SRC_QUADRATIC_NOISE. */
+int ga_quadratic_gradient(ga_ctx* ctx, uint32_t worker_id, const ga_grad_source* src, float* dev_g_out);
+
+/* Gap statistics of worker_id as if its gradient arrived next (C from the
+ * current m and 1 - beta^k).  Needs m: a GA mode or gap tracking on, else
+ * GA_ERR_STATE.  Waits for the stream; host_out is written on return. */
+int ga_diagnostics(ga_ctx* ctx, uint32_t worker_id, ga_diag* host_out);
+
+/* Copies of the state, N floats each, to 4-byte aligned device buffers. */
+int ga_get_theta(ga_ctx* ctx, float* dev_dst);
+int ga_get_v(ga_ctx* ctx, float* dev_dst);
+int ga_get_m(ga_ctx* ctx, float* dev_dst);
+int ga_get_snapshot(ga_ctx* ctx, uint32_t worker_id, float* dev_dst);
+/* Overwrite v, m or one snapshot from N device floats (tests and checkpoint
+ * restore; legal at any step). */
+int ga_put_theta(ga_ctx* ctx, const float* dev_src);
+int ga_put_v(ga_ctx* ctx, const float* dev_src);
+int ga_put_m(ga_ctx* ctx, const float* dev_src);
+int ga_put_snapshot(ga_ctx* ctx, uint32_t worker_id, const float* dev_src);
+
+/* Host bookkeeping: current step k; iter[W]; the delays of all arrivals so far
+ * (at most max_n are written, the total count goes to n_out). */
+uint64_t ga_step(const ga_ctx* ctx);
+int ga_get_iter(const ga_ctx* ctx, uint64_t* host_iter);
+int ga_get_delays(const ga_ctx* ctx, uint64_t* host_out, uint64_t max_n, uint64_t* n_out);
+/* Restore k and iter[W] (checkpoint resume; the device arrays are restored
+ * with the ga_put_* calls).  Every iter[i] must be <= k. */
+int ga_set_bookkeeping(ga_ctx* ctx, uint64_t k, const uint64_t* host_iter);
+
+/* Fill dev_out[0..n) with z(seed, k, j0 + j), the standard-normal noise of the
+ * quadratic source.  One Philox4x32-10 block (Salmon et al., SC'11) with
+ * counter (floor(j/4), k) and key seed serves parameters 4q..4q+3: words
+ * (x0, x1) feed the Box-Muller pair of lanes 0,1 and (x2, x3) that of lanes
+ * 2,3; the even lane takes the cosine.  The transform uses float operations
+ * only (atanh series for the logarithm, Taylor series for sine and cosine), so
+ * it is reproducible bit for bit.  hip_stream as in ga_create. */
+int ga_noise_fill(uint64_t seed, uint64_t k, uint64_t j0, uint64_t n, float* dev_out, void* hip_stream);
+
+/* Message of the last error on this context ("" if none).  ctx may be null:
+ * then the message of the last failed ga_create on this thread. */
+const char* ga_last_error(const ga_ctx* ctx);
+
+/* Library version, "major.minor". */
+const char* ga_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GA_H */

@@ -1,0 +1,541 @@
+// Host side of libga: the C ABI of include/ga.h, the integer bookkeeping of
+// the master (step counter, iter[], delays: Alg. 3 / Alg. 5), the per-arrival
+// scalars (step size, Alg. 14 bias correction) and the arrival-schedule
+// simulator.  Device work is delegated to the launchers in ga_kernels.hip.
+
+#include <hip/hip_runtime_api.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "ga_internal.h"
+
+struct ga_ctx {
+    uint64_t N = 0;
+    uint32_t W = 0;
+    int mode = GA_MODE_GA;
+    float eta_max = 0.f, lr = 0.f, gamma = 0.f, beta = 0.999f, eps = 1e-8f;
+    bool track_gap = false;
+    hipStream_t stream = nullptr;
+    ga::StatePtrs st{};
+    ga_arrival* dev_table = nullptr;
+    ga::DiagPartial* dev_partials = nullptr;
+    uint64_t k = 0;
+    std::vector<uint64_t> iter;
+    std::vector<uint64_t> delays;
+    std::vector<ga_arrival> rows;   // staging for one chunk of the table
+    std::string err;
+};
+
+namespace {
+
+thread_local std::string g_create_error;
+
+int fail(ga_ctx* ctx, int code, const char* fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    if (ctx) ctx->err = buf; else g_create_error = buf;
+    return code;
+}
+
+int hip_fail(ga_ctx* ctx, hipError_t e, const char* what) {
+    return fail(ctx, GA_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+bool is_gap_mode(int mode) { return mode == GA_MODE_GA || mode == GA_MODE_GA_HINGE; }
+bool valid_mode(int mode) { return mode >= GA_MODE_ASGD && mode <= GA_MODE_GA_HINGE; }
+
+uint64_t round_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
+
+struct Layout {
+    uint64_t Np;
+    size_t off_theta, off_v, off_m, off_snaps, off_table, off_partials, total;
+};
+
+Layout layout_for(uint64_t N, uint32_t W) {
+    Layout L;
+    L.Np = round_up(N, 64);                  // every array starts 256-byte aligned
+    const size_t row = (size_t)L.Np * sizeof(float);
+    L.off_theta = 0;
+    L.off_v = row;
+    L.off_m = 2 * row;
+    L.off_snaps = 3 * row;
+    L.off_table = L.off_snaps + (size_t)W * row;
+    L.off_partials = L.off_table + round_up((uint64_t)ga::kTableCap * sizeof(ga_arrival), 256);
+    L.total = L.off_partials + round_up((uint64_t)(ga::kDiagMaxBlocks + 1) * sizeof(ga::DiagPartial), 256);
+    return L;
+}
+
+// (float)(1 - beta^k), the power and the difference in double.
+float bias_correction(float beta, uint64_t k) {
+    return (float)(1.0 - std::pow((double)beta, (double)k));
+}
+
+// ----------------------------------------------------------- schedule draws
+// Philox4x32-10 (Salmon et al., SC'11), host copy used for iteration times.
+struct Block4 { uint32_t w[4]; };
+
+Block4 philox_block(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint64_t key) {
+    uint32_t k0 = (uint32_t)key, k1 = (uint32_t)(key >> 32);
+    for (int r = 0; r < 10; ++r) {
+        const uint64_t a = 0xD2511F53ull * c0;
+        const uint64_t b = 0xCD9E8D57ull * c2;
+        const uint32_t t0 = (uint32_t)(b >> 32) ^ c1 ^ k0;
+        const uint32_t t2 = (uint32_t)(a >> 32) ^ c3 ^ k1;
+        c1 = (uint32_t)b;
+        c3 = (uint32_t)a;
+        c0 = t0;
+        c2 = t2;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    return Block4{{c0, c1, c2, c3}};
+}
+
+double unit53(uint32_t lo, uint32_t hi) {   // 53 random bits -> [0, 1)
+    return (double)((((uint64_t)hi << 32) | lo) >> 11) * 0x1.0p-53;
+}
+
+double normal_of(const Block4& b) {          // Box-Muller, double
+    const double radius = std::sqrt(-2.0 * std::log1p(-unit53(b.w[0], b.w[1])));
+    return radius * std::cos(6.283185307179586476925286766559 * unit53(b.w[2], b.w[3]));
+}
+
+constexpr uint32_t kTagTime = 0x54494D45u;   // counter word 3: per-iteration draw
+constexpr uint32_t kTagMean = 0x4D45414Eu;   // counter word 3: per-worker draw
+
+class TimeModel {
+  public:
+    TimeModel(int dist, double sigma, uint64_t seed, uint32_t W) : dist_(dist), sigma_(sigma), seed_(seed) {
+        if (dist == GA_DIST_HETERO) {
+            mean_.resize(W);
+            for (uint32_t w = 0; w < W; ++w) mean_[w] = std::exp(sigma * normal_of(philox_block(w, 0, 0, kTagMean, seed)));
+        }
+    }
+    double draw(uint32_t w, uint64_t n) const {
+        const Block4 b = philox_block((uint32_t)n, (uint32_t)(n >> 32), w, kTagTime, seed_);
+        if (dist_ == GA_DIST_LOGNORMAL) return std::exp(sigma_ * normal_of(b));
+        const double e = -std::log1p(-unit53(b.w[0], b.w[1]));
+        return dist_ == GA_DIST_HETERO ? mean_[w] * e : e;
+    }
+
+  private:
+    int dist_;
+    double sigma_;
+    uint64_t seed_;
+    std::vector<double> mean_;
+};
+
+// ----------------------------------------------------------- per-arrival scalars
+ga_arrival make_row(uint32_t worker, uint64_t k, uint64_t tau, int mode, float eta_k, float beta) {
+    ga_arrival r;
+    r.worker = worker;
+    r.tau = (float)tau;
+    r.lr = (mode == GA_MODE_SA_STEP) ? eta_k / r.tau : eta_k;
+    r.bc_prev = (k == 1) ? 0.0f : bias_correction(beta, k - 1);
+    return r;
+}
+
+// Rows (and integer delays) of T arrivals after step k0.  Arguments are already validated.
+void plan(uint64_t T, const uint32_t* schedule, uint64_t k0, uint64_t* iter, int mode, float eta_k, float beta,
+          ga_arrival* rows, uint64_t* taus) {
+    for (uint64_t a = 0; a < T; ++a) {
+        const uint64_t k = k0 + a + 1;
+        const uint32_t w = schedule[a];
+        const uint64_t tau = k - iter[w];
+        rows[a] = make_row(w, k, tau, mode, eta_k, beta);
+        if (taus) taus[a] = tau;
+        iter[w] = k;
+    }
+}
+
+ga::StepConst step_const(const ga_ctx* c, const ga_arrival& r, uint64_t k) {
+    ga::StepConst s;
+    s.gamma = c->gamma;
+    s.lr = r.lr;
+    s.tau = r.tau;
+    s.bc_prev = r.bc_prev;
+    s.eta_max = c->eta_max;
+    s.eps = c->eps;
+    s.beta = c->beta;
+    s.one_minus_beta = 1.0f - c->beta;
+    s.first = (k == 1);
+    return s;
+}
+
+ga::RunConst run_const(const ga_ctx* c, const ga_grad_source* src) {
+    ga::RunConst r;
+    r.gamma = c->gamma;
+    r.eta_max = c->eta_max;
+    r.eps = c->eps;
+    r.beta = c->beta;
+    r.one_minus_beta = 1.0f - c->beta;
+    r.sigma = src->sigma;
+    r.seed_lo = (uint32_t)src->seed;
+    r.seed_hi = (uint32_t)(src->seed >> 32);
+    return r;
+}
+
+bool keeps_m(const ga_ctx* c) { return is_gap_mode(c->mode) || c->track_gap; }
+
+int check_quadratic_source(ga_ctx* ctx, const ga_grad_source* src) {
+    if (!src->dev_a || !src->dev_theta_star) return fail(ctx, GA_ERR_ARG, "quadratic source: dev_a / dev_theta_star is null");
+    if (((uintptr_t)src->dev_a & 15u) || ((uintptr_t)src->dev_theta_star & 15u))
+        return fail(ctx, GA_ERR_ALIGN, "quadratic source: dev_a / dev_theta_star must be 16-byte aligned");
+    if (!std::isfinite(src->sigma)) return fail(ctx, GA_ERR_ARG, "quadratic source: sigma is not finite");
+    return GA_OK;
+}
+
+// One arrival through the fused kernel; the bookkeeping is committed only if the launch succeeded.
+int apply_one(ga_ctx* ctx, uint32_t worker, const void* dev_grad, int dtype, bool write_snap) {
+    const uint64_t k = ctx->k + 1;
+    const uint64_t tau = k - ctx->iter[worker];
+    const ga_arrival row = make_row(worker, k, tau, ctx->mode, ctx->lr, ctx->beta);
+    const hipError_t e = ga::launch_apply(ctx->st, ctx->N, worker, dev_grad, dtype, ctx->mode, keeps_m(ctx),
+                                          write_snap, step_const(ctx, row, k), ctx->stream);
+    if (e != hipSuccess) return hip_fail(ctx, e, "apply launch");
+    ctx->k = k;
+    ctx->iter[worker] = k;
+    ctx->delays.push_back(tau);
+    return GA_OK;
+}
+
+int copy_out(ga_ctx* ctx, float* dst, const float* src) {
+    if (!ctx) return GA_ERR_ARG;
+    if (!dst) return fail(ctx, GA_ERR_ARG, "destination is null");
+    const hipError_t e = hipMemcpyAsync(dst, src, ctx->N * sizeof(float), hipMemcpyDeviceToDevice, ctx->stream);
+    return e == hipSuccess ? GA_OK : hip_fail(ctx, e, "copy");
+}
+
+int copy_in(ga_ctx* ctx, float* dst, const float* src) {
+    if (!ctx) return GA_ERR_ARG;
+    if (!src) return fail(ctx, GA_ERR_ARG, "source is null");
+    const hipError_t e = hipMemcpyAsync(dst, src, ctx->N * sizeof(float), hipMemcpyDeviceToDevice, ctx->stream);
+    return e == hipSuccess ? GA_OK : hip_fail(ctx, e, "copy");
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* ga_version(void) { return "0.1"; }
+
+const char* ga_last_error(const ga_ctx* ctx) { return ctx ? ctx->err.c_str() : g_create_error.c_str(); }
+
+// ------------------------------------------------------------------ host only
+int ga_simulate_schedule(uint32_t n_workers, uint64_t T, int dist, double sigma, uint64_t seed,
+                         uint32_t* host_schedule) {
+    if (n_workers == 0 || (T > 0 && !host_schedule)) return fail(nullptr, GA_ERR_ARG, "simulate_schedule: bad argument");
+    if (dist < GA_DIST_EXP || dist > GA_DIST_HETERO) return fail(nullptr, GA_ERR_ARG, "simulate_schedule: unknown distribution");
+    if ((dist != GA_DIST_EXP) && !(sigma >= 0.0 && std::isfinite(sigma)))
+        return fail(nullptr, GA_ERR_ARG, "simulate_schedule: sigma must be finite and >= 0");
+    const TimeModel model(dist, sigma, seed, n_workers);
+    std::vector<double> finish(n_workers);
+    std::vector<uint64_t> done(n_workers, 0);
+    for (uint32_t w = 0; w < n_workers; ++w) finish[w] = model.draw(w, 0);
+    for (uint64_t a = 0; a < T; ++a) {
+        uint32_t first = 0;                     // earliest finish; strict '<' keeps the lowest id on ties
+        for (uint32_t w = 1; w < n_workers; ++w)
+            if (finish[w] < finish[first]) first = w;
+        host_schedule[a] = first;
+        done[first] += 1;
+        finish[first] = finish[first] + model.draw(first, done[first]);
+    }
+    return GA_OK;
+}
+
+int ga_delays_from_schedule(uint32_t n_workers, uint64_t T, const uint32_t* host_schedule, uint64_t k0,
+                            uint64_t* host_iter, uint64_t* host_tau) {
+    if (n_workers == 0 || !host_iter || (T > 0 && (!host_schedule || !host_tau)))
+        return fail(nullptr, GA_ERR_ARG, "delays_from_schedule: bad argument");
+    for (uint64_t a = 0; a < T; ++a)
+        if (host_schedule[a] >= n_workers) return fail(nullptr, GA_ERR_WORKER, "schedule[%llu] = %u >= n_workers", (unsigned long long)a, host_schedule[a]);
+    for (uint32_t w = 0; w < n_workers; ++w)
+        if (host_iter[w] > k0) return fail(nullptr, GA_ERR_ARG, "iter[%u] is ahead of k0", w);
+    for (uint64_t a = 0; a < T; ++a) {
+        const uint64_t k = k0 + a + 1;
+        uint64_t& last = host_iter[host_schedule[a]];
+        host_tau[a] = k - last;
+        last = k;
+    }
+    return GA_OK;
+}
+
+int ga_plan_arrivals(uint32_t n_workers, uint64_t T, const uint32_t* host_schedule, uint64_t k0, uint64_t* host_iter,
+                     int mode, float eta_k, float beta, ga_arrival* host_rows) {
+    if (n_workers == 0 || !host_iter || (T > 0 && (!host_schedule || !host_rows)) || !valid_mode(mode))
+        return fail(nullptr, GA_ERR_ARG, "plan_arrivals: bad argument");
+    if (!(eta_k > 0.f) || !std::isfinite(eta_k) || !(beta >= 0.f && beta < 1.f))
+        return fail(nullptr, GA_ERR_ARG, "plan_arrivals: eta_k must be > 0 and beta in [0,1)");
+    for (uint64_t a = 0; a < T; ++a)
+        if (host_schedule[a] >= n_workers) return fail(nullptr, GA_ERR_WORKER, "schedule[%llu] = %u >= n_workers", (unsigned long long)a, host_schedule[a]);
+    for (uint32_t w = 0; w < n_workers; ++w)
+        if (host_iter[w] > k0) return fail(nullptr, GA_ERR_ARG, "iter[%u] is ahead of k0", w);
+    plan(T, host_schedule, k0, host_iter, mode, eta_k, beta, host_rows, nullptr);
+    return GA_OK;
+}
+
+// ------------------------------------------------------------------ context
+size_t ga_workspace_bytes(uint64_t N, uint32_t n_workers) {
+    if (N == 0 || n_workers == 0) return 0;
+    return layout_for(N, n_workers).total;
+}
+
+int ga_create(ga_ctx** out, uint64_t N, uint32_t n_workers, float eta, float gamma, int mode, void* dev_workspace,
+              size_t workspace_bytes, void* hip_stream) {
+    if (!out) return fail(nullptr, GA_ERR_ARG, "create: out is null");
+    *out = nullptr;
+    if (N == 0 || n_workers == 0) return fail(nullptr, GA_ERR_ARG, "create: N and n_workers must be positive");
+    if (N > (1ull << 40)) return fail(nullptr, GA_ERR_ARG, "create: N too large");
+    if (!(eta > 0.f) || !std::isfinite(eta)) return fail(nullptr, GA_ERR_ARG, "create: eta must be finite and > 0");
+    if (!(std::fabs(gamma) < 1.f)) return fail(nullptr, GA_ERR_ARG, "create: |gamma| must be < 1");
+    if (!valid_mode(mode)) return fail(nullptr, GA_ERR_ARG, "create: unknown mode %d", mode);
+    if (!dev_workspace) return fail(nullptr, GA_ERR_ARG, "create: workspace is null");
+    const Layout L = layout_for(N, n_workers);
+    if (((uintptr_t)dev_workspace & 255u) != 0) return fail(nullptr, GA_ERR_ALIGN, "create: workspace must be 256-byte aligned");
+    if (workspace_bytes < L.total)
+        return fail(nullptr, GA_ERR_ALIGN, "create: workspace has %zu bytes, %zu needed", workspace_bytes, L.total);
+
+    ga_ctx* c = new (std::nothrow) ga_ctx;
+    if (!c) return fail(nullptr, GA_ERR_ARG, "create: out of host memory");
+    c->N = N;
+    c->W = n_workers;
+    c->mode = mode;
+    c->eta_max = c->lr = eta;
+    c->gamma = gamma;
+    c->stream = static_cast<hipStream_t>(hip_stream);
+    char* base = static_cast<char*>(dev_workspace);
+    c->st.theta = reinterpret_cast<float*>(base + L.off_theta);
+    c->st.v = reinterpret_cast<float*>(base + L.off_v);
+    c->st.m = reinterpret_cast<float*>(base + L.off_m);
+    c->st.snaps = reinterpret_cast<float*>(base + L.off_snaps);
+    c->st.stride = L.Np;
+    c->dev_table = reinterpret_cast<ga_arrival*>(base + L.off_table);
+    c->dev_partials = reinterpret_cast<ga::DiagPartial*>(base + L.off_partials);
+    c->iter.assign(n_workers, 0);
+    c->rows.reserve(ga::kTableCap);
+
+    // theta, v, m and all snapshots are contiguous: one fill
+    const hipError_t e = ga::launch_fill(c->st.theta, (3 + (uint64_t)n_workers) * L.Np, 0.0f, c->stream);
+    if (e != hipSuccess) {
+        const int rc = hip_fail(nullptr, e, "create: initial fill");
+        delete c;
+        return rc;
+    }
+    *out = c;
+    return GA_OK;
+}
+
+void ga_destroy(ga_ctx* ctx) { delete ctx; }
+
+int ga_set_beta_eps(ga_ctx* ctx, float beta, float eps) {
+    if (!ctx) return GA_ERR_ARG;
+    if (ctx->k != 0) return fail(ctx, GA_ERR_STATE, "set_beta_eps: only before the first arrival");
+    if (!(beta >= 0.f && beta < 1.f)) return fail(ctx, GA_ERR_ARG, "set_beta_eps: beta must be in [0,1)");
+    if (!(eps > 0.f) || !std::isfinite(eps)) return fail(ctx, GA_ERR_ARG, "set_beta_eps: eps must be finite and > 0");
+    ctx->beta = beta;
+    ctx->eps = eps;
+    return GA_OK;
+}
+
+int ga_set_eta_max(ga_ctx* ctx, float eta_max) {
+    if (!ctx) return GA_ERR_ARG;
+    if (ctx->k != 0) return fail(ctx, GA_ERR_STATE, "set_eta_max: only before the first arrival");
+    if (!(eta_max > 0.f) || !std::isfinite(eta_max)) return fail(ctx, GA_ERR_ARG, "set_eta_max: must be finite and > 0");
+    ctx->eta_max = eta_max;
+    return GA_OK;
+}
+
+int ga_set_lr(ga_ctx* ctx, float eta_k) {
+    if (!ctx) return GA_ERR_ARG;
+    if (!(eta_k > 0.f) || !std::isfinite(eta_k)) return fail(ctx, GA_ERR_ARG, "set_lr: must be finite and > 0");
+    ctx->lr = eta_k;
+    return GA_OK;
+}
+
+int ga_set_track_gap(ga_ctx* ctx, int on) {
+    if (!ctx) return GA_ERR_ARG;
+    if (ctx->k != 0) return fail(ctx, GA_ERR_STATE, "set_track_gap: only before the first arrival");
+    ctx->track_gap = (on != 0);
+    return GA_OK;
+}
+
+int ga_set_theta(ga_ctx* ctx, const float* dev_theta0) {
+    if (!ctx) return GA_ERR_ARG;
+    if (!dev_theta0) return fail(ctx, GA_ERR_ARG, "set_theta: source is null");
+    if (ctx->k != 0) return fail(ctx, GA_ERR_STATE, "set_theta: only before the first arrival");
+    hipError_t e = ga::launch_broadcast_rows(ctx->st.theta, ctx->st.stride, 1, dev_theta0, ctx->N, ctx->stream);
+    if (e == hipSuccess) e = ga::launch_broadcast_rows(ctx->st.snaps, ctx->st.stride, ctx->W, dev_theta0, ctx->N, ctx->stream);
+    return e == hipSuccess ? GA_OK : hip_fail(ctx, e, "set_theta");
+}
+
+int ga_apply(ga_ctx* ctx, uint32_t worker_id, const void* dev_grad, int grad_dtype) {
+    if (!ctx) return GA_ERR_ARG;
+    if (worker_id >= ctx->W) return fail(ctx, GA_ERR_WORKER, "apply: worker %u >= n_workers %u", worker_id, ctx->W);
+    if (!dev_grad) return fail(ctx, GA_ERR_ARG, "apply: gradient is null");
+    if (grad_dtype != GA_F32 && grad_dtype != GA_BF16) return fail(ctx, GA_ERR_ARG, "apply: unknown gradient dtype %d", grad_dtype);
+    if (grad_dtype == GA_F32 && ((uintptr_t)dev_grad & 3u)) return fail(ctx, GA_ERR_ALIGN, "apply: float gradient must be 4-byte aligned");
+    if (grad_dtype == GA_BF16 && ((uintptr_t)dev_grad & 1u)) return fail(ctx, GA_ERR_ALIGN, "apply: bfloat16 gradient must be 2-byte aligned");
+    return apply_one(ctx, worker_id, dev_grad, grad_dtype, is_gap_mode(ctx->mode) || ctx->track_gap);
+}
+
+int ga_run_schedule(ga_ctx* ctx, const uint32_t* host_schedule, uint64_t T, const ga_grad_source* src) {
+    if (!ctx) return GA_ERR_ARG;
+    if (!src || (T > 0 && !host_schedule)) return fail(ctx, GA_ERR_ARG, "run_schedule: null argument");
+    for (uint64_t a = 0; a < T; ++a)
+        if (host_schedule[a] >= ctx->W)
+            return fail(ctx, GA_ERR_WORKER, "run_schedule: schedule[%llu] = %u >= n_workers %u", (unsigned long long)a, host_schedule[a], ctx->W);
+
+    if (src->kind == GA_SRC_BUFFERS) {
+        if (!src->host_dev_bufs || src->n_bufs == 0) return fail(ctx, GA_ERR_ARG, "run_schedule: no gradient buffers");
+        if (src->dtype != GA_F32 && src->dtype != GA_BF16) return fail(ctx, GA_ERR_ARG, "run_schedule: unknown gradient dtype");
+        if (src->pick != GA_PICK_BY_WORKER && src->pick != GA_PICK_BY_ARRIVAL) return fail(ctx, GA_ERR_ARG, "run_schedule: unknown pick rule");
+        const uintptr_t need = src->dtype == GA_F32 ? 3u : 1u;
+        for (uint32_t b = 0; b < src->n_bufs; ++b)
+            if (!src->host_dev_bufs[b] || ((uintptr_t)src->host_dev_bufs[b] & need))
+                return fail(ctx, GA_ERR_ARG, "run_schedule: gradient buffer %u is null or misaligned", b);
+        const bool write_snap = is_gap_mode(ctx->mode) || ctx->track_gap;
+        for (uint64_t a = 0; a < T; ++a) {
+            const uint32_t w = host_schedule[a];
+            const uint64_t b = (src->pick == GA_PICK_BY_WORKER) ? w % src->n_bufs : ctx->k % src->n_bufs;
+            const int rc = apply_one(ctx, w, src->host_dev_bufs[b], src->dtype, write_snap);
+            if (rc != GA_OK) return rc;
+        }
+        return GA_OK;
+    }
+
+    if (src->kind != GA_SRC_QUADRATIC_NOISE) return fail(ctx, GA_ERR_ARG, "run_schedule: unknown source kind %d", src->kind);
+    int rc = check_quadratic_source(ctx, src);
+    if (rc != GA_OK) return rc;
+    const ga::RunConst rcst = run_const(ctx, src);
+
+    if (!src->persistent) {
+        // one gradient launch and one update launch per arrival; the worker reads its snapshot,
+        // so the snapshot is written in every mode
+        if (!src->dev_scratch_g || ((uintptr_t)src->dev_scratch_g & 15u))
+            return fail(ctx, GA_ERR_ARG, "run_schedule: dev_scratch_g is null or not 16-byte aligned");
+        for (uint64_t a = 0; a < T; ++a) {
+            const uint32_t w = host_schedule[a];
+            const hipError_t e = ga::launch_quadratic_gradient(ctx->st, ctx->N, w, src->dev_a, src->dev_theta_star,
+                                                               ctx->k + 1, rcst, src->dev_scratch_g, ctx->stream);
+            if (e != hipSuccess) return hip_fail(ctx, e, "gradient launch");
+            rc = apply_one(ctx, w, src->dev_scratch_g, GA_F32, true);
+            if (rc != GA_OK) return rc;
+        }
+        return GA_OK;
+    }
+
+    // persistent path: the table of a chunk is planned on the host, uploaded, and replayed by one launch
+    for (uint64_t done = 0; done < T;) {
+        const uint32_t n = (uint32_t)((T - done < ga::kTableCap) ? (T - done) : ga::kTableCap);
+        std::vector<uint64_t> iter_after = ctx->iter;
+        std::vector<uint64_t> taus(n);
+        ctx->rows.resize(n);
+        plan(n, host_schedule + done, ctx->k, iter_after.data(), ctx->mode, ctx->lr, ctx->beta, ctx->rows.data(),
+             taus.data());
+        // pageable source: the runtime has consumed ctx->rows when the call returns
+        hipError_t e = hipMemcpyAsync(ctx->dev_table, ctx->rows.data(), (size_t)n * sizeof(ga_arrival),
+                                      hipMemcpyHostToDevice, ctx->stream);
+        if (e != hipSuccess) return hip_fail(ctx, e, "table upload");
+        e = ga::launch_persistent(ctx->st, ctx->N, ctx->dev_table, n, ctx->k, src->dev_a, src->dev_theta_star, ctx->mode,
+                                  keeps_m(ctx), rcst, ctx->stream);
+        if (e != hipSuccess) return hip_fail(ctx, e, "persistent launch");
+        ctx->delays.insert(ctx->delays.end(), taus.begin(), taus.end());
+        ctx->iter.swap(iter_after);
+        ctx->k += n;
+        done += n;
+    }
+    return GA_OK;
+}
+
+int ga_quadratic_gradient(ga_ctx* ctx, uint32_t worker_id, const ga_grad_source* src, float* dev_g_out) {
+    if (!ctx) return GA_ERR_ARG;
+    if (!src || src->kind != GA_SRC_QUADRATIC_NOISE) return fail(ctx, GA_ERR_ARG, "quadratic_gradient: source must be GA_SRC_QUADRATIC_NOISE");
+    if (worker_id >= ctx->W) return fail(ctx, GA_ERR_WORKER, "quadratic_gradient: worker %u >= n_workers %u", worker_id, ctx->W);
+    if (!dev_g_out || ((uintptr_t)dev_g_out & 15u)) return fail(ctx, GA_ERR_ALIGN, "quadratic_gradient: output is null or not 16-byte aligned");
+    const int rc = check_quadratic_source(ctx, src);
+    if (rc != GA_OK) return rc;
+    const hipError_t e = ga::launch_quadratic_gradient(ctx->st, ctx->N, worker_id, src->dev_a, src->dev_theta_star,
+                                                       ctx->k + 1, run_const(ctx, src), dev_g_out, ctx->stream);
+    return e == hipSuccess ? GA_OK : hip_fail(ctx, e, "gradient launch");
+}
+
+int ga_diagnostics(ga_ctx* ctx, uint32_t worker_id, ga_diag* host_out) {
+    if (!ctx) return GA_ERR_ARG;
+    if (!host_out) return fail(ctx, GA_ERR_ARG, "diagnostics: output is null");
+    if (worker_id >= ctx->W) return fail(ctx, GA_ERR_WORKER, "diagnostics: worker %u >= n_workers %u", worker_id, ctx->W);
+    if (!keeps_m(ctx)) return fail(ctx, GA_ERR_STATE, "diagnostics: m is not maintained in this mode (enable gap tracking)");
+    const float bc = ctx->k == 0 ? 0.0f : bias_correction(ctx->beta, ctx->k);
+    hipError_t e = ga::launch_diagnostics(ctx->st, ctx->N, worker_id, bc, ctx->k == 0, ctx->eta_max, ctx->eps,
+                                          ctx->dev_partials, ctx->stream);
+    if (e != hipSuccess) return hip_fail(ctx, e, "diagnostics launch");
+    ga::DiagPartial total;
+    e = hipMemcpyAsync(&total, ctx->dev_partials + ga::kDiagMaxBlocks, sizeof total, hipMemcpyDeviceToHost, ctx->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+    if (e != hipSuccess) return hip_fail(ctx, e, "diagnostics readback");
+    const double n = (double)ctx->N;
+    host_out->mean_graw = total.sum_graw / n;
+    host_out->frac_gt1 = (double)total.n_gt1 / n;
+    host_out->frac_gt0 = (double)total.n_gt0 / n;
+    host_out->n_nonfinite = total.n_bad;
+    return GA_OK;
+}
+
+int ga_get_theta(ga_ctx* ctx, float* dev_dst) { return copy_out(ctx, dev_dst, ctx ? ctx->st.theta : nullptr); }
+int ga_get_v(ga_ctx* ctx, float* dev_dst) { return copy_out(ctx, dev_dst, ctx ? ctx->st.v : nullptr); }
+int ga_get_m(ga_ctx* ctx, float* dev_dst) { return copy_out(ctx, dev_dst, ctx ? ctx->st.m : nullptr); }
+int ga_get_snapshot(ga_ctx* ctx, uint32_t worker_id, float* dev_dst) {
+    if (!ctx) return GA_ERR_ARG;
+    if (worker_id >= ctx->W) return fail(ctx, GA_ERR_WORKER, "get_snapshot: worker %u >= n_workers %u", worker_id, ctx->W);
+    return copy_out(ctx, dev_dst, ctx->st.snaps + (uint64_t)worker_id * ctx->st.stride);
+}
+int ga_put_theta(ga_ctx* ctx, const float* dev_src) { return copy_in(ctx, ctx ? ctx->st.theta : nullptr, dev_src); }
+int ga_put_v(ga_ctx* ctx, const float* dev_src) { return copy_in(ctx, ctx ? ctx->st.v : nullptr, dev_src); }
+int ga_put_m(ga_ctx* ctx, const float* dev_src) { return copy_in(ctx, ctx ? ctx->st.m : nullptr, dev_src); }
+int ga_put_snapshot(ga_ctx* ctx, uint32_t worker_id, const float* dev_src) {
+    if (!ctx) return GA_ERR_ARG;
+    if (worker_id >= ctx->W) return fail(ctx, GA_ERR_WORKER, "put_snapshot: worker %u >= n_workers %u", worker_id, ctx->W);
+    return copy_in(ctx, ctx->st.snaps + (uint64_t)worker_id * ctx->st.stride, dev_src);
+}
+
+uint64_t ga_step(const ga_ctx* ctx) { return ctx ? ctx->k : 0; }
+
+int ga_get_iter(const ga_ctx* ctx, uint64_t* host_iter) {
+    if (!ctx || !host_iter) return GA_ERR_ARG;
+    std::memcpy(host_iter, ctx->iter.data(), ctx->W * sizeof(uint64_t));
+    return GA_OK;
+}
+
+int ga_get_delays(const ga_ctx* ctx, uint64_t* host_out, uint64_t max_n, uint64_t* n_out) {
+    if (!ctx || (max_n > 0 && !host_out)) return GA_ERR_ARG;
+    const uint64_t n = ctx->delays.size() < max_n ? ctx->delays.size() : max_n;
+    if (n) std::memcpy(host_out, ctx->delays.data(), n * sizeof(uint64_t));
+    if (n_out) *n_out = ctx->delays.size();
+    return GA_OK;
+}
+
+int ga_set_bookkeeping(ga_ctx* ctx, uint64_t k, const uint64_t* host_iter) {
+    if (!ctx) return GA_ERR_ARG;
+    if (!host_iter) return fail(ctx, GA_ERR_ARG, "set_bookkeeping: iter is null");
+    for (uint32_t w = 0; w < ctx->W; ++w)
+        if (host_iter[w] > k) return fail(ctx, GA_ERR_ARG, "set_bookkeeping: iter[%u] is ahead of k", w);
+    ctx->k = k;
+    ctx->iter.assign(host_iter, host_iter + ctx->W);
+    return GA_OK;
+}
+
+int ga_noise_fill(uint64_t seed, uint64_t k, uint64_t j0, uint64_t n, float* dev_out, void* hip_stream) {
+    if (n > 0 && !dev_out) return fail(nullptr, GA_ERR_ARG, "noise_fill: output is null");
+    const hipError_t e = ga::launch_noise_fill(seed, k, j0, n, dev_out, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? GA_OK : hip_fail(nullptr, e, "noise_fill launch");
+}
+
+}  // extern "C"

@@ -1,0 +1,81 @@
+// Internal interface between the host bookkeeping (ga_host.cpp) and the
+// gfx950 kernels (ga_kernels.hip).  Not part of the public ABI.
+#ifndef GA_INTERNAL_H
+#define GA_INTERNAL_H
+
+#include <hip/hip_runtime_api.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "ga.h"
+
+namespace ga {
+
+// Scalars that are uniform over one arrival.
+struct StepConst {
+    float gamma;           // momentum coefficient
+    float lr;              // eta_k, or eta_k / tau_k (Alg. 3)
+    float tau;             // (float) tau_k
+    float bc_prev;         // (float)(1 - beta^(k-1))
+    float eta_max;         // Alg. 14
+    float eps;             // Alg. 14
+    float beta;            // Alg. 14
+    float one_minus_beta;  // 1.0f - beta
+    int first;             // k == 1: m-hat is taken as 0
+};
+
+// Scalars that are uniform over a whole schedule chunk.
+struct RunConst {
+    float gamma, eta_max, eps, beta, one_minus_beta;
+    float sigma;       // noise scale of the quadratic source
+    uint32_t seed_lo, seed_hi;
+};
+
+// Reduction partial of the diagnostics kernel (one per block, then one total).
+struct DiagPartial {
+    double sum_graw;
+    unsigned long long n_gt1, n_gt0, n_bad;
+};
+
+constexpr uint32_t kTableCap = 8192;       // arrivals per persistent launch
+constexpr uint32_t kDiagMaxBlocks = 2048;  // partials in the workspace
+
+// State pointers inside the workspace.  snaps is W rows of `stride` floats.
+struct StatePtrs {
+    float* theta;
+    float* v;
+    float* m;
+    float* snaps;
+    uint64_t stride;  // floats between consecutive workers' snapshots (N rounded up to 64)
+};
+
+// Fused update of one arrival.  g: N values of grad_dtype.  In the GA modes m
+// and the snapshot are always maintained; elsewhere keep_m / write_snap decide.
+hipError_t launch_apply(const StatePtrs& st, uint64_t N, uint32_t worker, const void* g, int grad_dtype, int mode,
+                        bool keep_m, bool write_snap, const StepConst& c, hipStream_t stream);
+
+// T arrivals replayed inside one launch, gradients generated in the kernel.
+// table: device array of T rows; k0: master step before the first row.
+hipError_t launch_persistent(const StatePtrs& st, uint64_t N, const ga_arrival* dev_table, uint32_t T, uint64_t k0,
+                             const float* a, const float* theta_star, int mode, bool keep_m, const RunConst& rc,
+                             hipStream_t stream);
+
+// g_out = a * (snap_w - theta_star) + sigma * z(seed, k, j)
+hipError_t launch_quadratic_gradient(const StatePtrs& st, uint64_t N, uint32_t worker, const float* a,
+                                     const float* theta_star, uint64_t k, const RunConst& rc, float* g_out,
+                                     hipStream_t stream);
+
+// Gap statistics of one worker: per-block partials, then a fixed-order total in partials[kDiagMaxBlocks].
+hipError_t launch_diagnostics(const StatePtrs& st, uint64_t N, uint32_t worker, float bc, int first, float eta_max,
+                              float eps, DiagPartial* dev_partials, hipStream_t stream);
+
+hipError_t launch_noise_fill(uint64_t seed, uint64_t k, uint64_t j0, uint64_t n, float* out, hipStream_t stream);
+
+// dst[0..n) = value;  dst[r][0..n) = src[0..n) for r < rows (row stride in floats).
+hipError_t launch_fill(float* dst, uint64_t n, float value, hipStream_t stream);
+hipError_t launch_broadcast_rows(float* dst, uint64_t stride, uint32_t rows, const float* src, uint64_t n,
+                                 hipStream_t stream);
+
+}  // namespace ga
+
+#endif

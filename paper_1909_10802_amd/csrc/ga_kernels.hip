@@ -1,0 +1,627 @@
+// gfx950 kernels of the Gap-Aware master update.
+//
+//   apply_kernel        one arrival, gradient from HBM (Alg. 2-5 + Alg. 14 fused)
+//   persistent_kernel   a chunk of arrivals per launch; every thread owns four
+//                       parameters for the whole chunk and generates the
+//                       quadratic-plus-noise gradients itself
+//   quadratic_gradient_kernel / noise_fill_kernel   the gradient source alone
+//   diag_kernel + diag_final_kernel                  Gap statistics (App. C.8)
+//
+// The whole path is elementwise (Sec. 4.3: every parameter is penalised
+// independently), so it is bound by HBM traffic or plain vector ALU work; there
+// is no contraction and therefore no MFMA.
+//
+// Floating point: every operation is a separately rounded IEEE float
+// operation in the order given in include/ga.h.  This file must be compiled
+// with -ffp-contract=off; '/' and sqrtf are correctly rounded (hipcc default).
+
+#include <hip/hip_runtime.h>
+
+#include "ga_internal.h"
+
+#pragma clang fp contract(off)
+
+namespace ga {
+namespace {
+
+constexpr int kBlock = 256;
+
+// native 128-bit / 64-bit vectors (one dwordx4 / dwordx2 access each)
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+// ---------------------------------------------------------------------------
+// One parameter, one arrival.
+// ---------------------------------------------------------------------------
+template <int MODE, bool KEEP_M>
+__device__ __forceinline__ void update_one(float& th, float& v, float& m, float s, float g, const StepConst& c) {
+    float ghat = g;
+    if constexpr (MODE == GA_MODE_GA || MODE == GA_MODE_GA_HINGE) {
+        const float diff = th - s;
+        const float delta = fabsf(diff);
+        // k = 1: m-hat is taken as 0.  Uniform selects and a mask instead of a branch, so
+        // that the divisions of a thread's parameters stay in one straight-line block.
+        const float bc = c.first ? 1.0f : c.bc_prev;
+        const uint32_t keep = c.first ? 0u : 0xFFFFFFFFu;
+        const float mhat = __uint_as_float(__float_as_uint(m / bc) & keep);
+        const float root = sqrtf(mhat);
+        const float sum = root + c.eps;
+        const float C = c.eta_max * sum;
+        const float graw = delta / C;
+        const float G = (MODE == GA_MODE_GA) ? 1.0f + graw : fmaxf(1.0f, graw);
+        ghat = g / G;
+    } else if constexpr (MODE == GA_MODE_SA) {
+        ghat = g / c.tau;
+    }
+    const float gv = c.gamma * v;
+    const float vn = gv + ghat;
+    const float step = c.lr * vn;
+    const float tn = th - step;
+    v = vn;
+    th = tn;
+    if constexpr (KEEP_M) {
+        const float bm = c.beta * m;
+        const float vv = vn * vn;
+        const float add = c.one_minus_beta * vv;
+        m = bm + add;
+    }
+}
+
+// Four parameters; lanes >= n_valid (padding past N) are left untouched.
+template <int MODE, bool KEEP_M>
+__device__ __forceinline__ void update4(f32x4& th, f32x4& v, f32x4& m, const f32x4& s, const f32x4& g,
+                                        const StepConst& c, uint32_t n_valid = 4) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        if ((uint32_t)e < n_valid) {
+            float t1 = th[e], v1 = v[e], m1 = m[e];
+            update_one<MODE, KEEP_M>(t1, v1, m1, s[e], g[e], c);
+            th[e] = t1;
+            v[e] = v1;
+            m[e] = m1;
+        }
+    }
+}
+
+__device__ __forceinline__ float bf16_bits_to_float(uint32_t h) { return __uint_as_float(h << 16); }
+
+// Four gradient values of group q (elements 4q..4q+3).
+template <int DT, bool ALIGNED>
+__device__ __forceinline__ f32x4 load_g4(const void* __restrict__ g, uint64_t q) {
+    f32x4 r;
+    if constexpr (DT == GA_F32) {
+        const float* p = static_cast<const float*>(g) + 4 * q;
+        if constexpr (ALIGNED) {
+            r = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));
+        } else {
+            r.x = p[0]; r.y = p[1]; r.z = p[2]; r.w = p[3];
+        }
+    } else {
+        const uint16_t* p = static_cast<const uint16_t*>(g) + 4 * q;
+        if constexpr (ALIGNED) {
+            const u32x2 w = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(p));
+            r.x = bf16_bits_to_float(w.x & 0xFFFFu);
+            r.y = bf16_bits_to_float(w.x >> 16);
+            r.z = bf16_bits_to_float(w.y & 0xFFFFu);
+            r.w = bf16_bits_to_float(w.y >> 16);
+        } else {
+            r.x = bf16_bits_to_float(p[0]); r.y = bf16_bits_to_float(p[1]);
+            r.z = bf16_bits_to_float(p[2]); r.w = bf16_bits_to_float(p[3]);
+        }
+    }
+    return r;
+}
+
+template <int DT>
+__device__ __forceinline__ float load_g1(const void* __restrict__ g, uint64_t j) {
+    if constexpr (DT == GA_F32) return static_cast<const float*>(g)[j];
+    else return bf16_bits_to_float(static_cast<const uint16_t*>(g)[j]);
+}
+
+// ---------------------------------------------------------------------------
+// Fused update of one arrival.  Each thread owns U groups of four consecutive
+// parameters, 256 groups apart, so that every wavefront issues 1 KiB
+// contiguous 128-bit loads and stores per array.  All loads of a thread are
+// issued before the first dependent operation.
+// ---------------------------------------------------------------------------
+template <int MODE, int DT, bool KEEP_M, bool SNAP, bool ALIGNED, int U>
+__global__ __launch_bounds__(kBlock) void apply_kernel(float* __restrict__ theta, float* __restrict__ v,
+                                                       float* __restrict__ m, float* __restrict__ snap,
+                                                       const void* __restrict__ g, uint64_t N, StepConst c) {
+    constexpr bool GAP = (MODE == GA_MODE_GA || MODE == GA_MODE_GA_HINGE);
+    const uint64_t n4 = N >> 2;
+    const uint64_t base = (uint64_t)blockIdx.x * (kBlock * U) + threadIdx.x;
+
+    f32x4 th[U], vv[U], mm[U], ss[U], gg[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const uint64_t q = base + (uint64_t)u * kBlock;
+        mm[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+        ss[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (q < n4) {
+            th[u] = reinterpret_cast<const f32x4*>(theta)[q];
+            vv[u] = reinterpret_cast<const f32x4*>(v)[q];
+            if constexpr (KEEP_M) mm[u] = reinterpret_cast<const f32x4*>(m)[q];
+            if constexpr (GAP) ss[u] = reinterpret_cast<const f32x4*>(snap)[q];
+            gg[u] = load_g4<DT, ALIGNED>(g, q);
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const uint64_t q = base + (uint64_t)u * kBlock;
+        if (q < n4) {
+            update4<MODE, KEEP_M>(th[u], vv[u], mm[u], ss[u], gg[u], c);
+            reinterpret_cast<f32x4*>(theta)[q] = th[u];
+            reinterpret_cast<f32x4*>(v)[q] = vv[u];
+            if constexpr (KEEP_M) reinterpret_cast<f32x4*>(m)[q] = mm[u];
+            if constexpr (SNAP) __builtin_nontemporal_store(th[u], reinterpret_cast<f32x4*>(snap) + q);
+        }
+    }
+
+    // ragged tail: the last N % 4 parameters, one per thread of block 0
+    if (blockIdx.x == 0 && threadIdx.x < (N & 3)) {
+        const uint64_t j = 4 * n4 + threadIdx.x;
+        float t1 = theta[j], v1 = v[j], m1 = 0.0f, s1 = 0.0f;
+        if constexpr (KEEP_M) m1 = m[j];
+        if constexpr (GAP) s1 = snap[j];
+        update_one<MODE, KEEP_M>(t1, v1, m1, s1, load_g1<DT>(g, j), c);
+        theta[j] = t1;
+        v[j] = v1;
+        if constexpr (KEEP_M) m[j] = m1;
+        if constexpr (SNAP) snap[j] = t1;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Noise of the quadratic source: Philox4x32-10 (Salmon et al., SC'11) and a
+// Box-Muller transform in float operations only.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0,
+                                              uint32_t k1, uint32_t (&x)[4]) {
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint32_t hi0 = __umulhi(0xD2511F53u, c0);
+        const uint32_t lo0 = 0xD2511F53u * c0;
+        const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2);
+        const uint32_t lo1 = 0xCD9E8D57u * c2;
+        const uint32_t n0 = hi1 ^ c1 ^ k0;
+        const uint32_t n2 = hi0 ^ c3 ^ k1;
+        c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    x[0] = c0; x[1] = c1; x[2] = c2; x[3] = c3;
+}
+
+// (xa, xb) -> (r cos(angle), r sin(angle)); see ga_noise_fill in include/ga.h.
+__device__ __forceinline__ void box_muller_pair(uint32_t xa, uint32_t xb, float& zc, float& zs) {
+    // radius: ln(u1), u1 = M 2^-24 with M odd below 2^24, M = t 2^e, t in [sqrt(1/2), sqrt(2))
+    const uint32_t M = 2u * (xa >> 9) + 1u;
+    const uint32_t bits = __float_as_uint((float)M);           // exact conversion
+    int e = (int)(bits >> 23) - 126;
+    float t = __uint_as_float((bits & 0x007FFFFFu) | 0x3F000000u);   // [1/2, 1)
+    if (t < 0.70710678f) {
+        t = 2.0f * t;
+        e -= 1;
+    }
+    const float E = (float)(e - 24);
+    const float num = t - 1.0f;
+    const float den = t + 1.0f;
+    const float s = num / den;
+    const float s2 = s * s;
+    float P = fmaf(s2, 1.0f / 9.0f, 1.0f / 7.0f);
+    P = fmaf(s2, P, 1.0f / 5.0f);
+    P = fmaf(s2, P, 1.0f / 3.0f);
+    const float s3 = s * s2;
+    const float L = fmaf(s3, P, s);                             // atanh(s)
+    const float twoL = 2.0f * L;
+    const float lnu = fmaf(E, 0.693147180559945f, twoL);
+    const float r = sqrtf(-2.0f * lnu);
+
+    // angle = quad * pi/2 + phi, phi in (-pi/4, pi/4)
+    const uint32_t quad = xb >> 30;
+    const int hi = (int)(2u * ((xb >> 7) & 0x7FFFFFu) + 1u) - (1 << 23);
+    const float h = (float)hi * 5.9604644775390625e-8f;         // 2^-24
+    const float phi = h * 1.5707963267948966f;
+    const float p2 = phi * phi;
+    float S = fmaf(p2, 1.0f / 362880.0f, -1.0f / 5040.0f);
+    S = fmaf(p2, S, 1.0f / 120.0f);
+    S = fmaf(p2, S, -1.0f / 6.0f);
+    const float p3 = phi * p2;
+    const float sn = fmaf(p3, S, phi);
+    float Cc = fmaf(p2, -1.0f / 3628800.0f, 1.0f / 40320.0f);
+    Cc = fmaf(p2, Cc, -1.0f / 720.0f);
+    Cc = fmaf(p2, Cc, 1.0f / 24.0f);
+    Cc = fmaf(p2, Cc, -0.5f);
+    const float cs = fmaf(p2, Cc, 1.0f);
+
+    // quarter-turn rotation: quad 0 (c, s), 1 (-s, c), 2 (-c, -s), 3 (s, -c)
+    const float ca0 = (quad & 1u) ? sn : cs;
+    const float sa0 = (quad & 1u) ? cs : sn;
+    const float ca = (quad == 1u || quad == 2u) ? -ca0 : ca0;
+    const float sa = (quad >= 2u) ? -sa0 : sa0;
+    zc = r * ca;
+    zs = r * sa;
+}
+
+// z for parameters 4q..4q+3 at master step k.
+__device__ __forceinline__ f32x4 noise4(uint32_t seed_lo, uint32_t seed_hi, uint64_t q, uint64_t k) {
+    uint32_t x[4];
+    philox4x32_10((uint32_t)q, (uint32_t)(q >> 32), (uint32_t)k, (uint32_t)(k >> 32), seed_lo, seed_hi, x);
+    float z0, z1, z2, z3;
+    box_muller_pair(x[0], x[1], z0, z1);
+    box_muller_pair(x[2], x[3], z2, z3);
+    return f32x4{z0, z1, z2, z3};
+}
+
+__device__ __forceinline__ float quadratic_g(float s, float a, float ts, float sigma, float z) {
+    const float off = s - ts;
+    const float pull = a * off;
+    const float noise = sigma * z;
+    return pull + noise;
+}
+
+__global__ __launch_bounds__(kBlock) void noise_fill_kernel(uint32_t seed_lo, uint32_t seed_hi, uint64_t k,
+                                                            uint64_t j0, uint64_t n, float* __restrict__ out) {
+    const uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (i >= n) return;
+    const uint64_t j = j0 + i;
+    const f32x4 z = noise4(seed_lo, seed_hi, j >> 2, k);
+    const uint32_t lane = (uint32_t)(j & 3);
+    out[i] = lane == 0 ? z.x : lane == 1 ? z.y : lane == 2 ? z.z : z.w;
+}
+
+__global__ __launch_bounds__(kBlock) void quadratic_gradient_kernel(const float* __restrict__ snap,
+                                                                    const float* __restrict__ a,
+                                                                    const float* __restrict__ ts, uint64_t N,
+                                                                    uint64_t k, RunConst rc,
+                                                                    float* __restrict__ g_out) {
+    const uint64_t q = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+    const uint64_t j0 = 4 * q;
+    if (j0 >= N) return;
+    const f32x4 z = noise4(rc.seed_lo, rc.seed_hi, q, k);
+    if (j0 + 3 < N) {
+        const f32x4 s = reinterpret_cast<const f32x4*>(snap)[q];
+        const f32x4 a4 = reinterpret_cast<const f32x4*>(a)[q];
+        const f32x4 t4 = reinterpret_cast<const f32x4*>(ts)[q];
+        f32x4 g;
+        g.x = quadratic_g(s.x, a4.x, t4.x, rc.sigma, z.x);
+        g.y = quadratic_g(s.y, a4.y, t4.y, rc.sigma, z.y);
+        g.z = quadratic_g(s.z, a4.z, t4.z, rc.sigma, z.z);
+        g.w = quadratic_g(s.w, a4.w, t4.w, rc.sigma, z.w);
+        reinterpret_cast<f32x4*>(g_out)[q] = g;
+    } else {
+        const float zz[4] = {z.x, z.y, z.z, z.w};
+        for (int e = 0; e < 4 && j0 + e < N; ++e)
+            g_out[j0 + e] = quadratic_g(snap[j0 + e], a[j0 + e], ts[j0 + e], rc.sigma, zz[e]);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Persistent multi-arrival kernel.  Thread = one group of four parameters.
+// theta, v, m, a, theta* stay in registers for the whole chunk; per arrival
+// the thread reads and rewrites only its 16 bytes of the arriving worker's
+// snapshot.  No thread ever needs another thread's data, so there is no
+// grid-wide or block-wide synchronisation.  The snapshot of the next arrival
+// is requested before the arithmetic of the current one.
+// ---------------------------------------------------------------------------
+template <int MODE, bool KEEP_M>
+__global__ __launch_bounds__(kBlock) void persistent_kernel(float* __restrict__ theta, float* __restrict__ v,
+                                                            float* __restrict__ m, float* snaps, uint64_t stride,
+                                                            const float* __restrict__ a,
+                                                            const float* __restrict__ ts,
+                                                            const ga_arrival* __restrict__ table, uint32_t T,
+                                                            uint64_t k0, uint64_t N, RunConst rc) {
+    const uint64_t q = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+    const uint64_t j0 = 4 * q;
+    if (j0 >= N || T == 0) return;
+    const uint32_t n_valid = (N - j0 >= 4) ? 4u : (uint32_t)(N - j0);
+
+    // state arrays are padded to a multiple of 64 floats: the 128-bit access is always in bounds
+    f32x4 th = reinterpret_cast<const f32x4*>(theta)[q];
+    f32x4 vv = reinterpret_cast<const f32x4*>(v)[q];
+    f32x4 mm = {0.f, 0.f, 0.f, 0.f};
+    if constexpr (KEEP_M) mm = reinterpret_cast<const f32x4*>(m)[q];
+    f32x4 a4, t4;
+    if (n_valid == 4) {
+        a4 = reinterpret_cast<const f32x4*>(a)[q];
+        t4 = reinterpret_cast<const f32x4*>(ts)[q];
+    } else {   // caller arrays hold exactly N floats
+        a4.x = a[j0];                          t4.x = ts[j0];
+        a4.y = n_valid > 1 ? a[j0 + 1] : 0.f;  t4.y = n_valid > 1 ? ts[j0 + 1] : 0.f;
+        a4.z = n_valid > 2 ? a[j0 + 2] : 0.f;  t4.z = n_valid > 2 ? ts[j0 + 2] : 0.f;
+        a4.w = 0.f;                            t4.w = 0.f;
+    }
+
+    StepConst c;
+    c.gamma = rc.gamma; c.eta_max = rc.eta_max; c.eps = rc.eps; c.beta = rc.beta;
+    c.one_minus_beta = rc.one_minus_beta;
+
+    f32x4* const snap_q = reinterpret_cast<f32x4*>(snaps) + q;       // this thread's column
+    const uint64_t stride4 = stride >> 2;
+    ga_arrival row = table[0];
+    f32x4 s = snap_q[(uint64_t)row.worker * stride4];
+
+    for (uint32_t t = 0; t < T; ++t) {
+        const bool more = (t + 1 < T);
+        ga_arrival next = row;
+        f32x4 s_next = s;
+        if (more) {
+            next = table[t + 1];
+            s_next = snap_q[(uint64_t)next.worker * stride4];
+        }
+        const uint64_t k = k0 + t + 1;
+        c.lr = row.lr; c.tau = row.tau; c.bc_prev = row.bc_prev; c.first = (k == 1);
+        const f32x4 z = noise4(rc.seed_lo, rc.seed_hi, q, k);
+
+        f32x4 g;
+        g.x = quadratic_g(s.x, a4.x, t4.x, rc.sigma, z.x);
+        g.y = quadratic_g(s.y, a4.y, t4.y, rc.sigma, z.y);
+        g.z = quadratic_g(s.z, a4.z, t4.z, rc.sigma, z.z);
+        g.w = quadratic_g(s.w, a4.w, t4.w, rc.sigma, z.w);
+        update4<MODE, KEEP_M>(th, vv, mm, s, g, c, n_valid);
+
+        snap_q[(uint64_t)row.worker * stride4] = th;     // padding lanes of th are never modified
+        // same worker twice in a row: its snapshot is what was just written
+        s = (next.worker == row.worker) ? th : s_next;
+        row = next;
+    }
+
+    reinterpret_cast<f32x4*>(theta)[q] = th;
+    reinterpret_cast<f32x4*>(v)[q] = vv;
+    if constexpr (KEEP_M) reinterpret_cast<f32x4*>(m)[q] = mm;
+}
+
+// ---------------------------------------------------------------------------
+// Gap statistics: per-thread accumulation, wavefront (64 lanes) butterfly,
+// one partial per block, then a single block adds the partials in a fixed
+// order so that the result does not depend on scheduling.
+// ---------------------------------------------------------------------------
+struct DiagAcc {
+    double sum;
+    uint32_t gt1, gt0, bad;
+};
+
+__device__ __forceinline__ void diag_one(DiagAcc& acc, float th, float s, float m, float bc, int first,
+                                         float eta_max, float eps) {
+    const float diff = th - s;
+    const float delta = fabsf(diff);
+    const float bc1 = first ? 1.0f : bc;
+    const uint32_t keep = first ? 0u : 0xFFFFFFFFu;
+    const float mhat = __uint_as_float(__float_as_uint(m / bc1) & keep);
+    const float root = sqrtf(mhat);
+    const float sum = root + eps;
+    const float C = eta_max * sum;
+    const float graw = delta / C;
+    if (!isfinite(graw)) {
+        acc.bad += 1;
+    } else {
+        acc.sum += (double)graw;
+        acc.gt1 += (graw > 1.0f);
+        acc.gt0 += (graw > 0.0f);
+    }
+}
+
+__device__ __forceinline__ DiagPartial block_reduce(double sum, unsigned long long gt1, unsigned long long gt0,
+                                                    unsigned long long bad) {
+    __shared__ DiagPartial wave_part[kBlock / 64];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        sum += __shfl_xor(sum, off, 64);
+        gt1 += __shfl_xor(gt1, off, 64);
+        gt0 += __shfl_xor(gt0, off, 64);
+        bad += __shfl_xor(bad, off, 64);
+    }
+    const int wave = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0) {
+        wave_part[wave].sum_graw = sum;
+        wave_part[wave].n_gt1 = gt1;
+        wave_part[wave].n_gt0 = gt0;
+        wave_part[wave].n_bad = bad;
+    }
+    __syncthreads();
+    DiagPartial r = wave_part[0];
+#pragma unroll
+    for (int w = 1; w < kBlock / 64; ++w) {
+        r.sum_graw += wave_part[w].sum_graw;
+        r.n_gt1 += wave_part[w].n_gt1;
+        r.n_gt0 += wave_part[w].n_gt0;
+        r.n_bad += wave_part[w].n_bad;
+    }
+    return r;
+}
+
+__global__ __launch_bounds__(kBlock) void diag_kernel(const float* __restrict__ theta, const float* __restrict__ m,
+                                                      const float* __restrict__ snap, uint64_t N, float bc,
+                                                      int first, float eta_max, float eps,
+                                                      DiagPartial* __restrict__ partials) {
+    const uint64_t n4 = N >> 2;
+    DiagAcc acc = {0.0, 0u, 0u, 0u};
+    for (uint64_t q = (uint64_t)blockIdx.x * kBlock + threadIdx.x; q < n4; q += (uint64_t)gridDim.x * kBlock) {
+        const f32x4 th = reinterpret_cast<const f32x4*>(theta)[q];
+        const f32x4 s = reinterpret_cast<const f32x4*>(snap)[q];
+        const f32x4 mm = reinterpret_cast<const f32x4*>(m)[q];
+        diag_one(acc, th.x, s.x, mm.x, bc, first, eta_max, eps);
+        diag_one(acc, th.y, s.y, mm.y, bc, first, eta_max, eps);
+        diag_one(acc, th.z, s.z, mm.z, bc, first, eta_max, eps);
+        diag_one(acc, th.w, s.w, mm.w, bc, first, eta_max, eps);
+    }
+    if (blockIdx.x == 0 && threadIdx.x < (N & 3)) {
+        const uint64_t j = 4 * n4 + threadIdx.x;
+        diag_one(acc, theta[j], snap[j], m[j], bc, first, eta_max, eps);
+    }
+    const DiagPartial r = block_reduce(acc.sum, acc.gt1, acc.gt0, acc.bad);
+    if (threadIdx.x == 0) partials[blockIdx.x] = r;
+}
+
+__global__ __launch_bounds__(kBlock) void diag_final_kernel(const DiagPartial* __restrict__ partials,
+                                                            uint32_t n_partials, DiagPartial* __restrict__ total) {
+    double sum = 0.0;
+    unsigned long long gt1 = 0, gt0 = 0, bad = 0;
+    for (uint32_t i = threadIdx.x; i < n_partials; i += kBlock) {
+        sum += partials[i].sum_graw;
+        gt1 += partials[i].n_gt1;
+        gt0 += partials[i].n_gt0;
+        bad += partials[i].n_bad;
+    }
+    const DiagPartial r = block_reduce(sum, gt1, gt0, bad);
+    if (threadIdx.x == 0) *total = r;
+}
+
+// ---------------------------------------------------------------------------
+// Fills.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kBlock) void fill_kernel(float* __restrict__ dst, uint64_t n, float value) {
+    for (uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += (uint64_t)gridDim.x * kBlock)
+        dst[i] = value;
+}
+
+__global__ __launch_bounds__(kBlock) void broadcast_rows_kernel(float* __restrict__ dst, uint64_t stride,
+                                                                uint32_t rows, const float* __restrict__ src,
+                                                                uint64_t n) {
+    for (uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += (uint64_t)gridDim.x * kBlock) {
+        const float x = src[i];
+        for (uint32_t r = 0; r < rows; ++r) dst[(uint64_t)r * stride + i] = x;
+    }
+}
+
+uint32_t blocks_for(uint64_t items, uint64_t per_block, uint32_t cap) {
+    const uint64_t b = (items + per_block - 1) / per_block;
+    return (uint32_t)(b < 1 ? 1 : (b > cap ? cap : b));
+}
+
+// ---------------------------------------------------------------------------
+// Dispatch of the apply kernel over (mode, dtype, keep_m, aligned).
+// ---------------------------------------------------------------------------
+constexpr int kApplyU = 2;
+
+template <int MODE, int DT, bool KEEP_M, bool SNAP, bool ALIGNED>
+hipError_t launch_apply_t(const StatePtrs& st, float* snap, const void* g, uint64_t N, const StepConst& c,
+                          hipStream_t stream) {
+    const uint64_t n4 = N >> 2;
+    const uint64_t per_block = (uint64_t)kBlock * kApplyU;
+    const uint64_t blocks = (n4 + per_block - 1) / per_block;
+    if (blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    const uint32_t grid = blocks == 0 ? 1u : (uint32_t)blocks;
+    hipLaunchKernelGGL((apply_kernel<MODE, DT, KEEP_M, SNAP, ALIGNED, kApplyU>), dim3(grid), dim3(kBlock), 0, stream,
+                       st.theta, st.v, st.m, snap, g, N, c);
+    return hipGetLastError();
+}
+
+template <int MODE, bool KEEP_M, bool SNAP>
+hipError_t launch_apply_m(const StatePtrs& st, float* snap, const void* g, int dt, uint64_t N, const StepConst& c,
+                          hipStream_t stream) {
+    const uintptr_t addr = reinterpret_cast<uintptr_t>(g);
+    if (dt == GA_F32) {
+        if ((addr & 15u) == 0) return launch_apply_t<MODE, GA_F32, KEEP_M, SNAP, true>(st, snap, g, N, c, stream);
+        return launch_apply_t<MODE, GA_F32, KEEP_M, SNAP, false>(st, snap, g, N, c, stream);
+    }
+    if ((addr & 7u) == 0) return launch_apply_t<MODE, GA_BF16, KEEP_M, SNAP, true>(st, snap, g, N, c, stream);
+    return launch_apply_t<MODE, GA_BF16, KEEP_M, SNAP, false>(st, snap, g, N, c, stream);
+}
+
+// non-GA modes: m and the snapshot are optional
+template <int MODE>
+hipError_t launch_apply_opt(const StatePtrs& st, float* snap, const void* g, int dt, uint64_t N, const StepConst& c,
+                            bool keep_m, bool write_snap, hipStream_t stream) {
+    if (keep_m) {
+        return write_snap ? launch_apply_m<MODE, true, true>(st, snap, g, dt, N, c, stream)
+                          : launch_apply_m<MODE, true, false>(st, snap, g, dt, N, c, stream);
+    }
+    return write_snap ? launch_apply_m<MODE, false, true>(st, snap, g, dt, N, c, stream)
+                      : launch_apply_m<MODE, false, false>(st, snap, g, dt, N, c, stream);
+}
+
+}  // namespace
+
+hipError_t launch_apply(const StatePtrs& st, uint64_t N, uint32_t worker, const void* g, int grad_dtype, int mode,
+                        bool keep_m, bool write_snap, const StepConst& c, hipStream_t stream) {
+    float* snap = st.snaps + (uint64_t)worker * st.stride;
+    switch (mode) {
+        case GA_MODE_GA:
+            return launch_apply_m<GA_MODE_GA, true, true>(st, snap, g, grad_dtype, N, c, stream);
+        case GA_MODE_GA_HINGE:
+            return launch_apply_m<GA_MODE_GA_HINGE, true, true>(st, snap, g, grad_dtype, N, c, stream);
+        case GA_MODE_SA:
+            return launch_apply_opt<GA_MODE_SA>(st, snap, g, grad_dtype, N, c, keep_m, write_snap, stream);
+        case GA_MODE_ASGD:
+        case GA_MODE_SA_STEP:   // the step-size penalty is already folded into c.lr
+            return launch_apply_opt<GA_MODE_ASGD>(st, snap, g, grad_dtype, N, c, keep_m, write_snap, stream);
+        default:
+            return hipErrorInvalidValue;
+    }
+}
+
+hipError_t launch_persistent(const StatePtrs& st, uint64_t N, const ga_arrival* dev_table, uint32_t T, uint64_t k0,
+                             const float* a, const float* theta_star, int mode, bool keep_m, const RunConst& rc,
+                             hipStream_t stream) {
+    const uint64_t groups = (N + 3) >> 2;
+    const uint64_t blocks = (groups + kBlock - 1) / kBlock;
+    if (blocks == 0 || blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    const dim3 grid((uint32_t)blocks), block(kBlock);
+#define GA_LAUNCH_PERSIST(MODE, KEEP)                                                                               \
+    hipLaunchKernelGGL((persistent_kernel<MODE, KEEP>), grid, block, 0, stream, st.theta, st.v, st.m, st.snaps,     \
+                       st.stride, a, theta_star, dev_table, T, k0, N, rc)
+    switch (mode) {
+        case GA_MODE_GA: GA_LAUNCH_PERSIST(GA_MODE_GA, true); break;
+        case GA_MODE_GA_HINGE: GA_LAUNCH_PERSIST(GA_MODE_GA_HINGE, true); break;
+        case GA_MODE_SA:
+            if (keep_m) GA_LAUNCH_PERSIST(GA_MODE_SA, true); else GA_LAUNCH_PERSIST(GA_MODE_SA, false);
+            break;
+        case GA_MODE_ASGD:
+        case GA_MODE_SA_STEP:
+            if (keep_m) GA_LAUNCH_PERSIST(GA_MODE_ASGD, true); else GA_LAUNCH_PERSIST(GA_MODE_ASGD, false);
+            break;
+        default: return hipErrorInvalidValue;
+    }
+#undef GA_LAUNCH_PERSIST
+    return hipGetLastError();
+}
+
+hipError_t launch_quadratic_gradient(const StatePtrs& st, uint64_t N, uint32_t worker, const float* a,
+                                     const float* theta_star, uint64_t k, const RunConst& rc, float* g_out,
+                                     hipStream_t stream) {
+    const uint64_t groups = (N + 3) >> 2;
+    const uint64_t blocks = (groups + kBlock - 1) / kBlock;
+    if (blocks == 0 || blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(quadratic_gradient_kernel, dim3((uint32_t)blocks), dim3(kBlock), 0, stream,
+                       st.snaps + (uint64_t)worker * st.stride, a, theta_star, N, k, rc, g_out);
+    return hipGetLastError();
+}
+
+hipError_t launch_diagnostics(const StatePtrs& st, uint64_t N, uint32_t worker, float bc, int first, float eta_max,
+                              float eps, DiagPartial* dev_partials, hipStream_t stream) {
+    const uint32_t grid = blocks_for(N >> 2, (uint64_t)kBlock * 4, kDiagMaxBlocks);
+    hipLaunchKernelGGL(diag_kernel, dim3(grid), dim3(kBlock), 0, stream, st.theta, st.m,
+                       st.snaps + (uint64_t)worker * st.stride, N, bc, first, eta_max, eps, dev_partials);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(diag_final_kernel, dim3(1), dim3(kBlock), 0, stream, dev_partials, grid,
+                       dev_partials + kDiagMaxBlocks);
+    return hipGetLastError();
+}
+
+hipError_t launch_noise_fill(uint64_t seed, uint64_t k, uint64_t j0, uint64_t n, float* out, hipStream_t stream) {
+    if (n == 0) return hipSuccess;
+    const uint64_t blocks = (n + kBlock - 1) / kBlock;
+    if (blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(noise_fill_kernel, dim3((uint32_t)blocks), dim3(kBlock), 0, stream, (uint32_t)seed,
+                       (uint32_t)(seed >> 32), k, j0, n, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_fill(float* dst, uint64_t n, float value, hipStream_t stream) {
+    if (n == 0) return hipSuccess;
+    hipLaunchKernelGGL(fill_kernel, dim3(blocks_for(n, kBlock * 8, 65536)), dim3(kBlock), 0, stream, dst, n, value);
+    return hipGetLastError();
+}
+
+hipError_t launch_broadcast_rows(float* dst, uint64_t stride, uint32_t rows, const float* src, uint64_t n,
+                                 hipStream_t stream) {
+    if (n == 0 || rows == 0) return hipSuccess;
+    hipLaunchKernelGGL(broadcast_rows_kernel, dim3(blocks_for(n, kBlock * 4, 65536)), dim3(kBlock), 0, stream, dst,
+                       stride, rows, src, n);
+    return hipGetLastError();
+}
+
+}  // namespace ga

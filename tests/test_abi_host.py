@@ -1,0 +1,129 @@
+"""C-ABI checks that need no GPU: the library loads, exports every symbol the
+header declares, and its host-only logic (schedule simulator, delay
+bookkeeping, per-arrival scalars, argument validation) agrees with the oracle
+bit for bit."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_1909_10802_amd as ga
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def header_functions():
+    text = open(os.path.join(ROOT, "include", "ga.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ga_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = header_functions()
+    assert len(names) >= 28
+    L = ga.lib()
+    for n in names:
+        assert hasattr(L, n), n
+    assert sorted(ga.SIGNATURES) == names          # the binding covers the whole header
+    assert ga.ga_version() == "0.1"
+
+
+def test_struct_layouts_match_the_header():
+    assert C.sizeof(ga.ga_arrival) == 16 and ga.ARRIVAL_DTYPE.itemsize == 16
+    assert C.sizeof(ga.ga_diag) == 32
+    assert ga.ga_grad_source.dev_a.offset == 8 and ga.ga_grad_source.seed.offset == 24
+
+
+@pytest.mark.parametrize("dist,sigma", [(ga.GA_DIST_EXP, 1.0), (ga.GA_DIST_LOGNORMAL, 1.0), (ga.GA_DIST_HETERO, 1.5)])
+def test_schedule_simulator_matches_oracle(dist, sigma):
+    for W, T, seed in [(1, 50, 0), (8, 1000, 1), (32, 10000, 2), (128, 5000, 2**40 + 17)]:
+        mine = ga.ga_simulate_schedule(W, T, dist, sigma, seed)
+        ref = oracle.simulate_schedule(W, T, dist, sigma, seed)
+        assert np.array_equal(mine, ref), (W, T, seed)
+
+
+def test_delays_match_oracle_and_resume():
+    W, T = 16, 3000
+    sched = ga.ga_simulate_schedule(W, T, seed=5)
+    tau, it = ga.ga_delays_from_schedule(W, sched)
+    tau_o, it_o = oracle.delays(W, sched)
+    assert np.array_equal(tau, tau_o) and np.array_equal(it, it_o)
+    ta, ia = ga.ga_delays_from_schedule(W, sched[:1000])
+    tb, ib = ga.ga_delays_from_schedule(W, sched[1000:], k0=1000, host_iter=ia.copy())
+    assert np.array_equal(np.concatenate([ta, tb]), tau) and np.array_equal(ib, it)
+
+
+@pytest.mark.parametrize("mode", [ga.GA_MODE_ASGD, ga.GA_MODE_SA, ga.GA_MODE_SA_STEP, ga.GA_MODE_GA])
+def test_arrival_rows(mode):
+    W, T, eta, beta = 8, 500, np.float32(0.1), np.float32(0.999)
+    sched = ga.ga_simulate_schedule(W, T, seed=3)
+    it = np.zeros(W, dtype=np.uint64)
+    rows = ga.ga_plan_arrivals(W, sched, 0, it, mode, float(eta), float(beta))
+    tau_o, it_o = oracle.delays(W, sched)
+    assert np.array_equal(rows["worker"], sched)
+    assert np.array_equal(rows["tau"], tau_o.astype(np.float32))
+    assert np.array_equal(it, it_o)
+    lr = eta / tau_o.astype(np.float32) if mode == ga.GA_MODE_SA_STEP else np.full(T, eta)
+    assert np.array_equal(rows["lr"], lr.astype(np.float32))
+    k = np.arange(1, T + 1)
+    bc = (1.0 - np.float64(beta) ** (k - 1).astype(np.float64)).astype(np.float32)
+    assert np.array_equal(rows["bc_prev"], bc) and rows["bc_prev"][0] == 0.0
+    # continuing from step 200 gives the same rows as the tail of the full plan
+    it2 = oracle.delays(W, sched[:200])[1]
+    rows2 = ga.ga_plan_arrivals(W, sched[200:], 200, it2, mode, float(eta), float(beta))
+    assert np.array_equal(rows2, rows[200:])
+
+
+def test_host_argument_errors():
+    with pytest.raises(ga.GaError) as e:
+        ga.ga_simulate_schedule(0, 10)
+    assert e.value.status == ga.GA_ERR_ARG
+    with pytest.raises(ga.GaError):
+        ga.ga_simulate_schedule(4, 10, dist=7)
+    with pytest.raises(ga.GaError) as e:
+        ga.ga_delays_from_schedule(4, np.array([0, 1, 4], dtype=np.uint32))
+    assert e.value.status == ga.GA_ERR_WORKER
+    with pytest.raises(ga.GaError):
+        ga.ga_delays_from_schedule(2, np.array([0, 1], dtype=np.uint32), k0=3, host_iter=np.array([5, 0], np.uint64))
+    with pytest.raises(ga.GaError):
+        ga.ga_plan_arrivals(2, np.array([0, 1], dtype=np.uint32), 0, np.zeros(2, np.uint64), 9, 0.1, 0.999)
+    with pytest.raises(ga.GaError):
+        ga.ga_plan_arrivals(2, np.array([0, 1], dtype=np.uint32), 0, np.zeros(2, np.uint64), 0, 0.1, 1.0)
+
+
+def test_workspace_size_and_create_validation():
+    L = ga.lib()
+    assert ga.ga_workspace_bytes(0, 4) == 0 and ga.ga_workspace_bytes(4, 0) == 0
+    n1 = ga.ga_workspace_bytes(1, 1)
+    assert n1 % 256 == 0 and n1 >= 4 * 256
+    big = ga.ga_workspace_bytes(350_000_000, 128)
+    assert big >= 131 * 350_000_000 * 4 and big < 131 * 350_000_064 * 4 + (1 << 20)
+    assert ga.ga_workspace_bytes(65, 3) - ga.ga_workspace_bytes(64, 3) == 6 * 64 * 4   # rows padded to 64 floats
+
+    ctx = C.c_void_p()
+    fake = C.c_void_p(0x7F0000000000)               # never dereferenced: validation fails first
+
+    def create(N=100, W=2, eta=0.1, gamma=0.9, mode=ga.GA_MODE_GA, ws=fake, nbytes=1 << 30):
+        return L.ga_create(C.byref(ctx), N, W, eta, gamma, mode, ws, nbytes, None)
+
+    assert create(N=0) == ga.GA_ERR_ARG
+    assert create(W=0) == ga.GA_ERR_ARG
+    assert create(eta=0.0) == ga.GA_ERR_ARG and create(eta=-1.0) == ga.GA_ERR_ARG
+    assert create(eta=float("nan")) == ga.GA_ERR_ARG
+    assert create(gamma=1.0) == ga.GA_ERR_ARG and create(gamma=-1.0) == ga.GA_ERR_ARG
+    assert create(mode=5) == ga.GA_ERR_ARG and create(mode=-1) == ga.GA_ERR_ARG
+    assert create(ws=None) == ga.GA_ERR_ARG
+    assert create(ws=C.c_void_p(0x7F0000000010)) == ga.GA_ERR_ALIGN
+    assert create(nbytes=1024) == ga.GA_ERR_ALIGN
+    assert b"workspace" in L.ga_last_error(None)
+    assert L.ga_create(None, 100, 2, 0.1, 0.9, 3, fake, 1 << 30, None) == ga.GA_ERR_ARG
+    assert ctx.value is None
+    # null context is an argument error everywhere, never a crash
+    assert L.ga_apply(None, 0, fake, 0) == ga.GA_ERR_ARG
+    assert L.ga_set_lr(None, 0.1) == ga.GA_ERR_ARG
+    assert L.ga_get_theta(None, fake) == ga.GA_ERR_ARG
+    assert L.ga_step(None) == 0
+    L.ga_destroy(None)
