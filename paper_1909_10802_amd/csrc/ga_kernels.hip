@@ -30,6 +30,23 @@ constexpr int kBlock = 256;
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
+// 128-bit accesses with or without the non-temporal hint.  The MI355X has a
+// 256 MB memory-side cache in front of HBM: arrays that are touched once per
+// arrival (gradient, the arriving worker's snapshot) are streamed around it so
+// that arrays touched at every arrival (theta, and v when both fit) stay in it.
+template <bool NT>
+__device__ __forceinline__ f32x4 load4(const float* __restrict__ base, uint64_t q) {
+    const f32x4* p = reinterpret_cast<const f32x4*>(base) + q;
+    if constexpr (NT) return __builtin_nontemporal_load(p);
+    else return *p;
+}
+template <bool NT>
+__device__ __forceinline__ void store4(float* __restrict__ base, uint64_t q, const f32x4& x) {
+    f32x4* p = reinterpret_cast<f32x4*>(base) + q;
+    if constexpr (NT) __builtin_nontemporal_store(x, p);
+    else *p = x;
+}
+
 // ---------------------------------------------------------------------------
 // One parameter, one arrival.
 // ---------------------------------------------------------------------------
@@ -124,7 +141,7 @@ __device__ __forceinline__ float load_g1(const void* __restrict__ g, uint64_t j)
 // contiguous 128-bit loads and stores per array.  All loads of a thread are
 // issued before the first dependent operation.
 // ---------------------------------------------------------------------------
-template <int MODE, int DT, bool KEEP_M, bool SNAP, bool ALIGNED, int U>
+template <int MODE, int DT, bool KEEP_M, bool SNAP, bool ALIGNED, bool STREAM_V, int U>
 __global__ __launch_bounds__(kBlock) void apply_kernel(float* __restrict__ theta, float* __restrict__ v,
                                                        float* __restrict__ m, float* __restrict__ snap,
                                                        const void* __restrict__ g, uint64_t N, StepConst c) {
@@ -139,10 +156,10 @@ __global__ __launch_bounds__(kBlock) void apply_kernel(float* __restrict__ theta
         mm[u] = f32x4{0.f, 0.f, 0.f, 0.f};
         ss[u] = f32x4{0.f, 0.f, 0.f, 0.f};
         if (q < n4) {
-            th[u] = reinterpret_cast<const f32x4*>(theta)[q];
-            vv[u] = reinterpret_cast<const f32x4*>(v)[q];
-            if constexpr (KEEP_M) mm[u] = reinterpret_cast<const f32x4*>(m)[q];
-            if constexpr (GAP) ss[u] = reinterpret_cast<const f32x4*>(snap)[q];
+            th[u] = load4<false>(theta, q);
+            vv[u] = load4<STREAM_V>(v, q);
+            if constexpr (KEEP_M) mm[u] = load4<true>(m, q);
+            if constexpr (GAP) ss[u] = load4<true>(snap, q);
             gg[u] = load_g4<DT, ALIGNED>(g, q);
         }
     }
@@ -151,10 +168,10 @@ __global__ __launch_bounds__(kBlock) void apply_kernel(float* __restrict__ theta
         const uint64_t q = base + (uint64_t)u * kBlock;
         if (q < n4) {
             update4<MODE, KEEP_M>(th[u], vv[u], mm[u], ss[u], gg[u], c);
-            reinterpret_cast<f32x4*>(theta)[q] = th[u];
-            reinterpret_cast<f32x4*>(v)[q] = vv[u];
-            if constexpr (KEEP_M) reinterpret_cast<f32x4*>(m)[q] = mm[u];
-            if constexpr (SNAP) __builtin_nontemporal_store(th[u], reinterpret_cast<f32x4*>(snap) + q);
+            store4<false>(theta, q, th[u]);
+            store4<STREAM_V>(v, q, vv[u]);
+            if constexpr (KEEP_M) store4<true>(m, q, mm[u]);
+            if constexpr (SNAP) store4<true>(snap, q, th[u]);
         }
     }
 
@@ -495,6 +512,9 @@ uint32_t blocks_for(uint64_t items, uint64_t per_block, uint32_t cap) {
 // ---------------------------------------------------------------------------
 constexpr int kApplyU = 2;
 
+// theta and v together must fit the memory-side cache with room to spare for v to be kept in it
+constexpr uint64_t kKeepVMaxN = (uint64_t)208 * 1024 * 1024 / 8;
+
 template <int MODE, int DT, bool KEEP_M, bool SNAP, bool ALIGNED>
 hipError_t launch_apply_t(const StatePtrs& st, float* snap, const void* g, uint64_t N, const StepConst& c,
                           hipStream_t stream) {
@@ -502,9 +522,13 @@ hipError_t launch_apply_t(const StatePtrs& st, float* snap, const void* g, uint6
     const uint64_t per_block = (uint64_t)kBlock * kApplyU;
     const uint64_t blocks = (n4 + per_block - 1) / per_block;
     if (blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
-    const uint32_t grid = blocks == 0 ? 1u : (uint32_t)blocks;
-    hipLaunchKernelGGL((apply_kernel<MODE, DT, KEEP_M, SNAP, ALIGNED, kApplyU>), dim3(grid), dim3(kBlock), 0, stream,
-                       st.theta, st.v, st.m, snap, g, N, c);
+    const dim3 grid(blocks == 0 ? 1u : (uint32_t)blocks), block(kBlock);
+    if (N <= kKeepVMaxN)
+        hipLaunchKernelGGL((apply_kernel<MODE, DT, KEEP_M, SNAP, ALIGNED, false, kApplyU>), grid, block, 0, stream,
+                           st.theta, st.v, st.m, snap, g, N, c);
+    else
+        hipLaunchKernelGGL((apply_kernel<MODE, DT, KEEP_M, SNAP, ALIGNED, true, kApplyU>), grid, block, 0, stream,
+                           st.theta, st.v, st.m, snap, g, N, c);
     return hipGetLastError();
 }
 
