@@ -33,7 +33,7 @@
  * tau_k = k - iter[i]), per parameter j, every line one IEEE float operation:
  *   GA modes (Alg. 4, Eq. 5; C from Alg. 14 as left by arrival k-1):
  *       diff  = theta - snap_i            delta = |diff|
- *       mhat  = m / (1 - beta^(k-1))      (taken as 0 when k = 1)
+ *       mhat  = m * inv_bc_prev           inv_bc_prev = 1/(1 - beta^(k-1)), 0 when k = 1
  *       C     = eta_max * (sqrt(mhat) + eps)
  *       Graw  = delta / C
  *       G     = 1 + Graw   (GA_MODE_GA)   or   max(1, Graw)   (GA_MODE_GA_HINGE)
@@ -44,8 +44,9 @@
  *   theta = theta - lr * v,   lr = eta_k, or eta_k / tau_k for GA_MODE_SA_STEP (Alg. 3)
  *   m     = beta * m + (1 - beta) * (v * v)                    (Alg. 14; GA modes, or gap tracking on)
  *   snap_i = theta                                             (Alg. 4)
- * then on the host iter[i] = k.  The scalars 1 - beta^(k-1) are evaluated in
- * double and rounded once to float.
+ * then on the host iter[i] = k.  The scalar 1/(1 - beta^(k-1)) is evaluated in
+ * double and rounded once to float (Alg. 14 divides by 1 - beta^k and leaves
+ * the rounding open; before the first arrival m-hat_0 = 0).
  */
 #ifndef GA_H
 #define GA_H
@@ -139,7 +140,7 @@ typedef struct ga_arrival {
     uint32_t worker;  /* i */
     float tau;        /* (float) tau_k */
     float lr;         /* eta_k, or eta_k / tau_k for GA_MODE_SA_STEP */
-    float bc_prev;    /* (float)(1 - beta^(k-1)); 0 when k = 1 */
+    float inv_bc_prev; /* (float)(1 / (1 - beta^(k-1))); 0 when k = 1 */
 } ga_arrival;
 
 /* ------------------------------------------------------------------ host only

@@ -271,17 +271,21 @@ struct Hyper {
     R eps;       // Alg. 14 epsilon
 };
 
-// 1 - beta^k, evaluated in double and rounded once to R.
+// 1 / (1 - beta^k), evaluated in double and rounded once to R: Alg. 14's bias
+// correction m-hat_k = m_k / (1 - beta^k) is applied as a multiplication by
+// this factor (the paper does not fix the rounding).  k = 0 (nothing received
+// yet, m_0 = 0, "0/0"): the factor is taken as 0, so that m-hat_0 = 0.
 template <typename R>
-R bias_correction(R beta, uint64_t k) {
-    return (R)(1.0 - std::pow((double)beta, (double)k));
+R inverse_bias_correction(R beta, uint64_t k) {
+    if (k == 0) return (R)0;
+    return (R)(1.0 / (1.0 - std::pow((double)beta, (double)k)));
 }
 
 // C_{k-1}: the coefficient as Alg. 14 leaves it after arrival k-1, from the
-// stored biased moment m_{k-1}.  Before the first arrival m-hat is taken as 0.
+// stored biased moment m_{k-1}.
 template <typename R>
-R coefficient_C(R m, R bc_prev, bool first, R eta_max, R eps) {
-    const R m_hat = first ? (R)0 : m / bc_prev;
+R coefficient_C(R m, R inv_bc_prev, R eta_max, R eps) {
+    const R m_hat = m * inv_bc_prev;
     const R root = std::sqrt(m_hat);
     const R sum = root + eps;
     return eta_max * sum;
@@ -294,7 +298,7 @@ void master_step(uint64_t n, R* theta, R* v, R* m, R* snap_i, const R* g, int mo
                  uint64_t tau, const Hyper<R>& h, int track_gap) {
     const bool gap_mode = (mode == MODE_GA || mode == MODE_GA_HINGE);
     const bool keep_m = gap_mode || track_gap;
-    const R bc_prev = bias_correction<R>(h.beta, k - 1);
+    const R inv_bc_prev = inverse_bias_correction<R>(h.beta, k - 1);
     const R one_minus_beta = (R)1 - h.beta;
     const R tau_r = (R)tau;
     const R lr = (mode == MODE_SA_STEP) ? h.eta_k / tau_r : h.eta_k;   // Alg. 3
@@ -305,7 +309,7 @@ void master_step(uint64_t n, R* theta, R* v, R* m, R* snap_i, const R* g, int mo
         if (gap_mode) {
             const R diff = theta[j] - snap_i[j];
             const R delta = std::fabs(diff);
-            const R C = coefficient_C<R>(m[j], bc_prev, k == 1, h.eta_max, h.eps);
+            const R C = coefficient_C<R>(m[j], inv_bc_prev, h.eta_max, h.eps);
             const R g_raw = delta / C;
             const R G = (mode == MODE_GA) ? (R)1 + g_raw          // Alg. 4 / Eq. 5
                                           : std::fmax((R)1, g_raw);
@@ -356,13 +360,13 @@ template <typename R>
 void gap_statistics(uint64_t n, const R* theta, const R* m, const R* snap_i, uint64_t k, R beta,
                     R eta_max, R eps, double* sum_graw, uint64_t* n_gt1, uint64_t* n_gt0,
                     uint64_t* n_nonfinite) {
-    const R bc = bias_correction<R>(beta, k);
+    const R inv_bc = inverse_bias_correction<R>(beta, k);
     double sum = 0.0;
     uint64_t gt1 = 0, gt0 = 0, bad = 0;
     for (uint64_t j = 0; j < n; ++j) {
         const R diff = theta[j] - snap_i[j];
         const R delta = std::fabs(diff);
-        const R C = coefficient_C<R>(m[j], bc, k == 0, eta_max, eps);
+        const R C = coefficient_C<R>(m[j], inv_bc, eta_max, eps);
         const R g_raw = delta / C;
         if (!std::isfinite(g_raw)) {
             bad += 1;

@@ -45,10 +45,10 @@ class ga_diag(C.Structure):
 
 
 class ga_arrival(C.Structure):
-    _fields_ = [("worker", C.c_uint32), ("tau", C.c_float), ("lr", C.c_float), ("bc_prev", C.c_float)]
+    _fields_ = [("worker", C.c_uint32), ("tau", C.c_float), ("lr", C.c_float), ("inv_bc_prev", C.c_float)]
 
 
-ARRIVAL_DTYPE = np.dtype([("worker", np.uint32), ("tau", np.float32), ("lr", np.float32), ("bc_prev", np.float32)])
+ARRIVAL_DTYPE = np.dtype([("worker", np.uint32), ("tau", np.float32), ("lr", np.float32), ("inv_bc_prev", np.float32)])
 
 _u64, _u32, _i, _f, _d, _p = C.c_uint64, C.c_uint32, C.c_int, C.c_float, C.c_double, C.c_void_p
 

@@ -74,9 +74,11 @@ Layout layout_for(uint64_t N, uint32_t W) {
     return L;
 }
 
-// (float)(1 - beta^k), the power and the difference in double.
-float bias_correction(float beta, uint64_t k) {
-    return (float)(1.0 - std::pow((double)beta, (double)k));
+// (float)(1 / (1 - beta^k)) with the power, difference and quotient in double; 0 for k = 0
+// (Alg. 14: m_0 = 0, so m-hat_0 is taken as 0).
+float inverse_bias_correction(float beta, uint64_t k) {
+    if (k == 0) return 0.0f;
+    return (float)(1.0 / (1.0 - std::pow((double)beta, (double)k)));
 }
 
 // ----------------------------------------------------------- schedule draws
@@ -140,7 +142,7 @@ ga_arrival make_row(uint32_t worker, uint64_t k, uint64_t tau, int mode, float e
     r.worker = worker;
     r.tau = (float)tau;
     r.lr = (mode == GA_MODE_SA_STEP) ? eta_k / r.tau : eta_k;
-    r.bc_prev = (k == 1) ? 0.0f : bias_correction(beta, k - 1);
+    r.inv_bc_prev = inverse_bias_correction(beta, k - 1);
     return r;
 }
 
@@ -157,17 +159,16 @@ void plan(uint64_t T, const uint32_t* schedule, uint64_t k0, uint64_t* iter, int
     }
 }
 
-ga::StepConst step_const(const ga_ctx* c, const ga_arrival& r, uint64_t k) {
+ga::StepConst step_const(const ga_ctx* c, const ga_arrival& r) {
     ga::StepConst s;
     s.gamma = c->gamma;
     s.lr = r.lr;
     s.tau = r.tau;
-    s.bc_prev = r.bc_prev;
+    s.inv_bc_prev = r.inv_bc_prev;
     s.eta_max = c->eta_max;
     s.eps = c->eps;
     s.beta = c->beta;
     s.one_minus_beta = 1.0f - c->beta;
-    s.first = (k == 1);
     return s;
 }
 
@@ -200,7 +201,7 @@ int apply_one(ga_ctx* ctx, uint32_t worker, const void* dev_grad, int dtype, boo
     const uint64_t tau = k - ctx->iter[worker];
     const ga_arrival row = make_row(worker, k, tau, ctx->mode, ctx->lr, ctx->beta);
     const hipError_t e = ga::launch_apply(ctx->st, ctx->N, worker, dev_grad, dtype, ctx->mode, keeps_m(ctx),
-                                          write_snap, step_const(ctx, row, k), ctx->stream);
+                                          write_snap, step_const(ctx, row), ctx->stream);
     if (e != hipSuccess) return hip_fail(ctx, e, "apply launch");
     ctx->k = k;
     ctx->iter[worker] = k;
@@ -473,9 +474,8 @@ int ga_diagnostics(ga_ctx* ctx, uint32_t worker_id, ga_diag* host_out) {
     if (!host_out) return fail(ctx, GA_ERR_ARG, "diagnostics: output is null");
     if (worker_id >= ctx->W) return fail(ctx, GA_ERR_WORKER, "diagnostics: worker %u >= n_workers %u", worker_id, ctx->W);
     if (!keeps_m(ctx)) return fail(ctx, GA_ERR_STATE, "diagnostics: m is not maintained in this mode (enable gap tracking)");
-    const float bc = ctx->k == 0 ? 0.0f : bias_correction(ctx->beta, ctx->k);
-    hipError_t e = ga::launch_diagnostics(ctx->st, ctx->N, worker_id, bc, ctx->k == 0, ctx->eta_max, ctx->eps,
-                                          ctx->dev_partials, ctx->stream);
+    hipError_t e = ga::launch_diagnostics(ctx->st, ctx->N, worker_id, inverse_bias_correction(ctx->beta, ctx->k),
+                                          ctx->eta_max, ctx->eps, ctx->dev_partials, ctx->stream);
     if (e != hipSuccess) return hip_fail(ctx, e, "diagnostics launch");
     ga::DiagPartial total;
     e = hipMemcpyAsync(&total, ctx->dev_partials + ga::kDiagMaxBlocks, sizeof total, hipMemcpyDeviceToHost, ctx->stream);

@@ -16,12 +16,11 @@ struct StepConst {
     float gamma;           // momentum coefficient
     float lr;              // eta_k, or eta_k / tau_k (Alg. 3)
     float tau;             // (float) tau_k
-    float bc_prev;         // (float)(1 - beta^(k-1))
+    float inv_bc_prev;     // (float)(1 / (1 - beta^(k-1))), 0 at k = 1
     float eta_max;         // Alg. 14
     float eps;             // Alg. 14
     float beta;            // Alg. 14
     float one_minus_beta;  // 1.0f - beta
-    int first;             // k == 1: m-hat is taken as 0
 };
 
 // Scalars that are uniform over a whole schedule chunk.
@@ -66,7 +65,7 @@ hipError_t launch_quadratic_gradient(const StatePtrs& st, uint64_t N, uint32_t w
                                      hipStream_t stream);
 
 // Gap statistics of one worker: per-block partials, then a fixed-order total in partials[kDiagMaxBlocks].
-hipError_t launch_diagnostics(const StatePtrs& st, uint64_t N, uint32_t worker, float bc, int first, float eta_max,
+hipError_t launch_diagnostics(const StatePtrs& st, uint64_t N, uint32_t worker, float inv_bc, float eta_max,
                               float eps, DiagPartial* dev_partials, hipStream_t stream);
 
 hipError_t launch_noise_fill(uint64_t seed, uint64_t k, uint64_t j0, uint64_t n, float* out, hipStream_t stream);

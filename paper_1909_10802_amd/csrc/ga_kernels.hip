@@ -56,11 +56,7 @@ __device__ __forceinline__ void update_one(float& th, float& v, float& m, float 
     if constexpr (MODE == GA_MODE_GA || MODE == GA_MODE_GA_HINGE) {
         const float diff = th - s;
         const float delta = fabsf(diff);
-        // k = 1: m-hat is taken as 0.  Uniform selects and a mask instead of a branch, so
-        // that the divisions of a thread's parameters stay in one straight-line block.
-        const float bc = c.first ? 1.0f : c.bc_prev;
-        const uint32_t keep = c.first ? 0u : 0xFFFFFFFFu;
-        const float mhat = __uint_as_float(__float_as_uint(m / bc) & keep);
+        const float mhat = m * c.inv_bc_prev;
         const float root = sqrtf(mhat);
         const float sum = root + c.eps;
         const float C = c.eta_max * sum;
@@ -368,7 +364,7 @@ __global__ __launch_bounds__(kBlock) void persistent_kernel(float* __restrict__ 
             s_next = snap_q[(uint64_t)next.worker * stride4];
         }
         const uint64_t k = k0 + t + 1;
-        c.lr = row.lr; c.tau = row.tau; c.bc_prev = row.bc_prev; c.first = (k == 1);
+        c.lr = row.lr; c.tau = row.tau; c.inv_bc_prev = row.inv_bc_prev;
         const f32x4 z = noise4(rc.seed_lo, rc.seed_hi, q, k);
 
         f32x4 g;
@@ -399,13 +395,11 @@ struct DiagAcc {
     uint32_t gt1, gt0, bad;
 };
 
-__device__ __forceinline__ void diag_one(DiagAcc& acc, float th, float s, float m, float bc, int first,
-                                         float eta_max, float eps) {
+__device__ __forceinline__ void diag_one(DiagAcc& acc, float th, float s, float m, float inv_bc, float eta_max,
+                                         float eps) {
     const float diff = th - s;
     const float delta = fabsf(diff);
-    const float bc1 = first ? 1.0f : bc;
-    const uint32_t keep = first ? 0u : 0xFFFFFFFFu;
-    const float mhat = __uint_as_float(__float_as_uint(m / bc1) & keep);
+    const float mhat = m * inv_bc;
     const float root = sqrtf(mhat);
     const float sum = root + eps;
     const float C = eta_max * sum;
@@ -449,8 +443,8 @@ __device__ __forceinline__ DiagPartial block_reduce(double sum, unsigned long lo
 }
 
 __global__ __launch_bounds__(kBlock) void diag_kernel(const float* __restrict__ theta, const float* __restrict__ m,
-                                                      const float* __restrict__ snap, uint64_t N, float bc,
-                                                      int first, float eta_max, float eps,
+                                                      const float* __restrict__ snap, uint64_t N, float inv_bc,
+                                                      float eta_max, float eps,
                                                       DiagPartial* __restrict__ partials) {
     const uint64_t n4 = N >> 2;
     DiagAcc acc = {0.0, 0u, 0u, 0u};
@@ -458,14 +452,14 @@ __global__ __launch_bounds__(kBlock) void diag_kernel(const float* __restrict__ 
         const f32x4 th = reinterpret_cast<const f32x4*>(theta)[q];
         const f32x4 s = reinterpret_cast<const f32x4*>(snap)[q];
         const f32x4 mm = reinterpret_cast<const f32x4*>(m)[q];
-        diag_one(acc, th.x, s.x, mm.x, bc, first, eta_max, eps);
-        diag_one(acc, th.y, s.y, mm.y, bc, first, eta_max, eps);
-        diag_one(acc, th.z, s.z, mm.z, bc, first, eta_max, eps);
-        diag_one(acc, th.w, s.w, mm.w, bc, first, eta_max, eps);
+        diag_one(acc, th.x, s.x, mm.x, inv_bc, eta_max, eps);
+        diag_one(acc, th.y, s.y, mm.y, inv_bc, eta_max, eps);
+        diag_one(acc, th.z, s.z, mm.z, inv_bc, eta_max, eps);
+        diag_one(acc, th.w, s.w, mm.w, inv_bc, eta_max, eps);
     }
     if (blockIdx.x == 0 && threadIdx.x < (N & 3)) {
         const uint64_t j = 4 * n4 + threadIdx.x;
-        diag_one(acc, theta[j], snap[j], m[j], bc, first, eta_max, eps);
+        diag_one(acc, theta[j], snap[j], m[j], inv_bc, eta_max, eps);
     }
     const DiagPartial r = block_reduce(acc.sum, acc.gt1, acc.gt0, acc.bad);
     if (threadIdx.x == 0) partials[blockIdx.x] = r;
@@ -613,11 +607,11 @@ hipError_t launch_quadratic_gradient(const StatePtrs& st, uint64_t N, uint32_t w
     return hipGetLastError();
 }
 
-hipError_t launch_diagnostics(const StatePtrs& st, uint64_t N, uint32_t worker, float bc, int first, float eta_max,
+hipError_t launch_diagnostics(const StatePtrs& st, uint64_t N, uint32_t worker, float inv_bc, float eta_max,
                               float eps, DiagPartial* dev_partials, hipStream_t stream) {
     const uint32_t grid = blocks_for(N >> 2, (uint64_t)kBlock * 4, kDiagMaxBlocks);
     hipLaunchKernelGGL(diag_kernel, dim3(grid), dim3(kBlock), 0, stream, st.theta, st.m,
-                       st.snaps + (uint64_t)worker * st.stride, N, bc, first, eta_max, eps, dev_partials);
+                       st.snaps + (uint64_t)worker * st.stride, N, inv_bc, eta_max, eps, dev_partials);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(diag_final_kernel, dim3(1), dim3(kBlock), 0, stream, dev_partials, grid,

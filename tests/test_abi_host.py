@@ -69,8 +69,10 @@ def test_arrival_rows(mode):
     lr = eta / tau_o.astype(np.float32) if mode == ga.GA_MODE_SA_STEP else np.full(T, eta)
     assert np.array_equal(rows["lr"], lr.astype(np.float32))
     k = np.arange(1, T + 1)
-    bc = (1.0 - np.float64(beta) ** (k - 1).astype(np.float64)).astype(np.float32)
-    assert np.array_equal(rows["bc_prev"], bc) and rows["bc_prev"][0] == 0.0
+    with np.errstate(divide="ignore"):
+        inv = (1.0 / (1.0 - np.float64(beta) ** (k - 1).astype(np.float64))).astype(np.float32)
+    inv[0] = 0.0                                        # before the first arrival m-hat is taken as 0
+    assert np.array_equal(rows["inv_bc_prev"], inv)
     # continuing from step 200 gives the same rows as the tail of the full plan
     it2 = oracle.delays(W, sched[:200])[1]
     rows2 = ga.ga_plan_arrivals(W, sched[200:], 200, it2, mode, float(eta), float(beta))

@@ -174,7 +174,7 @@ def test_first_step_coefficient():
 @pytest.mark.parametrize("dtype", [np.float32, np.float64])
 def test_dyadic_one_step_example(dtype):
     # Alg. 4 + Alg. 14 on numbers that are exact in binary, worked by hand:
-    # beta = 1/2, k = 2: 1 - beta^(k-1) = 1/2.  m_1 = 1/32 -> m-hat = 1/16 -> sqrt = 1/4;
+    # beta = 1/2, k = 2: 1/(1 - beta^(k-1)) = 2.  m_1 = 1/32 -> m-hat = 1/16 -> sqrt = 1/4;
     # eps = 0, eta_max = 1/2 -> C = 1/8.  theta = 1, theta^i = 1/2 -> |diff| = 1/2 -> Graw = 4.
     # Paper: G = 5, g = 10 -> g/G = 2;  v' = 1/2 * 1/4 + 2 = 2.125;  eta_k = 1/4 -> theta' = 1 - 0.53125.
     # m' = 1/2 * 1/32 + 1/2 * 2.125^2 = 2.2734375.
