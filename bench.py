@@ -24,6 +24,14 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+ALU_PEAK_TLOPS = 78.65         # fp32 vector 157.3 TFLOP/s / 2 flop per lane-operation
+# VALU lane-operations per parameter-update of the persistent kernel (SQ_INSTS_VALU * 64 / updates, profiles/)
+VALU_PER_UPDATE = {"ga": 115.0, "ga_hinge": 115.0}
+# HBM-side bytes per fused-update launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE scaled by a copy of
+# known size; profiles/apply_kernel_cfg3.md), valid for the kernel source with this hash only
+TRAFFIC = {
+    ("cfg3", "ga"): {"bytes": 919973346, "read": 511051700, "written": 408921646, "kernels_sha256": "7be5cb9943c58d2d"},
+}
 BYTES_PER_UPDATE = {           # algorithmic bytes per parameter per arrival, fused update
     ("ga", "f32"): 36, ("ga", "bf16"): 34, ("ga_hinge", "f32"): 36, ("ga_hinge", "bf16"): 34,
     ("asgd", "f32"): 20, ("sa", "f32"): 20, ("sa_step", "f32"): 20,
@@ -34,9 +42,9 @@ BYTES_PER_UPDATE = {           # algorithmic bytes per parameter per arrival, fu
 def parse():
     p = argparse.ArgumentParser()
     p.add_argument("--gpus", type=int, default=1)
-    p.add_argument("--steps", type=int, default=2000)
+    p.add_argument("--steps", type=int, default=None, help="arrivals to time (default: the workload's own count)")
     p.add_argument("--warmup", type=int, default=100)
-    p.add_argument("--workload", default="cfg3", choices=["cfg3", "cfg5"])
+    p.add_argument("--workload", default="cfg3", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
     p.add_argument("--mode", default="ga", choices=["ga", "ga_hinge", "sa", "sa_step", "asgd"])
     p.add_argument("--diag-every", type=int, default=250, help="Gap statistics every this many arrivals (0: never)")
     p.add_argument("--no-cpu-baseline", action="store_true")
@@ -73,31 +81,22 @@ def cpu_baseline(cfg, mode, n_slice, n_steps):
                       "gradient recipe (%.1f s)" % (n_slice, W, n_steps - 8, dt)}
 
 
-def main():
-    args = parse()
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on one GPU only (the master update shards by parameter range with no "
-              "exchange; see DESIGN.md). Run with --gpus 1.", file=sys.stderr)
-        sys.exit(2)
+def kernels_hash():
+    import hashlib
+    path = os.path.join(ROOT, "paper_1909_10802_amd", "csrc", "ga_kernels.hip")
+    return hashlib.sha256(open(path, "rb").read()).hexdigest()[:16]
 
-    import numpy as np
-    import torch
 
-    import ga_inputs
-    import paper_1909_10802_amd as ga
-
-    cfg = dict(ga_inputs.WORKLOADS[args.workload])
+def bench_fused(args, cfg, torch, ga, ga_inputs):
+    """Workloads with precomputed gradient buffers: one fused-update launch per arrival."""
     N, W, seed = cfg["N"], cfg["W"], cfg["seed"]
     dev = "cuda:0"
-    torch.cuda.set_device(0)
     K, Wm = args.steps, args.warmup
-
     bufs = ga_inputs.device_gradient_buffers(cfg["n_bufs"], N, seed, cfg["grad_std"], cfg["grad_dtype"], dev)
     src = ga.buffer_source(bufs, ga.GA_PICK_BY_WORKER if cfg["pick"] == "worker" else ga.GA_PICK_BY_ARRIVAL)
     sched = ga.ga_simulate_schedule(W, K + Wm + 1, ga_inputs.DIST_CODES[cfg["dist"]], cfg["sigma"], seed)
     M = ga.Master(N, W, eta=cfg["eta"], gamma=cfg["gamma"], mode=args.mode, device=dev,
                   track_gap=(args.diag_every > 0))
-
     M.run_schedule(sched[:Wm], src)
     if args.diag_every > 0:
         M.diagnostics(int(sched[0]))
@@ -129,35 +128,120 @@ def main():
     theta = M.theta()
     finite = bool(torch.isfinite(theta).all().item())
     if args.calibration_copy:
-        dst = torch.empty_like(bufs[0], dtype=torch.float32) if bufs[0].dtype != torch.float32 else torch.empty_like(bufs[0])
-        src_t = theta if theta.numel() == dst.numel() else theta[:dst.numel()]
+        dst = torch.empty(N, dtype=torch.float32, device=dev)
         for _ in range(3):
-            dst.copy_(src_t)
+            dst.copy_(theta)
         torch.cuda.synchronize()
+    t = TRAFFIC.get((args.workload, args.mode))
+    traffic = t["bytes"] if t and t["kernels_sha256"] == kernels_hash() else None
+    roof = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+            "traffic": traffic, "kernel": "apply_kernel", "bytes_per_update": bpu, "avg_launch_ms": kernel_ms,
+            "algorithmic_bytes_per_launch": bpu * N}
+    desc = ("%s: N=%d float parameters, %d workers, %s iteration times, %d %s gradient buffers picked by %s, one "
+            "fused-update launch per arrival, mode %s" % (args.workload, N, W, cfg["dist"], cfg["n_bufs"],
+                                                          cfg["grad_dtype"], cfg["pick"], args.mode))
+    extra = {"hbm_pct_of_peak": 100.0 * achieved / HBM_PEAK_GBS, "theta_finite": finite,
+             "mean_gap_last": None if last_diag is None else last_diag["mean_graw"] + 1.0}
+    return wall, roof, desc, extra
 
+
+def bench_persistent(args, cfg, torch, ga, ga_inputs):
+    """Workloads with the in-kernel quadratic-plus-noise source: the persistent multi-arrival kernel."""
+    N, W, seed = cfg["N"], cfg["W"], cfg["seed"]
+    dev = "cuda:0"
+    K, Wm = args.steps, args.warmup
+    a, ts = ga_inputs.device_curvatures(N, seed, dev), ga_inputs.device_optimum(N, seed, dev)
+    src = ga.quadratic_source(a, ts, seed, 0.01, persistent=True)
+    sched = ga.ga_simulate_schedule(W, K + Wm + 1, ga_inputs.DIST_CODES[cfg["dist"]], cfg["sigma"], seed)
+    M = ga.Master(N, W, eta=cfg["eta"], gamma=cfg["gamma"], mode=args.mode, device=dev)
+    M.run_schedule(sched[:Wm], src)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    M.run_schedule(sched[Wm:Wm + K], src)
+    e1.record()
+    last_diag = M.diagnostics(int(sched[Wm + K])) if args.mode in ("ga", "ga_hinge") else None
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    kernel_s = e0.elapsed_time(e1) * 1e-3                            # all chunks of the schedule
+    ups = N * K / kernel_s
+    if args.mode in VALU_PER_UPDATE:
+        ach = ups * VALU_PER_UPDATE[args.mode] / 1e12
+        roof = {"bound": "alu", "achieved": ach, "peak": ALU_PEAK_TLOPS, "unit": "T lane-op/s",
+                "frac": ach / ALU_PEAK_TLOPS, "traffic": None, "kernel": "persistent_kernel",
+                "valu_ops_per_update": VALU_PER_UPDATE[args.mode], "hbm_GBs_at_8B_per_update": 8 * ups / 1e9}
+    else:
+        ach = 8 * ups / 1e9
+        roof = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
+                "traffic": None, "kernel": "persistent_kernel", "bytes_per_update": 8}
+    roof["kernel_ms_total"] = kernel_s * 1e3
+    theta = M.theta()
+    desc = ("%s: N=%d float parameters, %d workers, %s iteration times, quadratic-plus-noise gradients generated in "
+            "the persistent multi-arrival kernel, mode %s" % (args.workload, N, W, cfg["dist"], args.mode))
+    extra = {"theta_finite": bool(torch.isfinite(theta).all().item()),
+             "mean_gap_last": None if last_diag is None else last_diag["mean_graw"] + 1.0}
+    return wall, roof, desc, extra
+
+
+def cpu_baseline_quadratic(cfg, mode, n_slice, n_steps):
+    """Oracle on a contiguous slice of a quadratic-source workload (it generates the noise itself)."""
+    import ga_inputs
+    import oracle
+    W, seed = cfg["W"], cfg["seed"]
+    n_slice = min(n_slice, cfg["N"], 1 << 20)
+    n_steps = min(n_steps, cfg["T"], 400)
+    a, ts = ga_inputs.curvatures(n_slice, seed), ga_inputs.optimum(n_slice, seed)
+    sched = oracle.simulate_schedule(W, n_steps, ga_inputs.DIST_CODES[cfg["dist"]], cfg["sigma"], seed)
+    modes = dict(ga=oracle.MODE_GA, ga_hinge=oracle.MODE_GA_HINGE, sa=oracle.MODE_SA, sa_step=oracle.MODE_SA_STEP,
+                 asgd=oracle.MODE_ASGD)
+    O = oracle.Master(n_slice, W, modes[mode], oracle.Hyper(cfg["eta"], cfg["gamma"]))
+    O.run_quadratic(sched[:8], a, ts, seed)
+    t0 = time.perf_counter()
+    O.run_quadratic(sched[8:], a, ts, seed)
+    dt = time.perf_counter() - t0
+    return {"value": float(n_slice) * (n_steps - 8) / dt / 1e9, "unit": "G param-updates/s",
+            "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": "first %d parameters, all %d workers, %d arrivals of the same schedule (%.1f s)"
+                      % (n_slice, W, n_steps - 8, dt)}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (the master update shards by parameter range with no "
+              "exchange; see DESIGN.md). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import ga_inputs
+    import paper_1909_10802_amd as ga
+
+    cfg = dict(ga_inputs.WORKLOADS[args.workload])
+    if args.steps is None:
+        args.steps = cfg["T"]
+    torch.cuda.set_device(0)
+    fused = cfg["source"] == "buffers"
+    wall, roof, desc, extra = (bench_fused if fused else bench_persistent)(args, cfg, torch, ga, ga_inputs)
+    N, K = cfg["N"], args.steps
     out = {
         "metric": "G param-updates/s and achieved HBM GB/s (% of peak), GA fused update",
         "value": N * K / wall / 1e9,
         "unit": "G param-updates/s",
-        "n_gpus": 1, "steps": K, "warmup": Wm,
+        "n_gpus": 1, "steps": K, "warmup": args.warmup,
         "ms_per_step": wall / K * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "%s: N=%d float parameters, %d workers, %s iteration times, %d %s gradient buffers "
-                               "picked by %s, one fused-update launch per arrival, mode %s"
-                               % (args.workload, N, W, cfg["dist"], cfg["n_bufs"], cfg["grad_dtype"], cfg["pick"],
-                                  args.mode),
-                   "N": N, "n_workers": W, "mode": args.mode, "grad_dtype": cfg["grad_dtype"],
-                   "eta": cfg["eta"], "gamma": cfg["gamma"], "diag_every": args.diag_every, "seed": seed},
-        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                     "kernel": "apply_kernel", "bytes_per_update": bpu, "avg_launch_ms": kernel_ms},
-        "hbm_pct_of_peak": 100.0 * achieved / HBM_PEAK_GBS,
-        "theta_finite": finite,
-        "mean_gap_last": None if last_diag is None else last_diag["mean_graw"] + 1.0,
+        "config": {"workload": desc, "N": N, "n_workers": cfg["W"], "mode": args.mode,
+                   "grad_dtype": cfg["grad_dtype"], "eta": cfg["eta"], "gamma": cfg["gamma"],
+                   "diag_every": args.diag_every if fused else None, "seed": cfg["seed"]},
+        "roofline": roof,
     }
+    out.update(extra)
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg, args.mode, args.cpu_slice, args.cpu_steps)
+        out["cpu_baseline"] = (cpu_baseline if fused else cpu_baseline_quadratic)(cfg, args.mode, args.cpu_slice,
+                                                                                  args.cpu_steps)
     print(json.dumps(out))
 
 
