@@ -61,6 +61,9 @@ def _declare(L):
     hyp = [_f64] * 5
     for sfx in ("f32", "f64"):
         getattr(L, "orc_step_" + sfx).argtypes = [_u64, _p, _p, _p, _p, _p, _int, _u64, _u64, *hyp, _int]
+        getattr(L, "orc_dana_step_" + sfx).argtypes = [_u64, _p, _p, _p, _p, _p, _p, _int, _u64, _u64, *hyp, _int]
+        getattr(L, "orc_adam_step_" + sfx).argtypes = [_u64, _p, _p, _p, _p, _p, _p, _int, _u64, _u64,
+                                                       _f64, _f64, _f64, _f64, _f64, _f64, _f64, _int]
         getattr(L, "orc_quadratic_gradient_" + sfx).argtypes = [_u64, _p, _p, _p, _p, _p, _u64, _u64, _f64]
         getattr(L, "orc_gap_statistics_" + sfx).argtypes = [_u64, _p, _p, _p, _u64, _f64, _f64, _f64, _p, _p, _p, _p]
         getattr(L, "orc_run_quadratic_" + sfx).argtypes = [
@@ -246,6 +249,83 @@ class Master:
 
     def gap_statistics(self, worker):
         return gap_statistics(self.theta, self.m, self.snaps[worker], self.k, self.hyper)
+
+
+class DanaMaster:
+    """DANA / DANA-SA / DANA-GA master (Alg. 6-8): per-worker momenta v^i, their running sum,
+    look-ahead snapshots.  The arrival loop is driven from Python, one oracle step per arrival."""
+
+    def __init__(self, N, W, mode, hyper, dtype=np.float32, theta0=None, track_gap=False):
+        self.N, self.W, self.mode, self.hyper, self.dtype = N, W, mode, hyper, np.dtype(dtype)
+        self.track_gap = track_gap
+        self.theta = np.zeros(N, dtype) if theta0 is None else np.array(theta0, dtype=dtype)
+        self.vw = np.zeros((W, N), dtype)                # v^i
+        self.vsum = np.zeros(N, dtype)                   # sum_j v^j
+        self.m = np.zeros(N, dtype)
+        self.snaps = np.tile(self.theta, (W, 1))         # theta^i = theta_0
+        self.iter = np.zeros(W, dtype=np.uint64)
+        self.k = 0
+        self.tau_log = []
+
+    def apply(self, worker, g):
+        self.k += 1
+        tau = self.k - int(self.iter[worker])
+        g = np.ascontiguousarray(g, dtype=self.dtype)
+        getattr(lib(), "orc_dana_step_" + _sfx(self.dtype))(
+            self.N, _ptr(self.theta), _ptr(self.vw[worker]), _ptr(self.vsum), _ptr(self.m), _ptr(self.snaps[worker]),
+            _ptr(_chk(g, self.dtype, self.N)), self.mode, self.k, tau, *self.hyper.args(), int(self.track_gap))
+        self.iter[worker] = self.k
+        self.tau_log.append(tau)
+        return tau
+
+    def run_quadratic(self, schedule, a, theta_star, seed, sigma=0.01, idx=None):
+        for w in schedule:
+            w = int(w)
+            self.apply(w, quadratic_gradient(self.snaps[w], a, theta_star, seed, self.k + 1, sigma, idx))
+
+    def run_buffers(self, schedule, bufs, pick_by_worker=True):
+        for w in schedule:
+            w = int(w)
+            self.apply(w, bufs[w % len(bufs)] if pick_by_worker else bufs[self.k % len(bufs)])
+
+    def gap_statistics(self, worker):
+        return gap_statistics(self.theta, self.m, self.snaps[worker], self.k, self.hyper)
+
+
+class AdamMaster:
+    """Adam / Adam-SA / Adam-GA master (Alg. 9-11).  c is the Alg. 14 state of the update vector."""
+
+    def __init__(self, N, W, mode, hyper, dtype=np.float32, theta0=None, track_gap=False, beta1=0.9, beta2=0.999,
+                 adam_eps=1e-8):
+        self.N, self.W, self.mode, self.hyper, self.dtype = N, W, mode, hyper, np.dtype(dtype)
+        self.track_gap = track_gap
+        r = (lambda x: float(np.float32(x))) if self.dtype == np.float32 else float
+        self.beta1, self.beta2, self.adam_eps = r(beta1), r(beta2), r(adam_eps)
+        self.theta = np.zeros(N, dtype) if theta0 is None else np.array(theta0, dtype=dtype)
+        self.m1 = np.zeros(N, dtype)
+        self.v2 = np.zeros(N, dtype)
+        self.m = np.zeros(N, dtype)                      # Alg. 14 state (called c in the C++ file)
+        self.snaps = np.tile(self.theta, (W, 1))
+        self.iter = np.zeros(W, dtype=np.uint64)
+        self.k = 0
+        self.tau_log = []
+
+    def apply(self, worker, g):
+        self.k += 1
+        tau = self.k - int(self.iter[worker])
+        g = np.ascontiguousarray(g, dtype=self.dtype)
+        h = self.hyper
+        getattr(lib(), "orc_adam_step_" + _sfx(self.dtype))(
+            self.N, _ptr(self.theta), _ptr(self.m1), _ptr(self.v2), _ptr(self.m), _ptr(self.snaps[worker]),
+            _ptr(_chk(g, self.dtype, self.N)), self.mode, self.k, tau, h.eta_k, h.eta_max, h.beta, h.eps,
+            self.beta1, self.beta2, self.adam_eps, int(self.track_gap))
+        self.iter[worker] = self.k
+        self.tau_log.append(tau)
+        return tau
+
+    run_quadratic = DanaMaster.run_quadratic
+    run_buffers = DanaMaster.run_buffers
+    gap_statistics = DanaMaster.gap_statistics
 
 
 def num_threads():

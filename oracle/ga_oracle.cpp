@@ -11,6 +11,8 @@
 //   * Gap-Aware master, parameter-wise Gap         -- Alg. 4, Eq. 5 (Sec. 4.3)
 //   * Staleness-Aware-Gradient master              -- Alg. 5 (App. C.1)
 //   * C coefficient                                -- Alg. 14 (App. C.6)
+//   * DANA / DANA-SA / DANA-GA masters             -- Alg. 6, 7, 8 (App. C.1)
+//   * Adam / Adam-SA / Adam-GA masters             -- Alg. 9, 10, 11 (App. C.1)
 //   * master is a FIFO over worker arrivals        -- App. C.1
 // plus two pieces that are not in the paper and are defined by this project's
 // synthetic workloads: the counter-based noise generator used by the
@@ -28,7 +30,9 @@
 // of Sec. 3.1; constant-gradient closed form for C and the Gap (Gap = delay
 // when all updates point the same way, remark after Def. 1); scaling
 // invariance of the Gap; schedule closed forms (round robin, mean delay = W
-// for exponential times).
+// for exponential times); DANA with one worker against a matrix-power closed
+// form and with gamma = 0 against the momentum master; Adam with one worker
+// against torch.optim.Adam; Adam-SA / Adam-GA steady-state step eta/tau.
 // Parity unpinned: the hinge penalty max(1, |d|/C) is this project's variant,
 // pinned only by its definition (equals the paper's form with "+1" replaced).
 
@@ -333,6 +337,123 @@ void master_step(uint64_t n, R* theta, R* v, R* m, R* snap_i, const R* g, int mo
     }
 }
 
+// ---------------------------------------------------------------------------
+// Penalty shared by the three families: the factor the gradient is divided by.
+//   GA modes: G from the parameter-wise Gap (Eq. 5) with C_{k-1} (Alg. 14)
+//   SA:       tau_k                              (Alg. 5 / 7 / 10)
+//   else:     1
+// ---------------------------------------------------------------------------
+template <typename R>
+R penalty(int mode, R theta, R snap, R c_state, R inv_bc_prev, R tau_r, R eta_max, R eps) {
+    if (mode == MODE_GA || mode == MODE_GA_HINGE) {
+        const R diff = theta - snap;
+        const R delta = std::fabs(diff);
+        const R C = coefficient_C<R>(c_state, inv_bc_prev, eta_max, eps);
+        const R g_raw = delta / C;
+        return (mode == MODE_GA) ? (R)1 + g_raw : std::fmax((R)1, g_raw);
+    }
+    if (mode == MODE_SA) return tau_r;
+    return (R)1;
+}
+
+// DANA masters (Alg. 6 / 7 / 8): one momentum vector per worker, v^i; the
+// master steps with the arriving worker's momentum and hands the worker a
+// look-ahead estimate theta - eta*gamma*sum_j v^j.  vsum = sum_j v^j is kept
+// incrementally.  m is the Alg. 14 state, fed with the step actually taken (v^i).
+template <typename R>
+void dana_step(uint64_t n, R* theta, R* v_i, R* vsum, R* m, R* snap_i, const R* g, int mode, uint64_t k,
+               uint64_t tau, const Hyper<R>& h, int track_gap) {
+    const bool gap_mode = (mode == MODE_GA || mode == MODE_GA_HINGE);
+    const bool keep_m = gap_mode || track_gap;
+    const R inv_bc_prev = inverse_bias_correction<R>(h.beta, k - 1);
+    const R one_minus_beta = (R)1 - h.beta;
+    const R tau_r = (R)tau;
+    const R eta_gamma = h.eta_k * h.gamma;
+#pragma omp parallel for schedule(static)
+    for (int64_t jj = 0; jj < (int64_t)n; ++jj) {
+        const uint64_t j = (uint64_t)jj;
+        R g_hat = g[j];
+        if (gap_mode || mode == MODE_SA) {
+            const R G = penalty<R>(mode, theta[j], snap_i[j], m[j], inv_bc_prev, tau_r, h.eta_max, h.eps);
+            g_hat = g[j] / G;
+        }
+        const R v_old = v_i[j];
+        const R gv = h.gamma * v_old;
+        const R v_new = gv + g_hat;                 // v^i <- gamma v^i + g / G
+        const R step = h.eta_k * v_new;
+        const R theta_new = theta[j] - step;        // theta_{k+1} <- theta_k - eta v^i
+        const R less = vsum[j] - v_old;
+        const R sum_new = less + v_new;             // sum_j v^j with the new v^i
+        v_i[j] = v_new;
+        theta[j] = theta_new;
+        vsum[j] = sum_new;
+        if (keep_m) {
+            const R bm = h.beta * m[j];
+            const R vv = v_new * v_new;
+            const R add = one_minus_beta * vv;
+            m[j] = bm + add;
+        }
+        const R ahead = eta_gamma * sum_new;
+        snap_i[j] = theta_new - ahead;              // theta^i <- theta_{k+1} - eta gamma sum_j v^j
+    }
+}
+
+template <typename R>
+struct AdamHyper {
+    R beta1, beta2, eps;
+};
+
+// Adam masters (Alg. 9 / 10 / 11).  The penalty goes on the first moment only
+// (App. C.1): m1 <- beta1 m1 + ((1-beta1)/G) g ; v2 <- beta2 v2 + (1-beta2) g^2.
+// u = m1-hat / (sqrt(v2-hat) + eps) is the update vector; theta <- theta - eta_k u.
+// The Alg. 14 state c follows u (the step the parameters actually take).
+template <typename R>
+void adam_step(uint64_t n, R* theta, R* m1, R* v2, R* c, R* snap_i, const R* g, int mode, uint64_t k,
+               uint64_t tau, const Hyper<R>& h, const AdamHyper<R>& ah, int track_gap) {
+    const bool gap_mode = (mode == MODE_GA || mode == MODE_GA_HINGE);
+    const bool keep_c = gap_mode || track_gap;
+    const R inv_bc_prev = inverse_bias_correction<R>(h.beta, k - 1);
+    const R one_minus_beta = (R)1 - h.beta;
+    const R omb1 = (R)1 - ah.beta1;
+    const R omb2 = (R)1 - ah.beta2;
+    const R inv_bc1 = inverse_bias_correction<R>(ah.beta1, k);
+    const R inv_bc2 = inverse_bias_correction<R>(ah.beta2, k);
+    const R tau_r = (R)tau;
+#pragma omp parallel for schedule(static)
+    for (int64_t jj = 0; jj < (int64_t)n; ++jj) {
+        const uint64_t j = (uint64_t)jj;
+        R coef = omb1;
+        if (gap_mode || mode == MODE_SA) {
+            const R G = penalty<R>(mode, theta[j], snap_i[j], c[j], inv_bc_prev, tau_r, h.eta_max, h.eps);
+            coef = omb1 / G;                        // (1 - beta1) / G_k
+        }
+        const R b1m = ah.beta1 * m1[j];
+        const R cg = coef * g[j];
+        const R m1_new = b1m + cg;
+        const R b2v = ah.beta2 * v2[j];
+        const R gg = g[j] * g[j];
+        const R add2 = omb2 * gg;
+        const R v2_new = b2v + add2;
+        const R m1_hat = m1_new * inv_bc1;
+        const R v2_hat = v2_new * inv_bc2;
+        const R root = std::sqrt(v2_hat);
+        const R den = root + ah.eps;
+        const R u = m1_hat / den;
+        const R step = h.eta_k * u;
+        const R theta_new = theta[j] - step;
+        m1[j] = m1_new;
+        v2[j] = v2_new;
+        theta[j] = theta_new;
+        if (keep_c) {
+            const R bc = h.beta * c[j];
+            const R uu = u * u;
+            const R add = one_minus_beta * uu;
+            c[j] = bc + add;
+        }
+        snap_i[j] = theta_new;
+    }
+}
+
 // Quadratic-plus-noise worker gradient (synthetic stand-in for Alg. 1): the
 // worker holds theta_w = snap_i and returns
 //   g = a * (theta_w - theta_star) + sigma * z(seed, k, j).
@@ -505,6 +626,33 @@ void orc_step_f64(uint64_t n, double* theta, double* v, double* m, double* snap_
                   double beta, double eps, int track_gap) {
     master_step<double>(n, theta, v, m, snap_i, g, mode, k, tau,
                         make_hyper<double>(eta_k, eta_max, gamma, beta, eps), track_gap);
+}
+
+void orc_dana_step_f32(uint64_t n, float* theta, float* v_i, float* vsum, float* m, float* snap_i,
+                       const float* g, int mode, uint64_t k, uint64_t tau, double eta_k, double eta_max,
+                       double gamma, double beta, double eps, int track_gap) {
+    dana_step<float>(n, theta, v_i, vsum, m, snap_i, g, mode, k, tau,
+                     make_hyper<float>(eta_k, eta_max, gamma, beta, eps), track_gap);
+}
+void orc_dana_step_f64(uint64_t n, double* theta, double* v_i, double* vsum, double* m, double* snap_i,
+                       const double* g, int mode, uint64_t k, uint64_t tau, double eta_k, double eta_max,
+                       double gamma, double beta, double eps, int track_gap) {
+    dana_step<double>(n, theta, v_i, vsum, m, snap_i, g, mode, k, tau,
+                      make_hyper<double>(eta_k, eta_max, gamma, beta, eps), track_gap);
+}
+void orc_adam_step_f32(uint64_t n, float* theta, float* m1, float* v2, float* c, float* snap_i,
+                       const float* g, int mode, uint64_t k, uint64_t tau, double eta_k, double eta_max,
+                       double beta, double eps, double beta1, double beta2, double adam_eps, int track_gap) {
+    AdamHyper<float> ah = {(float)beta1, (float)beta2, (float)adam_eps};
+    adam_step<float>(n, theta, m1, v2, c, snap_i, g, mode, k, tau,
+                     make_hyper<float>(eta_k, eta_max, 0.0, beta, eps), ah, track_gap);
+}
+void orc_adam_step_f64(uint64_t n, double* theta, double* m1, double* v2, double* c, double* snap_i,
+                       const double* g, int mode, uint64_t k, uint64_t tau, double eta_k, double eta_max,
+                       double beta, double eps, double beta1, double beta2, double adam_eps, int track_gap) {
+    AdamHyper<double> ah = {beta1, beta2, adam_eps};
+    adam_step<double>(n, theta, m1, v2, c, snap_i, g, mode, k, tau,
+                      make_hyper<double>(eta_k, eta_max, 0.0, beta, eps), ah, track_gap);
 }
 
 void orc_quadratic_gradient_f32(uint64_t n, float* g, const float* snap_i, const float* a,
