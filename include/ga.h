@@ -68,7 +68,38 @@ enum ga_mode {
     GA_MODE_GA_HINGE = 4  /* variant: gradient divided by max(1, |diff|/C) */
 };
 
+/* Which master algorithm family the context runs.  The penalty mode applies
+ * inside each family:
+ *   MOMENTUM: Alg. 2 (ASGD), Alg. 5 (SA), Alg. 3 (SA_STEP), Alg. 4 (GA, GA_HINGE)
+ *   DANA:     Alg. 6 (ASGD), Alg. 7 (SA), Alg. 8 (GA, GA_HINGE)
+ *   ADAM:     Alg. 9 (ASGD), Alg. 10 (SA), Alg. 11 (GA, GA_HINGE)
+ * GA_MODE_SA_STEP exists for MOMENTUM only.
+ *
+ * DANA, per parameter (v_i = momentum of the arriving worker, vsum = sum_j v_j):
+ *   ghat = g / G (GA modes, G as in the header comment) | g / tau (SA) | g
+ *   vnew = gamma * v_i + ghat ;  theta = theta - eta_k * vnew
+ *   vsum = (vsum - v_i) + vnew ;  v_i = vnew
+ *   m    = beta * m + (1 - beta) * (vnew * vnew)             (Alg. 14 on the step taken)
+ *   snap_i = theta - (eta_k * gamma) * vsum                   (look-ahead estimate sent to the worker)
+ * ADAM, per parameter (m1, v2 = Adam moments; m = Alg. 14 state of the update vector u):
+ *   coef = (1 - beta1) / G (GA modes) | (1 - beta1) / tau (SA) | (1 - beta1)
+ *   m1 = beta1 * m1 + coef * g ;  v2 = beta2 * v2 + (1 - beta2) * (g * g)
+ *   u  = (m1 * ib1) / (sqrt(v2 * ib2) + adam_eps),  ib = (float)(1 / (1 - beta^k)) in double
+ *   theta = theta - eta_k * u ;  m = beta * m + (1 - beta) * (u * u) ;  snap_i = theta
+ */
+enum ga_family { GA_FAMILY_MOMENTUM = 0, GA_FAMILY_DANA = 1, GA_FAMILY_ADAM = 2 };
+
 enum ga_dtype { GA_F32 = 0, GA_BF16 = 1 };
+
+/* Device arrays of a context, for ga_get_array / ga_put_array. */
+enum ga_array {
+    GA_ARR_THETA = 0,
+    GA_ARR_V = 1,         /* MOMENTUM: v;  DANA: vsum;  ADAM: m1 */
+    GA_ARR_M = 2,         /* Alg. 14 state */
+    GA_ARR_SNAPSHOT = 3,  /* per worker */
+    GA_ARR_WORKER_V = 4,  /* DANA only, per worker: v_i */
+    GA_ARR_ADAM_V2 = 5    /* ADAM only */
+};
 
 enum ga_status {
     GA_OK = 0,
@@ -98,8 +129,8 @@ enum ga_pick { GA_PICK_BY_WORKER = 0, GA_PICK_BY_ARRIVAL = 1 };
  *       g = a[j] * (theta_w[j] - theta_star[j]) + sigma * z(seed, k, j)
  *   with z the counter-based standard normal documented at ga_noise_fill.
  *   dev_a and dev_theta_star are device arrays of N floats, 16-byte aligned.
- *   persistent != 0: all arrivals are replayed inside one kernel per chunk of
- *   the schedule (no per-arrival launch); persistent == 0: one gradient launch
+ *   persistent != 0 (MOMENTUM family only): all arrivals are replayed inside
+ *   one kernel per chunk of the schedule (no per-arrival launch); persistent == 0: one gradient launch
  *   and one update launch per arrival, through dev_scratch_g (N floats,
  *   16-byte aligned device buffer, required in that case only).
  *
@@ -143,8 +174,27 @@ typedef struct ga_arrival {
     float inv_bc_prev; /* (float)(1 / (1 - beta^(k-1))); 0 when k = 1 */
 } ga_arrival;
 
+/* Full configuration of a master, for ga_create_ex.  Fill with ga_config_init
+ * first, then change what differs. */
+typedef struct ga_config {
+    uint64_t N;
+    uint32_t n_workers;
+    int family;      /* ga_family, default GA_FAMILY_MOMENTUM */
+    int mode;        /* ga_mode, default GA_MODE_GA */
+    float eta;       /* eta_k = eta_max, default 0.1 */
+    float gamma;     /* momentum coefficient, |gamma| < 1, default 0.9; ignored by ADAM */
+    float beta;      /* Alg. 14 decay, default 0.999 */
+    float eps;       /* Alg. 14 epsilon, default 1e-8 */
+    float adam_beta1, adam_beta2, adam_eps; /* Alg. 9-11, defaults 0.9, 0.999, 1e-8 */
+    int track_gap;   /* maintain m and snapshots in the non-GA modes too */
+} ga_config;
+
 /* ------------------------------------------------------------------ host only
- * These three touch no device and need no context. */
+ * These touch no device and need no context. */
+
+/* Defaults listed at ga_config (N and n_workers are set to 0). */
+void ga_config_init(ga_config* cfg);
+
 
 /* Arrival order of n_workers simulated workers (App. C.1: FIFO master).  All
  * workers start at time 0; worker w's n-th iteration takes a time drawn from
@@ -183,6 +233,13 @@ size_t ga_workspace_bytes(uint64_t N, uint32_t n_workers);
  * GA_ERR_ALIGN for a misaligned or short workspace. */
 int ga_create(ga_ctx** out, uint64_t N, uint32_t n_workers, float eta, float gamma, int mode,
               void* dev_workspace, size_t workspace_bytes, void* hip_stream);
+
+/* The same for any family.  ga_create(N, W, eta, gamma, mode, ...) is
+ * ga_create_ex with the other fields at their defaults.  Extra errors:
+ * GA_ERR_ARG for an unknown family, GA_MODE_SA_STEP outside MOMENTUM, Adam
+ * betas outside [0,1) or adam_eps <= 0. */
+size_t ga_workspace_bytes_ex(const ga_config* cfg);
+int ga_create_ex(ga_ctx** out, const ga_config* cfg, void* dev_workspace, size_t workspace_bytes, void* hip_stream);
 
 void ga_destroy(ga_ctx* ctx);
 
@@ -235,6 +292,11 @@ int ga_put_theta(ga_ctx* ctx, const float* dev_src);
 int ga_put_v(ga_ctx* ctx, const float* dev_src);
 int ga_put_m(ga_ctx* ctx, const float* dev_src);
 int ga_put_snapshot(ga_ctx* ctx, uint32_t worker_id, const float* dev_src);
+
+/* Generic access to any state array (N floats; worker_id is used by the
+ * per-worker arrays only).  GA_ERR_ARG if the family does not have the array. */
+int ga_get_array(ga_ctx* ctx, int which, uint32_t worker_id, float* dev_dst);
+int ga_put_array(ga_ctx* ctx, int which, uint32_t worker_id, const float* dev_src);
 
 /* Host bookkeeping: current step k; iter[W]; the delays of all arrivals so far
  * (at most max_n are written, the total count goes to n_out). */

@@ -16,12 +16,15 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libga.so")
 
 GA_MODE_ASGD, GA_MODE_SA, GA_MODE_SA_STEP, GA_MODE_GA, GA_MODE_GA_HINGE = range(5)
+GA_FAMILY_MOMENTUM, GA_FAMILY_DANA, GA_FAMILY_ADAM = range(3)
+GA_ARR_THETA, GA_ARR_V, GA_ARR_M, GA_ARR_SNAPSHOT, GA_ARR_WORKER_V, GA_ARR_ADAM_V2 = range(6)
 GA_F32, GA_BF16 = 0, 1
 GA_OK, GA_ERR_ARG, GA_ERR_WORKER, GA_ERR_ALIGN, GA_ERR_STATE, GA_ERR_HIP = 0, -1, -2, -3, -4, -5
 GA_DIST_EXP, GA_DIST_LOGNORMAL, GA_DIST_HETERO = range(3)
 GA_SRC_QUADRATIC_NOISE, GA_SRC_BUFFERS = 0, 1
 GA_PICK_BY_WORKER, GA_PICK_BY_ARRIVAL = 0, 1
 
+FAMILIES = {"momentum": GA_FAMILY_MOMENTUM, "dana": GA_FAMILY_DANA, "adam": GA_FAMILY_ADAM}
 MODES = {"asgd": GA_MODE_ASGD, "sa": GA_MODE_SA, "sa_step": GA_MODE_SA_STEP, "ga": GA_MODE_GA,
          "ga_hinge": GA_MODE_GA_HINGE}
 
@@ -44,6 +47,13 @@ class ga_diag(C.Structure):
                 ("n_nonfinite", C.c_uint64)]
 
 
+class ga_config(C.Structure):
+    _fields_ = [("N", C.c_uint64), ("n_workers", C.c_uint32), ("family", C.c_int), ("mode", C.c_int),
+                ("eta", C.c_float), ("gamma", C.c_float), ("beta", C.c_float), ("eps", C.c_float),
+                ("adam_beta1", C.c_float), ("adam_beta2", C.c_float), ("adam_eps", C.c_float),
+                ("track_gap", C.c_int)]
+
+
 class ga_arrival(C.Structure):
     _fields_ = [("worker", C.c_uint32), ("tau", C.c_float), ("lr", C.c_float), ("inv_bc_prev", C.c_float)]
 
@@ -57,7 +67,12 @@ SIGNATURES = {
     "ga_simulate_schedule": (_i, [_u32, _u64, _i, _d, _u64, _p]),
     "ga_delays_from_schedule": (_i, [_u32, _u64, _p, _u64, _p, _p]),
     "ga_plan_arrivals": (_i, [_u32, _u64, _p, _u64, _p, _i, _f, _f, _p]),
+    "ga_config_init": (None, [C.POINTER(ga_config)]),
     "ga_workspace_bytes": (C.c_size_t, [_u64, _u32]),
+    "ga_workspace_bytes_ex": (C.c_size_t, [C.POINTER(ga_config)]),
+    "ga_create_ex": (_i, [C.POINTER(_p), C.POINTER(ga_config), _p, C.c_size_t, _p]),
+    "ga_get_array": (_i, [_p, _i, _u32, _p]),
+    "ga_put_array": (_i, [_p, _i, _u32, _p]),
     "ga_create": (_i, [C.POINTER(_p), _u64, _u32, _f, _f, _i, _p, C.c_size_t, _p]),
     "ga_destroy": (None, [_p]),
     "ga_set_beta_eps": (_i, [_p, _f, _f]),
@@ -170,6 +185,39 @@ def ga_create(N, n_workers, eta, gamma, mode, dev_workspace, stream=None):
     _check(lib().ga_create(C.byref(ctx), N, n_workers, eta, gamma, mode, ptr, dev_workspace.numel(),
                            _stream_ptr(stream)))
     return ctx
+
+
+def ga_config_init(**kw):
+    """A ga_config with the library defaults, then the given fields."""
+    cfg = ga_config()
+    lib().ga_config_init(C.byref(cfg))
+    for k, v in kw.items():
+        assert hasattr(cfg, k), k
+        setattr(cfg, k, v)
+    return cfg
+
+
+def ga_workspace_bytes_ex(cfg):
+    return lib().ga_workspace_bytes_ex(C.byref(cfg))
+
+
+def ga_create_ex(cfg, dev_workspace, stream=None):
+    import torch
+    ctx = _p()
+    ptr = _dev(dev_workspace, torch.uint8)
+    _check(lib().ga_create_ex(C.byref(ctx), C.byref(cfg), ptr, dev_workspace.numel(), _stream_ptr(stream)))
+    return ctx
+
+
+def ga_get_array(ctx, which, worker_id, dev_dst):
+    import torch
+    _check(lib().ga_get_array(ctx, which, worker_id, _dev(dev_dst, torch.float32)), ctx)
+    return dev_dst
+
+
+def ga_put_array(ctx, which, worker_id, dev_src):
+    import torch
+    _check(lib().ga_put_array(ctx, which, worker_id, _dev(dev_src, torch.float32)), ctx)
 
 
 def ga_destroy(ctx):
@@ -314,24 +362,30 @@ class Master:
     """One master context plus the torch tensors it borrows (workspace)."""
 
     def __init__(self, N, n_workers, eta=0.1, gamma=0.9, mode=GA_MODE_GA, device="cuda:0", stream=None,
-                 beta=None, eps=None, eta_max=None, track_gap=False, theta0=None):
+                 beta=None, eps=None, eta_max=None, track_gap=False, theta0=None, family=GA_FAMILY_MOMENTUM,
+                 adam_beta1=0.9, adam_beta2=0.999, adam_eps=1e-8):
         import torch
         self.N, self.W, self.mode = N, n_workers, MODES.get(mode, mode)
+        self.family = FAMILIES.get(family, family)
         self.device = torch.device(device)
+        cfg = ga_config_init(N=N, n_workers=n_workers, family=self.family, mode=self.mode, eta=eta, gamma=gamma,
+                             adam_beta1=adam_beta1, adam_beta2=adam_beta2, adam_eps=adam_eps,
+                             track_gap=int(track_gap))
+        if beta is not None:
+            cfg.beta = beta
+        if eps is not None:
+            cfg.eps = eps
+        self.ctx = None
         with torch.cuda.device(self.device):
-            self.workspace = torch.empty(ga_workspace_bytes(N, n_workers), dtype=torch.uint8, device=self.device)
-            self.ctx = ga_create(N, n_workers, eta, gamma, self.mode, self.workspace, stream)
-        if beta is not None or eps is not None:
-            ga_set_beta_eps(self.ctx, 0.999 if beta is None else beta, 1e-8 if eps is None else eps)
+            self.workspace = torch.empty(ga_workspace_bytes_ex(cfg), dtype=torch.uint8, device=self.device)
+            self.ctx = ga_create_ex(cfg, self.workspace, stream)
         if eta_max is not None:
             ga_set_eta_max(self.ctx, eta_max)
-        if track_gap:
-            ga_set_track_gap(self.ctx, True)
         if theta0 is not None:
             ga_set_theta(self.ctx, theta0)
 
     def close(self):
-        if self.ctx is not None:
+        if getattr(self, "ctx", None) is not None:
             ga_destroy(self.ctx)
             self.ctx = None
 
@@ -365,6 +419,9 @@ class Master:
 
     def snapshot(self, w):
         return ga_get_snapshot(self.ctx, w, self._new())
+
+    def array(self, which, worker_id=0):
+        return ga_get_array(self.ctx, which, worker_id, self._new())
 
     @property
     def k(self):

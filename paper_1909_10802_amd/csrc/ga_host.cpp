@@ -18,8 +18,10 @@
 struct ga_ctx {
     uint64_t N = 0;
     uint32_t W = 0;
+    int family = GA_FAMILY_MOMENTUM;
     int mode = GA_MODE_GA;
     float eta_max = 0.f, lr = 0.f, gamma = 0.f, beta = 0.999f, eps = 1e-8f;
+    float beta1 = 0.9f, beta2 = 0.999f, adam_eps = 1e-8f;
     bool track_gap = false;
     hipStream_t stream = nullptr;
     ga::StatePtrs st{};
@@ -56,11 +58,12 @@ bool valid_mode(int mode) { return mode >= GA_MODE_ASGD && mode <= GA_MODE_GA_HI
 uint64_t round_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
 
 struct Layout {
-    uint64_t Np;
-    size_t off_theta, off_v, off_m, off_snaps, off_table, off_partials, total;
+    uint64_t Np, n_rows;
+    size_t off_theta, off_v, off_m, off_snaps, off_worker_v, off_v2, off_table, off_partials, total;
 };
 
-Layout layout_for(uint64_t N, uint32_t W) {
+// theta | v | m | W snapshots | [DANA: W worker momenta] | [ADAM: v2] | arrival table | reduction partials
+Layout layout_for(uint64_t N, uint32_t W, int family) {
     Layout L;
     L.Np = round_up(N, 64);                  // every array starts 256-byte aligned
     const size_t row = (size_t)L.Np * sizeof(float);
@@ -68,7 +71,16 @@ Layout layout_for(uint64_t N, uint32_t W) {
     L.off_v = row;
     L.off_m = 2 * row;
     L.off_snaps = 3 * row;
-    L.off_table = L.off_snaps + (size_t)W * row;
+    L.n_rows = 3 + (uint64_t)W;
+    L.off_worker_v = L.off_v2 = 0;
+    if (family == GA_FAMILY_DANA) {
+        L.off_worker_v = L.n_rows * row;
+        L.n_rows += W;
+    } else if (family == GA_FAMILY_ADAM) {
+        L.off_v2 = L.n_rows * row;
+        L.n_rows += 1;
+    }
+    L.off_table = L.n_rows * row;
     L.off_partials = L.off_table + round_up((uint64_t)ga::kTableCap * sizeof(ga_arrival), 256);
     L.total = L.off_partials + round_up((uint64_t)(ga::kDiagMaxBlocks + 1) * sizeof(ga::DiagPartial), 256);
     return L;
@@ -159,8 +171,8 @@ void plan(uint64_t T, const uint32_t* schedule, uint64_t k0, uint64_t* iter, int
     }
 }
 
-ga::StepConst step_const(const ga_ctx* c, const ga_arrival& r) {
-    ga::StepConst s;
+ga::StepConst step_const(const ga_ctx* c, const ga_arrival& r, uint64_t k) {
+    ga::StepConst s = {};
     s.gamma = c->gamma;
     s.lr = r.lr;
     s.tau = r.tau;
@@ -169,6 +181,16 @@ ga::StepConst step_const(const ga_ctx* c, const ga_arrival& r) {
     s.eps = c->eps;
     s.beta = c->beta;
     s.one_minus_beta = 1.0f - c->beta;
+    s.eta_gamma = r.lr * c->gamma;
+    if (c->family == GA_FAMILY_ADAM) {
+        s.beta1 = c->beta1;
+        s.omb1 = 1.0f - c->beta1;
+        s.beta2 = c->beta2;
+        s.omb2 = 1.0f - c->beta2;
+        s.adam_eps = c->adam_eps;
+        s.inv_bc1 = inverse_bias_correction(c->beta1, k);
+        s.inv_bc2 = inverse_bias_correction(c->beta2, k);
+    }
     return s;
 }
 
@@ -200,8 +222,14 @@ int apply_one(ga_ctx* ctx, uint32_t worker, const void* dev_grad, int dtype, boo
     const uint64_t k = ctx->k + 1;
     const uint64_t tau = k - ctx->iter[worker];
     const ga_arrival row = make_row(worker, k, tau, ctx->mode, ctx->lr, ctx->beta);
-    const hipError_t e = ga::launch_apply(ctx->st, ctx->N, worker, dev_grad, dtype, ctx->mode, keeps_m(ctx),
-                                          write_snap, step_const(ctx, row), ctx->stream);
+    const ga::StepConst sc = step_const(ctx, row, k);
+    hipError_t e;
+    if (ctx->family == GA_FAMILY_DANA)
+        e = ga::launch_apply_dana(ctx->st, ctx->N, worker, dev_grad, dtype, ctx->mode, keeps_m(ctx), write_snap, sc, ctx->stream);
+    else if (ctx->family == GA_FAMILY_ADAM)
+        e = ga::launch_apply_adam(ctx->st, ctx->N, worker, dev_grad, dtype, ctx->mode, keeps_m(ctx), write_snap, sc, ctx->stream);
+    else
+        e = ga::launch_apply(ctx->st, ctx->N, worker, dev_grad, dtype, ctx->mode, keeps_m(ctx), write_snap, sc, ctx->stream);
     if (e != hipSuccess) return hip_fail(ctx, e, "apply launch");
     ctx->k = k;
     ctx->iter[worker] = k;
@@ -285,22 +313,56 @@ int ga_plan_arrivals(uint32_t n_workers, uint64_t T, const uint32_t* host_schedu
 }
 
 // ------------------------------------------------------------------ context
-size_t ga_workspace_bytes(uint64_t N, uint32_t n_workers) {
-    if (N == 0 || n_workers == 0) return 0;
-    return layout_for(N, n_workers).total;
+void ga_config_init(ga_config* cfg) {
+    if (!cfg) return;
+    cfg->N = 0;
+    cfg->n_workers = 0;
+    cfg->family = GA_FAMILY_MOMENTUM;
+    cfg->mode = GA_MODE_GA;
+    cfg->eta = 0.1f;
+    cfg->gamma = 0.9f;
+    cfg->beta = 0.999f;
+    cfg->eps = 1e-8f;
+    cfg->adam_beta1 = 0.9f;
+    cfg->adam_beta2 = 0.999f;
+    cfg->adam_eps = 1e-8f;
+    cfg->track_gap = 0;
 }
 
-int ga_create(ga_ctx** out, uint64_t N, uint32_t n_workers, float eta, float gamma, int mode, void* dev_workspace,
-              size_t workspace_bytes, void* hip_stream) {
+size_t ga_workspace_bytes_ex(const ga_config* cfg) {
+    if (!cfg || cfg->N == 0 || cfg->n_workers == 0) return 0;
+    if (cfg->family < GA_FAMILY_MOMENTUM || cfg->family > GA_FAMILY_ADAM) return 0;
+    return layout_for(cfg->N, cfg->n_workers, cfg->family).total;
+}
+
+size_t ga_workspace_bytes(uint64_t N, uint32_t n_workers) {
+    if (N == 0 || n_workers == 0) return 0;
+    return layout_for(N, n_workers, GA_FAMILY_MOMENTUM).total;
+}
+
+int ga_create_ex(ga_ctx** out, const ga_config* cfg, void* dev_workspace, size_t workspace_bytes, void* hip_stream) {
     if (!out) return fail(nullptr, GA_ERR_ARG, "create: out is null");
     *out = nullptr;
+    if (!cfg) return fail(nullptr, GA_ERR_ARG, "create: configuration is null");
+    const uint64_t N = cfg->N;
+    const uint32_t n_workers = cfg->n_workers;
     if (N == 0 || n_workers == 0) return fail(nullptr, GA_ERR_ARG, "create: N and n_workers must be positive");
     if (N > (1ull << 40)) return fail(nullptr, GA_ERR_ARG, "create: N too large");
-    if (!(eta > 0.f) || !std::isfinite(eta)) return fail(nullptr, GA_ERR_ARG, "create: eta must be finite and > 0");
-    if (!(std::fabs(gamma) < 1.f)) return fail(nullptr, GA_ERR_ARG, "create: |gamma| must be < 1");
-    if (!valid_mode(mode)) return fail(nullptr, GA_ERR_ARG, "create: unknown mode %d", mode);
+    if (cfg->family < GA_FAMILY_MOMENTUM || cfg->family > GA_FAMILY_ADAM) return fail(nullptr, GA_ERR_ARG, "create: unknown family %d", cfg->family);
+    if (!(cfg->eta > 0.f) || !std::isfinite(cfg->eta)) return fail(nullptr, GA_ERR_ARG, "create: eta must be finite and > 0");
+    if (!(std::fabs(cfg->gamma) < 1.f)) return fail(nullptr, GA_ERR_ARG, "create: |gamma| must be < 1");
+    if (!valid_mode(cfg->mode)) return fail(nullptr, GA_ERR_ARG, "create: unknown mode %d", cfg->mode);
+    if (cfg->mode == GA_MODE_SA_STEP && cfg->family != GA_FAMILY_MOMENTUM)
+        return fail(nullptr, GA_ERR_ARG, "create: GA_MODE_SA_STEP exists for the momentum family only");
+    if (!(cfg->beta >= 0.f && cfg->beta < 1.f)) return fail(nullptr, GA_ERR_ARG, "create: beta must be in [0,1)");
+    if (!(cfg->eps > 0.f) || !std::isfinite(cfg->eps)) return fail(nullptr, GA_ERR_ARG, "create: eps must be finite and > 0");
+    if (cfg->family == GA_FAMILY_ADAM) {
+        if (!(cfg->adam_beta1 >= 0.f && cfg->adam_beta1 < 1.f) || !(cfg->adam_beta2 >= 0.f && cfg->adam_beta2 < 1.f))
+            return fail(nullptr, GA_ERR_ARG, "create: Adam betas must be in [0,1)");
+        if (!(cfg->adam_eps > 0.f) || !std::isfinite(cfg->adam_eps)) return fail(nullptr, GA_ERR_ARG, "create: adam_eps must be finite and > 0");
+    }
     if (!dev_workspace) return fail(nullptr, GA_ERR_ARG, "create: workspace is null");
-    const Layout L = layout_for(N, n_workers);
+    const Layout L = layout_for(N, n_workers, cfg->family);
     if (((uintptr_t)dev_workspace & 255u) != 0) return fail(nullptr, GA_ERR_ALIGN, "create: workspace must be 256-byte aligned");
     if (workspace_bytes < L.total)
         return fail(nullptr, GA_ERR_ALIGN, "create: workspace has %zu bytes, %zu needed", workspace_bytes, L.total);
@@ -309,23 +371,32 @@ int ga_create(ga_ctx** out, uint64_t N, uint32_t n_workers, float eta, float gam
     if (!c) return fail(nullptr, GA_ERR_ARG, "create: out of host memory");
     c->N = N;
     c->W = n_workers;
-    c->mode = mode;
-    c->eta_max = c->lr = eta;
-    c->gamma = gamma;
+    c->family = cfg->family;
+    c->mode = cfg->mode;
+    c->eta_max = c->lr = cfg->eta;
+    c->gamma = cfg->family == GA_FAMILY_ADAM ? 0.0f : cfg->gamma;
+    c->beta = cfg->beta;
+    c->eps = cfg->eps;
+    c->beta1 = cfg->adam_beta1;
+    c->beta2 = cfg->adam_beta2;
+    c->adam_eps = cfg->adam_eps;
+    c->track_gap = cfg->track_gap != 0;
     c->stream = static_cast<hipStream_t>(hip_stream);
     char* base = static_cast<char*>(dev_workspace);
     c->st.theta = reinterpret_cast<float*>(base + L.off_theta);
     c->st.v = reinterpret_cast<float*>(base + L.off_v);
     c->st.m = reinterpret_cast<float*>(base + L.off_m);
     c->st.snaps = reinterpret_cast<float*>(base + L.off_snaps);
+    c->st.worker_v = L.off_worker_v ? reinterpret_cast<float*>(base + L.off_worker_v) : nullptr;
+    c->st.v2 = L.off_v2 ? reinterpret_cast<float*>(base + L.off_v2) : nullptr;
     c->st.stride = L.Np;
     c->dev_table = reinterpret_cast<ga_arrival*>(base + L.off_table);
     c->dev_partials = reinterpret_cast<ga::DiagPartial*>(base + L.off_partials);
     c->iter.assign(n_workers, 0);
     c->rows.reserve(ga::kTableCap);
 
-    // theta, v, m and all snapshots are contiguous: one fill
-    const hipError_t e = ga::launch_fill(c->st.theta, (3 + (uint64_t)n_workers) * L.Np, 0.0f, c->stream);
+    // all state rows are contiguous: one fill
+    const hipError_t e = ga::launch_fill(c->st.theta, L.n_rows * L.Np, 0.0f, c->stream);
     if (e != hipSuccess) {
         const int rc = hip_fail(nullptr, e, "create: initial fill");
         delete c;
@@ -333,6 +404,18 @@ int ga_create(ga_ctx** out, uint64_t N, uint32_t n_workers, float eta, float gam
     }
     *out = c;
     return GA_OK;
+}
+
+int ga_create(ga_ctx** out, uint64_t N, uint32_t n_workers, float eta, float gamma, int mode, void* dev_workspace,
+              size_t workspace_bytes, void* hip_stream) {
+    ga_config cfg;
+    ga_config_init(&cfg);
+    cfg.N = N;
+    cfg.n_workers = n_workers;
+    cfg.eta = eta;
+    cfg.gamma = gamma;
+    cfg.mode = mode;
+    return ga_create_ex(out, &cfg, dev_workspace, workspace_bytes, hip_stream);
 }
 
 void ga_destroy(ga_ctx* ctx) { delete ctx; }
@@ -417,6 +500,9 @@ int ga_run_schedule(ga_ctx* ctx, const uint32_t* host_schedule, uint64_t T, cons
     int rc = check_quadratic_source(ctx, src);
     if (rc != GA_OK) return rc;
     const ga::RunConst rcst = run_const(ctx, src);
+
+    if (src->persistent && ctx->family != GA_FAMILY_MOMENTUM)
+        return fail(ctx, GA_ERR_ARG, "run_schedule: the persistent kernel exists for the momentum family only");
 
     if (!src->persistent) {
         // one gradient launch and one update launch per arrival; the worker reads its snapshot,
@@ -504,6 +590,44 @@ int ga_put_snapshot(ga_ctx* ctx, uint32_t worker_id, const float* dev_src) {
     if (!ctx) return GA_ERR_ARG;
     if (worker_id >= ctx->W) return fail(ctx, GA_ERR_WORKER, "put_snapshot: worker %u >= n_workers %u", worker_id, ctx->W);
     return copy_in(ctx, ctx->st.snaps + (uint64_t)worker_id * ctx->st.stride, dev_src);
+}
+
+static float* array_of(ga_ctx* ctx, int which, uint32_t worker_id, int* status) {
+    *status = GA_OK;
+    const bool per_worker = (which == GA_ARR_SNAPSHOT || which == GA_ARR_WORKER_V);
+    if (per_worker && worker_id >= ctx->W) {
+        *status = fail(ctx, GA_ERR_WORKER, "array access: worker %u >= n_workers %u", worker_id, ctx->W);
+        return nullptr;
+    }
+    switch (which) {
+        case GA_ARR_THETA: return ctx->st.theta;
+        case GA_ARR_V: return ctx->st.v;
+        case GA_ARR_M: return ctx->st.m;
+        case GA_ARR_SNAPSHOT: return ctx->st.snaps + (uint64_t)worker_id * ctx->st.stride;
+        case GA_ARR_WORKER_V:
+            if (ctx->st.worker_v) return ctx->st.worker_v + (uint64_t)worker_id * ctx->st.stride;
+            break;
+        case GA_ARR_ADAM_V2:
+            if (ctx->st.v2) return ctx->st.v2;
+            break;
+        default: break;
+    }
+    *status = fail(ctx, GA_ERR_ARG, "array access: this context has no array %d", which);
+    return nullptr;
+}
+
+int ga_get_array(ga_ctx* ctx, int which, uint32_t worker_id, float* dev_dst) {
+    if (!ctx) return GA_ERR_ARG;
+    int rc;
+    float* p = array_of(ctx, which, worker_id, &rc);
+    return p ? copy_out(ctx, dev_dst, p) : rc;
+}
+
+int ga_put_array(ga_ctx* ctx, int which, uint32_t worker_id, const float* dev_src) {
+    if (!ctx) return GA_ERR_ARG;
+    int rc;
+    float* p = array_of(ctx, which, worker_id, &rc);
+    return p ? copy_in(ctx, p, dev_src) : rc;
 }
 
 uint64_t ga_step(const ga_ctx* ctx) { return ctx ? ctx->k : 0; }

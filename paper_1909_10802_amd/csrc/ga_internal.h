@@ -21,6 +21,10 @@ struct StepConst {
     float eps;             // Alg. 14
     float beta;            // Alg. 14
     float one_minus_beta;  // 1.0f - beta
+    float eta_gamma;       // DANA: eta_k * gamma (float product)
+    // ADAM (Alg. 9-11)
+    float beta1, omb1, beta2, omb2, adam_eps;
+    float inv_bc1, inv_bc2;  // (float)(1 / (1 - beta1^k)), (float)(1 / (1 - beta2^k))
 };
 
 // Scalars that are uniform over a whole schedule chunk.
@@ -42,16 +46,24 @@ constexpr uint32_t kDiagMaxBlocks = 2048;  // partials in the workspace
 // State pointers inside the workspace.  snaps is W rows of `stride` floats.
 struct StatePtrs {
     float* theta;
-    float* v;
+    float* v;         // MOMENTUM: v;  DANA: vsum;  ADAM: m1
     float* m;
     float* snaps;
-    uint64_t stride;  // floats between consecutive workers' snapshots (N rounded up to 64)
+    float* worker_v;  // DANA: W rows of v_i, else null
+    float* v2;        // ADAM: second moment, else null
+    uint64_t stride;  // floats between consecutive workers' rows (N rounded up to 64)
 };
 
 // Fused update of one arrival.  g: N values of grad_dtype.  In the GA modes m
 // and the snapshot are always maintained; elsewhere keep_m / write_snap decide.
 hipError_t launch_apply(const StatePtrs& st, uint64_t N, uint32_t worker, const void* g, int grad_dtype, int mode,
                         bool keep_m, bool write_snap, const StepConst& c, hipStream_t stream);
+
+// DANA (Alg. 6-8) and Adam (Alg. 9-11) fused updates of one arrival; mode is ASGD, SA, GA or GA_HINGE.
+hipError_t launch_apply_dana(const StatePtrs& st, uint64_t N, uint32_t worker, const void* g, int grad_dtype, int mode,
+                             bool keep_m, bool write_snap, const StepConst& c, hipStream_t stream);
+hipError_t launch_apply_adam(const StatePtrs& st, uint64_t N, uint32_t worker, const void* g, int grad_dtype, int mode,
+                             bool keep_m, bool write_snap, const StepConst& c, hipStream_t stream);
 
 // T arrivals replayed inside one launch, gradients generated in the kernel.
 // table: device array of T rows; k0: master step before the first row.

@@ -1,6 +1,7 @@
 // gfx950 kernels of the Gap-Aware master update.
 //
 //   apply_kernel        one arrival, gradient from HBM (Alg. 2-5 + Alg. 14 fused)
+//   family_apply_kernel the same for the DANA (Alg. 6-8) and Adam (Alg. 9-11) masters
 //   persistent_kernel   a chunk of arrivals per launch; every thread owns four
 //                       parameters for the whole chunk and generates the
 //                       quadratic-plus-noise gradients itself
@@ -50,34 +51,94 @@ __device__ __forceinline__ void store4(float* __restrict__ base, uint64_t q, con
 // ---------------------------------------------------------------------------
 // One parameter, one arrival.
 // ---------------------------------------------------------------------------
-template <int MODE, bool KEEP_M>
-__device__ __forceinline__ void update_one(float& th, float& v, float& m, float s, float g, const StepConst& c) {
-    float ghat = g;
+// The factor the gradient is divided by: the Gap G (Eq. 5, with C from the Alg. 14 state
+// as arrival k-1 left it), the delay (Alg. 5 / 7 / 10), or 1.
+template <int MODE>
+__device__ __forceinline__ float penalty_of(float th, float s, float cstate, const StepConst& c) {
     if constexpr (MODE == GA_MODE_GA || MODE == GA_MODE_GA_HINGE) {
         const float diff = th - s;
         const float delta = fabsf(diff);
-        const float mhat = m * c.inv_bc_prev;
+        const float mhat = cstate * c.inv_bc_prev;
         const float root = sqrtf(mhat);
         const float sum = root + c.eps;
         const float C = c.eta_max * sum;
         const float graw = delta / C;
-        const float G = (MODE == GA_MODE_GA) ? 1.0f + graw : fmaxf(1.0f, graw);
-        ghat = g / G;
+        return (MODE == GA_MODE_GA) ? 1.0f + graw : fmaxf(1.0f, graw);
     } else if constexpr (MODE == GA_MODE_SA) {
-        ghat = g / c.tau;
+        return c.tau;
+    } else {
+        return 1.0f;
     }
+}
+
+// Alg. 14: m <- beta m + (1 - beta) x^2
+__device__ __forceinline__ float second_moment(float m, float x, const StepConst& c) {
+    const float bm = c.beta * m;
+    const float xx = x * x;
+    const float add = c.one_minus_beta * xx;
+    return bm + add;
+}
+
+// MOMENTUM family (Alg. 2-5), one parameter, one arrival.
+template <int MODE, bool KEEP_M>
+__device__ __forceinline__ void update_one(float& th, float& v, float& m, float s, float g, const StepConst& c) {
+    float ghat = g;
+    if constexpr (MODE != GA_MODE_ASGD) ghat = g / penalty_of<MODE>(th, s, m, c);
     const float gv = c.gamma * v;
     const float vn = gv + ghat;
     const float step = c.lr * vn;
     const float tn = th - step;
     v = vn;
     th = tn;
-    if constexpr (KEEP_M) {
-        const float bm = c.beta * m;
-        const float vv = vn * vn;
-        const float add = c.one_minus_beta * vv;
-        m = bm + add;
-    }
+    if constexpr (KEEP_M) m = second_moment(m, vn, c);
+}
+
+// DANA family (Alg. 6-8).  x = sum_j v_j, y = v_i of the arriving worker; returns the look-ahead snapshot.
+template <int MODE, bool KEEP_M>
+__device__ __forceinline__ float dana_one(float& th, float& x, float& y, float& m, float s, float g,
+                                          const StepConst& c) {
+    float ghat = g;
+    if constexpr (MODE != GA_MODE_ASGD) ghat = g / penalty_of<MODE>(th, s, m, c);
+    const float v_old = y;
+    const float gv = c.gamma * v_old;
+    const float vn = gv + ghat;
+    const float step = c.lr * vn;
+    const float tn = th - step;
+    const float less = x - v_old;
+    const float sn = less + vn;
+    y = vn;
+    th = tn;
+    x = sn;
+    if constexpr (KEEP_M) m = second_moment(m, vn, c);
+    const float ahead = c.eta_gamma * sn;
+    return tn - ahead;
+}
+
+// ADAM family (Alg. 9-11).  x = m1, y = v2; m is the Alg. 14 state of the update vector u.
+template <int MODE, bool KEEP_M>
+__device__ __forceinline__ float adam_one(float& th, float& x, float& y, float& m, float s, float g,
+                                          const StepConst& c) {
+    float coef = c.omb1;
+    if constexpr (MODE != GA_MODE_ASGD) coef = c.omb1 / penalty_of<MODE>(th, s, m, c);
+    const float b1m = c.beta1 * x;
+    const float cg = coef * g;
+    const float m1n = b1m + cg;
+    const float b2v = c.beta2 * y;
+    const float gg = g * g;
+    const float add2 = c.omb2 * gg;
+    const float v2n = b2v + add2;
+    const float m1h = m1n * c.inv_bc1;
+    const float v2h = v2n * c.inv_bc2;
+    const float root = sqrtf(v2h);
+    const float den = root + c.adam_eps;
+    const float u = m1h / den;
+    const float step = c.lr * u;
+    const float tn = th - step;
+    x = m1n;
+    y = v2n;
+    th = tn;
+    if constexpr (KEEP_M) m = second_moment(m, u, c);
+    return tn;
 }
 
 // Four parameters; lanes >= n_valid (padding past N) are left untouched.
@@ -182,6 +243,71 @@ __global__ __launch_bounds__(kBlock) void apply_kernel(float* __restrict__ theta
         v[j] = v1;
         if constexpr (KEEP_M) m[j] = m1;
         if constexpr (SNAP) snap[j] = t1;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Fused update of one arrival for the DANA and ADAM families: the same launch
+// shape as apply_kernel with one more state array.  x: vsum | m1 (touched at
+// every arrival, kept in the memory-side cache when it fits); y: the arriving
+// worker's v_i (streamed) | v2.
+// ---------------------------------------------------------------------------
+template <int FAMILY, int MODE, int DT, bool KEEP_M, bool SNAP, bool ALIGNED, bool STREAM_X, int U>
+__global__ __launch_bounds__(kBlock) void family_apply_kernel(float* __restrict__ theta, float* __restrict__ x,
+                                                              float* __restrict__ y, float* __restrict__ m,
+                                                              float* __restrict__ snap,
+                                                              const void* __restrict__ g, uint64_t N, StepConst c) {
+    constexpr bool GAP = (MODE == GA_MODE_GA || MODE == GA_MODE_GA_HINGE);
+    const uint64_t n4 = N >> 2;
+    const uint64_t base = (uint64_t)blockIdx.x * (kBlock * U) + threadIdx.x;
+
+    f32x4 th[U], xx[U], yy[U], mm[U], ss[U], gg[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const uint64_t q = base + (uint64_t)u * kBlock;
+        mm[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+        ss[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (q < n4) {
+            th[u] = load4<false>(theta, q);
+            xx[u] = load4<STREAM_X>(x, q);
+            yy[u] = load4<true>(y, q);
+            if constexpr (KEEP_M) mm[u] = load4<true>(m, q);
+            if constexpr (GAP) ss[u] = load4<true>(snap, q);
+            gg[u] = load_g4<DT, ALIGNED>(g, q);
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const uint64_t q = base + (uint64_t)u * kBlock;
+        if (q < n4) {
+            f32x4 out;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                float t1 = th[u][e], x1 = xx[u][e], y1 = yy[u][e], m1 = mm[u][e];
+                if constexpr (FAMILY == GA_FAMILY_DANA) out[e] = dana_one<MODE, KEEP_M>(t1, x1, y1, m1, ss[u][e], gg[u][e], c);
+                else out[e] = adam_one<MODE, KEEP_M>(t1, x1, y1, m1, ss[u][e], gg[u][e], c);
+                th[u][e] = t1; xx[u][e] = x1; yy[u][e] = y1; mm[u][e] = m1;
+            }
+            store4<false>(theta, q, th[u]);
+            store4<STREAM_X>(x, q, xx[u]);
+            store4<true>(y, q, yy[u]);
+            if constexpr (KEEP_M) store4<true>(m, q, mm[u]);
+            if constexpr (SNAP) store4<true>(snap, q, out);
+        }
+    }
+
+    if (blockIdx.x == 0 && threadIdx.x < (N & 3)) {
+        const uint64_t j = 4 * n4 + threadIdx.x;
+        float t1 = theta[j], x1 = x[j], y1 = y[j], m1 = 0.0f, s1 = 0.0f, out;
+        if constexpr (KEEP_M) m1 = m[j];
+        if constexpr (GAP) s1 = snap[j];
+        if constexpr (FAMILY == GA_FAMILY_DANA) out = dana_one<MODE, KEEP_M>(t1, x1, y1, m1, s1, load_g1<DT>(g, j), c);
+        else out = adam_one<MODE, KEEP_M>(t1, x1, y1, m1, s1, load_g1<DT>(g, j), c);
+        theta[j] = t1;
+        x[j] = x1;
+        y[j] = y1;
+        if constexpr (KEEP_M) m[j] = m1;
+        if constexpr (SNAP) snap[j] = out;
     }
 }
 
@@ -346,7 +472,7 @@ __global__ __launch_bounds__(kBlock) void persistent_kernel(float* __restrict__ 
         a4.w = 0.f;                            t4.w = 0.f;
     }
 
-    StepConst c;
+    StepConst c = {};
     c.gamma = rc.gamma; c.eta_max = rc.eta_max; c.eps = rc.eps; c.beta = rc.beta;
     c.one_minus_beta = rc.one_minus_beta;
 
@@ -550,7 +676,74 @@ hipError_t launch_apply_opt(const StatePtrs& st, float* snap, const void* g, int
                       : launch_apply_m<MODE, false, false>(st, snap, g, dt, N, c, stream);
 }
 
+// ---------------------------------------------------------------------------
+// Dispatch of the DANA / ADAM kernel.
+// ---------------------------------------------------------------------------
+constexpr int kFamilyU = 1;
+
+template <int FAMILY, int MODE, int DT, bool KEEP_M, bool SNAP, bool ALIGNED>
+hipError_t launch_family_t(float* theta, float* x, float* y, float* m, float* snap, const void* g, uint64_t N,
+                           const StepConst& c, hipStream_t stream) {
+    const uint64_t n4 = N >> 2;
+    const uint64_t per_block = (uint64_t)kBlock * kFamilyU;
+    const uint64_t blocks = (n4 + per_block - 1) / per_block;
+    if (blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    const dim3 grid(blocks == 0 ? 1u : (uint32_t)blocks), block(kBlock);
+    if (N <= kKeepVMaxN)
+        hipLaunchKernelGGL((family_apply_kernel<FAMILY, MODE, DT, KEEP_M, SNAP, ALIGNED, false, kFamilyU>), grid, block,
+                           0, stream, theta, x, y, m, snap, g, N, c);
+    else
+        hipLaunchKernelGGL((family_apply_kernel<FAMILY, MODE, DT, KEEP_M, SNAP, ALIGNED, true, kFamilyU>), grid, block,
+                           0, stream, theta, x, y, m, snap, g, N, c);
+    return hipGetLastError();
+}
+
+template <int FAMILY, int MODE, bool KEEP_M, bool SNAP>
+hipError_t launch_family_m(float* theta, float* x, float* y, float* m, float* snap, const void* g, int dt,
+                           uint64_t N, const StepConst& c, hipStream_t stream) {
+    const uintptr_t addr = reinterpret_cast<uintptr_t>(g);
+    if (dt == GA_F32) {
+        if ((addr & 15u) == 0)
+            return launch_family_t<FAMILY, MODE, GA_F32, KEEP_M, SNAP, true>(theta, x, y, m, snap, g, N, c, stream);
+        return launch_family_t<FAMILY, MODE, GA_F32, KEEP_M, SNAP, false>(theta, x, y, m, snap, g, N, c, stream);
+    }
+    if ((addr & 7u) == 0)
+        return launch_family_t<FAMILY, MODE, GA_BF16, KEEP_M, SNAP, true>(theta, x, y, m, snap, g, N, c, stream);
+    return launch_family_t<FAMILY, MODE, GA_BF16, KEEP_M, SNAP, false>(theta, x, y, m, snap, g, N, c, stream);
+}
+
+template <int FAMILY>
+hipError_t launch_family(float* theta, float* x, float* y, float* m, float* snap, const void* g, int dt, uint64_t N,
+                         int mode, bool keep_m, bool write_snap, const StepConst& c, hipStream_t stream) {
+#define GA_FAM(MODE, KEEP, SNAP) launch_family_m<FAMILY, MODE, KEEP, SNAP>(theta, x, y, m, snap, g, dt, N, c, stream)
+    switch (mode) {
+        case GA_MODE_GA: return GA_FAM(GA_MODE_GA, true, true);
+        case GA_MODE_GA_HINGE: return GA_FAM(GA_MODE_GA_HINGE, true, true);
+        case GA_MODE_SA:
+            if (keep_m) return write_snap ? GA_FAM(GA_MODE_SA, true, true) : GA_FAM(GA_MODE_SA, true, false);
+            return write_snap ? GA_FAM(GA_MODE_SA, false, true) : GA_FAM(GA_MODE_SA, false, false);
+        case GA_MODE_ASGD:
+            if (keep_m) return write_snap ? GA_FAM(GA_MODE_ASGD, true, true) : GA_FAM(GA_MODE_ASGD, true, false);
+            return write_snap ? GA_FAM(GA_MODE_ASGD, false, true) : GA_FAM(GA_MODE_ASGD, false, false);
+        default: return hipErrorInvalidValue;
+    }
+#undef GA_FAM
+}
+
 }  // namespace
+
+hipError_t launch_apply_dana(const StatePtrs& st, uint64_t N, uint32_t worker, const void* g, int grad_dtype, int mode,
+                             bool keep_m, bool write_snap, const StepConst& c, hipStream_t stream) {
+    return launch_family<GA_FAMILY_DANA>(st.theta, st.v, st.worker_v + (uint64_t)worker * st.stride, st.m,
+                                         st.snaps + (uint64_t)worker * st.stride, g, grad_dtype, N, mode, keep_m,
+                                         write_snap, c, stream);
+}
+
+hipError_t launch_apply_adam(const StatePtrs& st, uint64_t N, uint32_t worker, const void* g, int grad_dtype, int mode,
+                             bool keep_m, bool write_snap, const StepConst& c, hipStream_t stream) {
+    return launch_family<GA_FAMILY_ADAM>(st.theta, st.v, st.v2, st.m, st.snaps + (uint64_t)worker * st.stride, g,
+                                         grad_dtype, N, mode, keep_m, write_snap, c, stream);
+}
 
 hipError_t launch_apply(const StatePtrs& st, uint64_t N, uint32_t worker, const void* g, int grad_dtype, int mode,
                         bool keep_m, bool write_snap, const StepConst& c, hipStream_t stream) {
