@@ -45,6 +45,8 @@ def parse():
     p.add_argument("--steps", type=int, default=None, help="arrivals to time (default: the workload's own count)")
     p.add_argument("--warmup", type=int, default=100)
     p.add_argument("--workload", default="cfg3", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+    p.add_argument("--family", default="momentum", choices=["momentum", "dana", "adam"],
+                   help="master algorithm family: Alg. 2-5, Alg. 6-8 or Alg. 9-11")
     p.add_argument("--mode", default="ga", choices=["ga", "ga_hinge", "sa", "sa_step", "asgd"])
     p.add_argument("--diag-every", type=int, default=250, help="Gap statistics every this many arrivals (0: never)")
     p.add_argument("--no-cpu-baseline", action="store_true")
@@ -95,7 +97,8 @@ def bench_fused(args, cfg, torch, ga, ga_inputs):
     bufs = ga_inputs.device_gradient_buffers(cfg["n_bufs"], N, seed, cfg["grad_std"], cfg["grad_dtype"], dev)
     src = ga.buffer_source(bufs, ga.GA_PICK_BY_WORKER if cfg["pick"] == "worker" else ga.GA_PICK_BY_ARRIVAL)
     sched = ga.ga_simulate_schedule(W, K + Wm + 1, ga_inputs.DIST_CODES[cfg["dist"]], cfg["sigma"], seed)
-    M = ga.Master(N, W, eta=cfg["eta"], gamma=cfg["gamma"], mode=args.mode, device=dev,
+    eta = 0.01 if args.family == "adam" else cfg["eta"]
+    M = ga.Master(N, W, eta=eta, gamma=cfg["gamma"], mode=args.mode, device=dev, family=args.family,
                   track_gap=(args.diag_every > 0))
     M.run_schedule(sched[:Wm], src)
     if args.diag_every > 0:
@@ -124,6 +127,8 @@ def bench_fused(args, cfg, torch, ga, ga_inputs):
     bpu = BYTES_PER_UPDATE[(args.mode, cfg["grad_dtype"])]
     if args.mode in ("asgd", "sa", "sa_step") and args.diag_every > 0:
         bpu += 12                                                   # gap tracking: m read + write, snapshot write
+    if args.family != "momentum":
+        bpu += 8                                                    # one more state array read and written
     achieved = bpu * N / (kernel_ms * 1e-3) / 1e9
     theta = M.theta()
     finite = bool(torch.isfinite(theta).all().item())
@@ -135,11 +140,13 @@ def bench_fused(args, cfg, torch, ga, ga_inputs):
     t = TRAFFIC.get((args.workload, args.mode))
     traffic = t["bytes"] if t and t["kernels_sha256"] == kernels_hash() else None
     roof = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-            "traffic": traffic, "kernel": "apply_kernel", "bytes_per_update": bpu, "avg_launch_ms": kernel_ms,
+            "traffic": traffic if args.family == "momentum" else None,
+            "kernel": "apply_kernel" if args.family == "momentum" else "family_apply_kernel", "bytes_per_update": bpu, "avg_launch_ms": kernel_ms,
             "algorithmic_bytes_per_launch": bpu * N}
     desc = ("%s: N=%d float parameters, %d workers, %s iteration times, %d %s gradient buffers picked by %s, one "
-            "fused-update launch per arrival, mode %s" % (args.workload, N, W, cfg["dist"], cfg["n_bufs"],
-                                                          cfg["grad_dtype"], cfg["pick"], args.mode))
+            "fused-update launch per arrival, family %s, mode %s" % (args.workload, N, W, cfg["dist"], cfg["n_bufs"],
+                                                                     cfg["grad_dtype"], cfg["pick"], args.family,
+                                                                     args.mode))
     extra = {"hbm_pct_of_peak": 100.0 * achieved / HBM_PEAK_GBS, "theta_finite": finite,
              "mean_gap_last": None if last_diag is None else last_diag["mean_graw"] + 1.0}
     return wall, roof, desc, extra
@@ -223,6 +230,8 @@ def main():
         args.steps = cfg["T"]
     torch.cuda.set_device(0)
     fused = cfg["source"] == "buffers"
+    if not fused and args.family != "momentum":
+        sys.exit("bench.py: the persistent-kernel workloads exist for the momentum family only")
     wall, roof, desc, extra = (bench_fused if fused else bench_persistent)(args, cfg, torch, ga, ga_inputs)
     N, K = cfg["N"], args.steps
     out = {
@@ -233,7 +242,7 @@ def main():
         "ms_per_step": wall / K * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": desc, "N": N, "n_workers": cfg["W"], "mode": args.mode,
+        "config": {"workload": desc, "N": N, "n_workers": cfg["W"], "family": args.family, "mode": args.mode,
                    "grad_dtype": cfg["grad_dtype"], "eta": cfg["eta"], "gamma": cfg["gamma"],
                    "diag_every": args.diag_every if fused else None, "seed": cfg["seed"]},
         "roofline": roof,
