@@ -64,6 +64,7 @@ def _declare(L):
         getattr(L, "orc_dana_step_" + sfx).argtypes = [_u64, _p, _p, _p, _p, _p, _p, _int, _u64, _u64, *hyp, _int]
         getattr(L, "orc_adam_step_" + sfx).argtypes = [_u64, _p, _p, _p, _p, _p, _p, _int, _u64, _u64,
                                                        _f64, _f64, _f64, _f64, _f64, _f64, _f64, _int]
+        getattr(L, "orc_step_layerwise_" + sfx).argtypes = [_u64, _p, _p, _p, _p, _p, _p, _u32, _int, _u64, *hyp, _p]
         getattr(L, "orc_quadratic_gradient_" + sfx).argtypes = [_u64, _p, _p, _p, _p, _p, _u64, _u64, _f64]
         getattr(L, "orc_gap_statistics_" + sfx).argtypes = [_u64, _p, _p, _p, _u64, _f64, _f64, _f64, _p, _p, _p, _p]
         getattr(L, "orc_run_quadratic_" + sfx).argtypes = [
@@ -249,6 +250,40 @@ class Master:
 
     def gap_statistics(self, worker):
         return gap_statistics(self.theta, self.m, self.snaps[worker], self.k, self.hyper)
+
+
+class LayerwiseMaster(Master):
+    """Gap-Aware master with one Gap per layer (Eq. 4); a single layer gives the global Gap (Def. 1)."""
+
+    def __init__(self, N, W, mode, hyper, layer_sizes=None, dtype=np.float32, theta0=None):
+        super().__init__(N, W, mode, hyper, dtype, theta0)
+        assert mode in (MODE_GA, MODE_GA_HINGE)
+        self.layer_sizes = np.array([N] if layer_sizes is None else layer_sizes, dtype=np.uint64)
+        assert int(self.layer_sizes.sum()) == N
+        self.last_gaps = np.zeros(self.layer_sizes.size, self.dtype)
+
+    def apply(self, worker, g):
+        self.k += 1
+        tau = self.k - int(self.iter[worker])
+        g = np.ascontiguousarray(g, dtype=self.dtype)
+        rc = getattr(lib(), "orc_step_layerwise_" + _sfx(self.dtype))(
+            self.N, _ptr(self.theta), _ptr(self.v), _ptr(self.m), _ptr(self.snaps[worker]),
+            _ptr(_chk(g, self.dtype, self.N)), _ptr(self.layer_sizes), self.layer_sizes.size, self.mode, self.k,
+            *self.hyper.args(), _ptr(self.last_gaps))
+        assert rc == 0
+        self.iter[worker] = self.k
+        self.tau_log.append(tau)
+        return tau
+
+    def run_quadratic(self, schedule, a, theta_star, seed, sigma=0.01, idx=None):
+        for w in schedule:
+            w = int(w)
+            self.apply(w, quadratic_gradient(self.snaps[w], a, theta_star, seed, self.k + 1, sigma, idx))
+
+    def run_buffers(self, schedule, bufs, pick_by_worker=True):
+        for w in schedule:
+            w = int(w)
+            self.apply(w, bufs[w % len(bufs)] if pick_by_worker else bufs[self.k % len(bufs)])
 
 
 class DanaMaster:

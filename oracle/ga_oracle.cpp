@@ -13,6 +13,7 @@
 //   * C coefficient                                -- Alg. 14 (App. C.6)
 //   * DANA / DANA-SA / DANA-GA masters             -- Alg. 6, 7, 8 (App. C.1)
 //   * Adam / Adam-SA / Adam-GA masters             -- Alg. 9, 10, 11 (App. C.1)
+//   * layer-wise and global Gap                    -- Eq. 4 and Def. 1 (Sec. 4.3)
 //   * master is a FIFO over worker arrivals        -- App. C.1
 // plus two pieces that are not in the paper and are defined by this project's
 // synthetic workloads: the counter-based noise generator used by the
@@ -454,6 +455,57 @@ void adam_step(uint64_t n, R* theta, R* m1, R* v2, R* c, R* snap_i, const R* g, 
     }
 }
 
+// ---------------------------------------------------------------------------
+// Layer-wise Gap (Eq. 4) and, with a single layer, the global Gap (Def. 1):
+//   G_p = ||theta_p - theta^i_p|| / C_p + 1,   one penalty per layer p,
+// applied to every gradient element of that layer (Alg. 4 otherwise).
+// C_p = eta_max (sqrt(sum_{j in p} m-hat_j) + eps): the Alg. 14 estimate of
+// E[v_j^2] summed over the layer estimates E||v_p||^2.
+// Norms are accumulated in double and rounded once to R.
+// layer_sizes: P contiguous layers covering the n parameters.  gaps_out (P
+// values, optional) receives G_p.
+// ---------------------------------------------------------------------------
+template <typename R>
+void master_step_layerwise(uint64_t n, R* theta, R* v, R* m, R* snap_i, const R* g, const uint64_t* layer_sizes,
+                           uint32_t P, int mode, uint64_t k, const Hyper<R>& h, R* gaps_out) {
+    const R inv_bc_prev = inverse_bias_correction<R>(h.beta, k - 1);
+    const R one_minus_beta = (R)1 - h.beta;
+    uint64_t start = 0;
+    for (uint32_t p = 0; p < P; ++p) {
+        const uint64_t end = start + layer_sizes[p];
+        double dist2 = 0.0, msum = 0.0;
+        for (uint64_t j = start; j < end; ++j) {
+            const R diff = theta[j] - snap_i[j];
+            dist2 += (double)diff * (double)diff;
+            msum += (double)m[j];
+        }
+        const R delta = (R)std::sqrt(dist2);                 // ||theta_p - theta^i_p||
+        const R m_hat = (R)msum * inv_bc_prev;
+        const R root = std::sqrt(m_hat);
+        const R sum = root + h.eps;
+        const R C = h.eta_max * sum;
+        const R g_raw = delta / C;
+        const R G = (mode == MODE_GA) ? (R)1 + g_raw : std::fmax((R)1, g_raw);
+        if (gaps_out) gaps_out[p] = G;
+        for (uint64_t j = start; j < end; ++j) {
+            const R g_hat = g[j] / G;
+            const R gv = h.gamma * v[j];
+            const R v_new = gv + g_hat;
+            const R step = h.eta_k * v_new;
+            const R theta_new = theta[j] - step;
+            v[j] = v_new;
+            theta[j] = theta_new;
+            const R bm = h.beta * m[j];
+            const R vv = v_new * v_new;
+            const R add = one_minus_beta * vv;
+            m[j] = bm + add;
+            snap_i[j] = theta_new;
+        }
+        start = end;
+    }
+    (void)n;
+}
+
 // Quadratic-plus-noise worker gradient (synthetic stand-in for Alg. 1): the
 // worker holds theta_w = snap_i and returns
 //   g = a * (theta_w - theta_star) + sigma * z(seed, k, j).
@@ -653,6 +705,27 @@ void orc_adam_step_f64(uint64_t n, double* theta, double* m1, double* v2, double
     AdamHyper<double> ah = {beta1, beta2, adam_eps};
     adam_step<double>(n, theta, m1, v2, c, snap_i, g, mode, k, tau,
                       make_hyper<double>(eta_k, eta_max, 0.0, beta, eps), ah, track_gap);
+}
+
+int orc_step_layerwise_f32(uint64_t n, float* theta, float* v, float* m, float* snap_i, const float* g,
+                           const uint64_t* layer_sizes, uint32_t P, int mode, uint64_t k, double eta_k,
+                           double eta_max, double gamma, double beta, double eps, float* gaps_out) {
+    uint64_t total = 0;
+    for (uint32_t p = 0; p < P; ++p) total += layer_sizes[p];
+    if (total != n || (mode != MODE_GA && mode != MODE_GA_HINGE)) return -1;
+    master_step_layerwise<float>(n, theta, v, m, snap_i, g, layer_sizes, P, mode, k,
+                                 make_hyper<float>(eta_k, eta_max, gamma, beta, eps), gaps_out);
+    return 0;
+}
+int orc_step_layerwise_f64(uint64_t n, double* theta, double* v, double* m, double* snap_i, const double* g,
+                           const uint64_t* layer_sizes, uint32_t P, int mode, uint64_t k, double eta_k,
+                           double eta_max, double gamma, double beta, double eps, double* gaps_out) {
+    uint64_t total = 0;
+    for (uint32_t p = 0; p < P; ++p) total += layer_sizes[p];
+    if (total != n || (mode != MODE_GA && mode != MODE_GA_HINGE)) return -1;
+    master_step_layerwise<double>(n, theta, v, m, snap_i, g, layer_sizes, P, mode, k,
+                                  make_hyper<double>(eta_k, eta_max, gamma, beta, eps), gaps_out);
+    return 0;
 }
 
 void orc_quadratic_gradient_f32(uint64_t n, float* g, const float* snap_i, const float* a,

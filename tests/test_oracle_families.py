@@ -165,3 +165,62 @@ def test_families_reach_the_minimum():
         A = AdamMaster(N, W, mode, Hyper(0.01, 0.0, f32=False), np.float64)
         A.run_quadratic(sched, a, ts, seed=0, sigma=0.0)
         assert np.abs(A.theta - ts).max() < 0.02 * np.abs(ts).max(), mode
+
+
+# ------------------------------------------------------------------ layer-wise and global Gap
+from oracle import LayerwiseMaster
+
+
+@pytest.mark.parametrize("mode", [MODE_GA, MODE_GA_HINGE])
+def test_layers_of_one_parameter_are_the_parameter_wise_gap(mode):
+    # Eq. 4 with every layer a single parameter is Eq. 5: ||x|| = |x| and the summed m-hat is m-hat itself.
+    N, W, T = 300, 4, 150
+    a, ts = quad_inputs(N, 5, np.float32)
+    sched = oracle.simulate_schedule(W, T, seed=5)
+    L = LayerwiseMaster(N, W, mode, Hyper(), np.ones(N, np.uint64), np.float32)
+    M = Master(N, W, mode, Hyper(), np.float32)
+    L.run_quadratic(sched, a, ts, seed=9)
+    M.run_quadratic(sched, a, ts, seed=9)
+    assert np.array_equal(L.theta, M.theta) and np.array_equal(L.m, M.m) and np.array_equal(L.snaps, M.snaps)
+
+
+@pytest.mark.parametrize("layers", [[40], [1, 7, 32], [13, 27]])
+def test_layer_gap_constant_gradient_equals_delay(layers):
+    # ASGD-like history (gamma = 0, huge eta_max so that the penalty is ~1 while m is built), then read the Gap:
+    # build the state with the plain master, then one layer-wise step.  Every update was -eta c, so a snapshot
+    # s steps old has ||theta - theta^i|| = s eta ||c||, C_p = eta (||c_p|| + eps): G_p = s + 1 for every layer,
+    # whatever its size (remark after Def. 1).
+    N, W, eta = 40, 4, 0.1
+    c = np.linspace(0.5, 3.0, N) * np.where(np.arange(N) % 3, 1, -1)
+    P = Master(N, W, MODE_ASGD, Hyper(eta, 0.0, f32=False), np.float64, track_gap=True)
+    sched = np.array([0, 1, 2, 3, 0, 1, 2, 0, 1, 0, 0], np.uint32)
+    P.run_buffers(sched, c[None, :])
+    L = LayerwiseMaster(N, W, MODE_GA, Hyper(eta, 0.0, f32=False), layers, np.float64)
+    L.theta[:], L.v[:], L.m[:], L.snaps[:], L.k, L.iter[:] = P.theta, P.v, P.m, P.snaps, P.k, P.iter
+    age = P.k - int(P.iter[3])                      # worker 3 was last seen `age` steps ago
+    th_before = L.theta.copy()
+    L.apply(3, c)
+    assert np.allclose(L.last_gaps, age + 1, rtol=1e-7)
+    assert np.allclose(th_before - L.theta, eta * c / (age + 1), rtol=1e-7)      # one penalty for the whole layer
+
+
+def test_global_gap_is_scale_free_and_uniform():
+    N, W, T = 200, 4, 80
+    a, ts = quad_inputs(N, 3, np.float32)
+    sched = oracle.simulate_schedule(W, T, seed=3)
+    out = []
+    for s in (1.0, 256.0):
+        L = LayerwiseMaster(N, W, MODE_GA, Hyper(eps=float(np.float32(1e-8)) * s), None, np.float32)
+        L.run_quadratic(sched, a, ts * np.float32(s), seed=4, sigma=float(np.float32(0.01)) * s)
+        out.append(L.theta / np.float32(s))
+    assert np.array_equal(out[0], out[1])
+    # the penalty is one number per layer: v' - gamma v is g / G with the same G for every parameter
+    L = LayerwiseMaster(N, W, MODE_GA, Hyper(f32=False), [50, 150], np.float64)
+    L.run_quadratic(sched, a.astype(np.float64), ts.astype(np.float64), seed=4)
+    v0 = L.v.copy()
+    w = int(sched[0])
+    g = oracle.quadratic_gradient(L.snaps[w], a.astype(np.float64), ts.astype(np.float64), 4, L.k + 1, 0.01)
+    L.apply(w, g)
+    ratio = g / (L.v - 0.9 * v0)
+    assert np.allclose(ratio[:50], L.last_gaps[0], rtol=1e-9) and np.allclose(ratio[50:], L.last_gaps[1], rtol=1e-9)
+    assert abs(L.last_gaps[0] - L.last_gaps[1]) > 1e-6
