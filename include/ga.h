@@ -174,6 +174,16 @@ typedef struct ga_arrival {
     float inv_bc_prev; /* (float)(1 / (1 - beta^(k-1))); 0 when k = 1 */
 } ga_arrival;
 
+/* How many parameters share one Gap (Sec. 4.3).  PARAMETER is Eq. 5 (the
+ * paper's choice).  LAYER is Eq. 4: per layer p,
+ *     G_p = ||theta_p - snap_i,p|| / C_p + 1,   C_p = eta_max * (sqrt(sum_{j in p} mhat_j) + eps)
+ * (hinge mode: max(1, ||.|| / C_p)), and every gradient element of the layer is
+ * divided by G_p.  GLOBAL is Def. 1: one layer holding all parameters.  The
+ * two sums are accumulated in double and rounded once to float.  LAYER and
+ * GLOBAL exist for the MOMENTUM family in the two GA modes, one arrival per
+ * launch sequence (reduce, per-layer Gap, update); not in the persistent kernel. */
+enum ga_gap_scope { GA_GAP_PARAMETER = 0, GA_GAP_LAYER = 1, GA_GAP_GLOBAL = 2 };
+
 /* Full configuration of a master, for ga_create_ex.  Fill with ga_config_init
  * first, then change what differs. */
 typedef struct ga_config {
@@ -187,6 +197,10 @@ typedef struct ga_config {
     float eps;       /* Alg. 14 epsilon, default 1e-8 */
     float adam_beta1, adam_beta2, adam_eps; /* Alg. 9-11, defaults 0.9, 0.999, 1e-8 */
     int track_gap;   /* maintain m and snapshots in the non-GA modes too */
+    int gap_scope;   /* ga_gap_scope, default GA_GAP_PARAMETER */
+    uint32_t n_layers;                 /* GA_GAP_LAYER: number of layers */
+    const uint64_t* host_layer_sizes;  /* GA_GAP_LAYER: n_layers sizes (each > 0) summing to N; read during
+                                          ga_workspace_bytes_ex / ga_create_ex only */
 } ga_config;
 
 /* ------------------------------------------------------------------ host only
@@ -297,6 +311,11 @@ int ga_put_snapshot(ga_ctx* ctx, uint32_t worker_id, const float* dev_src);
  * per-worker arrays only).  GA_ERR_ARG if the family does not have the array. */
 int ga_get_array(ga_ctx* ctx, int which, uint32_t worker_id, float* dev_dst);
 int ga_put_array(ga_ctx* ctx, int which, uint32_t worker_id, const float* dev_src);
+
+/* GA_GAP_LAYER / GA_GAP_GLOBAL: the Gaps G_p of the most recent arrival, one
+ * float per layer (at most max_n are written).  Waits for the stream.
+ * GA_ERR_STATE for a parameter-wise context or before the first arrival. */
+int ga_get_layer_gaps(ga_ctx* ctx, float* host_out, uint32_t max_n);
 
 /* Host bookkeeping: current step k; iter[W]; the delays of all arrivals so far
  * (at most max_n are written, the total count goes to n_out). */

@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libga.so")
 GA_MODE_ASGD, GA_MODE_SA, GA_MODE_SA_STEP, GA_MODE_GA, GA_MODE_GA_HINGE = range(5)
 GA_FAMILY_MOMENTUM, GA_FAMILY_DANA, GA_FAMILY_ADAM = range(3)
 GA_ARR_THETA, GA_ARR_V, GA_ARR_M, GA_ARR_SNAPSHOT, GA_ARR_WORKER_V, GA_ARR_ADAM_V2 = range(6)
+GA_GAP_PARAMETER, GA_GAP_LAYER, GA_GAP_GLOBAL = range(3)
 GA_F32, GA_BF16 = 0, 1
 GA_OK, GA_ERR_ARG, GA_ERR_WORKER, GA_ERR_ALIGN, GA_ERR_STATE, GA_ERR_HIP = 0, -1, -2, -3, -4, -5
 GA_DIST_EXP, GA_DIST_LOGNORMAL, GA_DIST_HETERO = range(3)
@@ -51,7 +52,8 @@ class ga_config(C.Structure):
     _fields_ = [("N", C.c_uint64), ("n_workers", C.c_uint32), ("family", C.c_int), ("mode", C.c_int),
                 ("eta", C.c_float), ("gamma", C.c_float), ("beta", C.c_float), ("eps", C.c_float),
                 ("adam_beta1", C.c_float), ("adam_beta2", C.c_float), ("adam_eps", C.c_float),
-                ("track_gap", C.c_int)]
+                ("track_gap", C.c_int), ("gap_scope", C.c_int), ("n_layers", C.c_uint32),
+                ("host_layer_sizes", C.c_void_p)]
 
 
 class ga_arrival(C.Structure):
@@ -72,6 +74,7 @@ SIGNATURES = {
     "ga_workspace_bytes_ex": (C.c_size_t, [C.POINTER(ga_config)]),
     "ga_create_ex": (_i, [C.POINTER(_p), C.POINTER(ga_config), _p, C.c_size_t, _p]),
     "ga_get_array": (_i, [_p, _i, _u32, _p]),
+    "ga_get_layer_gaps": (_i, [_p, _p, _u32]),
     "ga_put_array": (_i, [_p, _i, _u32, _p]),
     "ga_create": (_i, [C.POINTER(_p), _u64, _u32, _f, _f, _i, _p, C.c_size_t, _p]),
     "ga_destroy": (None, [_p]),
@@ -191,9 +194,14 @@ def ga_config_init(**kw):
     """A ga_config with the library defaults, then the given fields."""
     cfg = ga_config()
     lib().ga_config_init(C.byref(cfg))
+    sizes = kw.pop("layer_sizes", None)
     for k, v in kw.items():
         assert hasattr(cfg, k), k
         setattr(cfg, k, v)
+    if sizes is not None:
+        sizes = np.ascontiguousarray(sizes, dtype=np.uint64)
+        cfg.gap_scope, cfg.n_layers, cfg.host_layer_sizes = GA_GAP_LAYER, sizes.size, sizes.ctypes.data
+        cfg._keep = sizes
     return cfg
 
 
@@ -207,6 +215,12 @@ def ga_create_ex(cfg, dev_workspace, stream=None):
     ptr = _dev(dev_workspace, torch.uint8)
     _check(lib().ga_create_ex(C.byref(ctx), C.byref(cfg), ptr, dev_workspace.numel(), _stream_ptr(stream)))
     return ctx
+
+
+def ga_get_layer_gaps(ctx, n_layers):
+    out = np.empty(n_layers, dtype=np.float32)
+    _check(lib().ga_get_layer_gaps(ctx, _np_ptr(out), n_layers), ctx)
+    return out
 
 
 def ga_get_array(ctx, which, worker_id, dev_dst):
@@ -363,14 +377,15 @@ class Master:
 
     def __init__(self, N, n_workers, eta=0.1, gamma=0.9, mode=GA_MODE_GA, device="cuda:0", stream=None,
                  beta=None, eps=None, eta_max=None, track_gap=False, theta0=None, family=GA_FAMILY_MOMENTUM,
-                 adam_beta1=0.9, adam_beta2=0.999, adam_eps=1e-8):
+                 adam_beta1=0.9, adam_beta2=0.999, adam_eps=1e-8, gap_scope=GA_GAP_PARAMETER, layer_sizes=None):
         import torch
         self.N, self.W, self.mode = N, n_workers, MODES.get(mode, mode)
         self.family = FAMILIES.get(family, family)
         self.device = torch.device(device)
         cfg = ga_config_init(N=N, n_workers=n_workers, family=self.family, mode=self.mode, eta=eta, gamma=gamma,
                              adam_beta1=adam_beta1, adam_beta2=adam_beta2, adam_eps=adam_eps,
-                             track_gap=int(track_gap))
+                             track_gap=int(track_gap), gap_scope=gap_scope, layer_sizes=layer_sizes)
+        self.n_layers = 0 if cfg.gap_scope == GA_GAP_PARAMETER else (1 if cfg.gap_scope == GA_GAP_GLOBAL else cfg.n_layers)
         if beta is not None:
             cfg.beta = beta
         if eps is not None:
@@ -419,6 +434,9 @@ class Master:
 
     def snapshot(self, w):
         return ga_get_snapshot(self.ctx, w, self._new())
+
+    def layer_gaps(self):
+        return ga_get_layer_gaps(self.ctx, self.n_layers)
 
     def array(self, which, worker_id=0):
         return ga_get_array(self.ctx, which, worker_id, self._new())

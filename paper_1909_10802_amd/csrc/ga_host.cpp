@@ -31,6 +31,10 @@ struct ga_ctx {
     std::vector<uint64_t> iter;
     std::vector<uint64_t> delays;
     std::vector<ga_arrival> rows;   // staging for one chunk of the table
+    int gap_scope = GA_GAP_PARAMETER;
+    ga::LayerTables layers{};
+    std::vector<ga::LayerChunk> host_chunks;   // uploaded at create; kept for the lifetime of the context
+    std::vector<ga::LayerSpan> host_spans;
     std::string err;
 };
 
@@ -60,10 +64,33 @@ uint64_t round_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
 struct Layout {
     uint64_t Np, n_rows;
     size_t off_theta, off_v, off_m, off_snaps, off_worker_v, off_v2, off_table, off_partials, total;
+    size_t off_chunks, off_spans, off_layer_partials, off_gaps;
 };
 
+// Chunks of at most kLayerChunk parameters, never across a layer boundary.  sizes == nullptr: one layer of N.
+bool build_layer_tables(uint64_t N, uint32_t n_layers, const uint64_t* sizes, std::vector<ga::LayerChunk>* chunks,
+                        std::vector<ga::LayerSpan>* spans, uint64_t* n_chunks_out) {
+    uint64_t start = 0, n_chunks = 0;
+    for (uint32_t p = 0; p < n_layers; ++p) {
+        const uint64_t len = sizes ? sizes[p] : N;
+        if (len == 0 || len > N - start) return false;
+        const uint64_t c = (len + ga::kLayerChunk - 1) / ga::kLayerChunk;
+        if (spans) spans->push_back(ga::LayerSpan{(uint32_t)n_chunks, (uint32_t)c});
+        if (chunks)
+            for (uint64_t i = 0; i < c; ++i) {
+                const uint64_t off = i * ga::kLayerChunk;
+                const uint64_t l = len - off < ga::kLayerChunk ? len - off : ga::kLayerChunk;
+                chunks->push_back(ga::LayerChunk{start + off, (uint32_t)l, p});
+            }
+        n_chunks += c;
+        start += len;
+    }
+    *n_chunks_out = n_chunks;
+    return start == N && n_chunks < 0x7FFFFFFFull;
+}
+
 // theta | v | m | W snapshots | [DANA: W worker momenta] | [ADAM: v2] | arrival table | reduction partials
-Layout layout_for(uint64_t N, uint32_t W, int family) {
+Layout layout_for(uint64_t N, uint32_t W, int family, uint64_t n_chunks = 0, uint32_t n_layers = 0) {
     Layout L;
     L.Np = round_up(N, 64);                  // every array starts 256-byte aligned
     const size_t row = (size_t)L.Np * sizeof(float);
@@ -83,6 +110,11 @@ Layout layout_for(uint64_t N, uint32_t W, int family) {
     L.off_table = L.n_rows * row;
     L.off_partials = L.off_table + round_up((uint64_t)ga::kTableCap * sizeof(ga_arrival), 256);
     L.total = L.off_partials + round_up((uint64_t)(ga::kDiagMaxBlocks + 1) * sizeof(ga::DiagPartial), 256);
+    L.off_chunks = L.total;
+    L.off_spans = L.off_chunks + round_up(n_chunks * sizeof(ga::LayerChunk), 256);
+    L.off_layer_partials = L.off_spans + round_up((uint64_t)n_layers * sizeof(ga::LayerSpan), 256);
+    L.off_gaps = L.off_layer_partials + round_up(n_chunks * sizeof(ga::LayerPartial), 256);
+    L.total = L.off_gaps + round_up((uint64_t)n_layers * sizeof(float), 256);
     return L;
 }
 
@@ -224,7 +256,9 @@ int apply_one(ga_ctx* ctx, uint32_t worker, const void* dev_grad, int dtype, boo
     const ga_arrival row = make_row(worker, k, tau, ctx->mode, ctx->lr, ctx->beta);
     const ga::StepConst sc = step_const(ctx, row, k);
     hipError_t e;
-    if (ctx->family == GA_FAMILY_DANA)
+    if (ctx->gap_scope != GA_GAP_PARAMETER)
+        e = ga::launch_apply_layerwise(ctx->st, ctx->N, worker, dev_grad, dtype, ctx->mode, ctx->layers, sc, ctx->stream);
+    else if (ctx->family == GA_FAMILY_DANA)
         e = ga::launch_apply_dana(ctx->st, ctx->N, worker, dev_grad, dtype, ctx->mode, keeps_m(ctx), write_snap, sc, ctx->stream);
     else if (ctx->family == GA_FAMILY_ADAM)
         e = ga::launch_apply_adam(ctx->st, ctx->N, worker, dev_grad, dtype, ctx->mode, keeps_m(ctx), write_snap, sc, ctx->stream);
@@ -327,12 +361,32 @@ void ga_config_init(ga_config* cfg) {
     cfg->adam_beta2 = 0.999f;
     cfg->adam_eps = 1e-8f;
     cfg->track_gap = 0;
+    cfg->gap_scope = GA_GAP_PARAMETER;
+    cfg->n_layers = 0;
+    cfg->host_layer_sizes = nullptr;
+}
+
+// Number of layers and chunks a configuration asks for; false if the layer description is invalid.
+static bool layer_counts(const ga_config* cfg, uint32_t* n_layers, uint64_t* n_chunks) {
+    *n_layers = 0;
+    *n_chunks = 0;
+    if (cfg->gap_scope == GA_GAP_PARAMETER) return true;
+    if (cfg->gap_scope == GA_GAP_GLOBAL) {
+        *n_layers = 1;
+        return build_layer_tables(cfg->N, 1, nullptr, nullptr, nullptr, n_chunks);
+    }
+    if (cfg->gap_scope != GA_GAP_LAYER || cfg->n_layers == 0 || !cfg->host_layer_sizes) return false;
+    *n_layers = cfg->n_layers;
+    return build_layer_tables(cfg->N, cfg->n_layers, cfg->host_layer_sizes, nullptr, nullptr, n_chunks);
 }
 
 size_t ga_workspace_bytes_ex(const ga_config* cfg) {
     if (!cfg || cfg->N == 0 || cfg->n_workers == 0) return 0;
     if (cfg->family < GA_FAMILY_MOMENTUM || cfg->family > GA_FAMILY_ADAM) return 0;
-    return layout_for(cfg->N, cfg->n_workers, cfg->family).total;
+    uint32_t n_layers;
+    uint64_t n_chunks;
+    if (!layer_counts(cfg, &n_layers, &n_chunks)) return 0;
+    return layout_for(cfg->N, cfg->n_workers, cfg->family, n_chunks, n_layers).total;
 }
 
 size_t ga_workspace_bytes(uint64_t N, uint32_t n_workers) {
@@ -361,8 +415,15 @@ int ga_create_ex(ga_ctx** out, const ga_config* cfg, void* dev_workspace, size_t
             return fail(nullptr, GA_ERR_ARG, "create: Adam betas must be in [0,1)");
         if (!(cfg->adam_eps > 0.f) || !std::isfinite(cfg->adam_eps)) return fail(nullptr, GA_ERR_ARG, "create: adam_eps must be finite and > 0");
     }
+    uint32_t n_layers;
+    uint64_t n_chunks;
+    if (!layer_counts(cfg, &n_layers, &n_chunks))
+        return fail(nullptr, GA_ERR_ARG, "create: invalid gap scope or layer sizes (each > 0, summing to N)");
+    if (cfg->gap_scope != GA_GAP_PARAMETER &&
+        (cfg->family != GA_FAMILY_MOMENTUM || (cfg->mode != GA_MODE_GA && cfg->mode != GA_MODE_GA_HINGE)))
+        return fail(nullptr, GA_ERR_ARG, "create: layer-wise / global Gap exists for the momentum family in the GA modes only");
     if (!dev_workspace) return fail(nullptr, GA_ERR_ARG, "create: workspace is null");
-    const Layout L = layout_for(N, n_workers, cfg->family);
+    const Layout L = layout_for(N, n_workers, cfg->family, n_chunks, n_layers);
     if (((uintptr_t)dev_workspace & 255u) != 0) return fail(nullptr, GA_ERR_ALIGN, "create: workspace must be 256-byte aligned");
     if (workspace_bytes < L.total)
         return fail(nullptr, GA_ERR_ALIGN, "create: workspace has %zu bytes, %zu needed", workspace_bytes, L.total);
@@ -395,8 +456,25 @@ int ga_create_ex(ga_ctx** out, const ga_config* cfg, void* dev_workspace, size_t
     c->iter.assign(n_workers, 0);
     c->rows.reserve(ga::kTableCap);
 
+    c->gap_scope = cfg->gap_scope;
     // all state rows are contiguous: one fill
-    const hipError_t e = ga::launch_fill(c->st.theta, L.n_rows * L.Np, 0.0f, c->stream);
+    hipError_t e = ga::launch_fill(c->st.theta, L.n_rows * L.Np, 0.0f, c->stream);
+    if (e == hipSuccess && n_layers > 0) {
+        uint64_t nc = 0;
+        build_layer_tables(N, n_layers, cfg->gap_scope == GA_GAP_LAYER ? cfg->host_layer_sizes : nullptr,
+                           &c->host_chunks, &c->host_spans, &nc);
+        ga::LayerChunk* dchunks = reinterpret_cast<ga::LayerChunk*>(base + L.off_chunks);
+        ga::LayerSpan* dspans = reinterpret_cast<ga::LayerSpan*>(base + L.off_spans);
+        c->layers.chunks = dchunks;
+        c->layers.spans = dspans;
+        c->layers.partials = reinterpret_cast<ga::LayerPartial*>(base + L.off_layer_partials);
+        c->layers.gaps = reinterpret_cast<float*>(base + L.off_gaps);
+        c->layers.n_chunks = (uint32_t)nc;
+        c->layers.n_layers = n_layers;
+        e = hipMemcpyAsync(dchunks, c->host_chunks.data(), nc * sizeof(ga::LayerChunk), hipMemcpyHostToDevice, c->stream);
+        if (e == hipSuccess)
+            e = hipMemcpyAsync(dspans, c->host_spans.data(), (size_t)n_layers * sizeof(ga::LayerSpan), hipMemcpyHostToDevice, c->stream);
+    }
     if (e != hipSuccess) {
         const int rc = hip_fail(nullptr, e, "create: initial fill");
         delete c;
@@ -501,8 +579,8 @@ int ga_run_schedule(ga_ctx* ctx, const uint32_t* host_schedule, uint64_t T, cons
     if (rc != GA_OK) return rc;
     const ga::RunConst rcst = run_const(ctx, src);
 
-    if (src->persistent && ctx->family != GA_FAMILY_MOMENTUM)
-        return fail(ctx, GA_ERR_ARG, "run_schedule: the persistent kernel exists for the momentum family only");
+    if (src->persistent && (ctx->family != GA_FAMILY_MOMENTUM || ctx->gap_scope != GA_GAP_PARAMETER))
+        return fail(ctx, GA_ERR_ARG, "run_schedule: the persistent kernel exists for the momentum family with the parameter-wise Gap only");
 
     if (!src->persistent) {
         // one gradient launch and one update launch per arrival; the worker reads its snapshot,
@@ -628,6 +706,17 @@ int ga_put_array(ga_ctx* ctx, int which, uint32_t worker_id, const float* dev_sr
     int rc;
     float* p = array_of(ctx, which, worker_id, &rc);
     return p ? copy_in(ctx, p, dev_src) : rc;
+}
+
+int ga_get_layer_gaps(ga_ctx* ctx, float* host_out, uint32_t max_n) {
+    if (!ctx) return GA_ERR_ARG;
+    if (!host_out && max_n > 0) return fail(ctx, GA_ERR_ARG, "get_layer_gaps: output is null");
+    if (ctx->gap_scope == GA_GAP_PARAMETER) return fail(ctx, GA_ERR_STATE, "get_layer_gaps: the context uses the parameter-wise Gap");
+    if (ctx->k == 0) return fail(ctx, GA_ERR_STATE, "get_layer_gaps: no arrival yet");
+    const uint32_t n = ctx->layers.n_layers < max_n ? ctx->layers.n_layers : max_n;
+    hipError_t e = hipMemcpyAsync(host_out, ctx->layers.gaps, (size_t)n * sizeof(float), hipMemcpyDeviceToHost, ctx->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+    return e == hipSuccess ? GA_OK : hip_fail(ctx, e, "get_layer_gaps");
 }
 
 uint64_t ga_step(const ga_ctx* ctx) { return ctx ? ctx->k : 0; }

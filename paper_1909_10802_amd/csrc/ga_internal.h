@@ -40,6 +40,28 @@ struct DiagPartial {
     unsigned long long n_gt1, n_gt0, n_bad;
 };
 
+// Layer-wise Gap: layers are cut into chunks of at most kLayerChunk parameters; one block per chunk.
+constexpr uint32_t kLayerChunk = 8192;
+struct LayerChunk {
+    uint64_t start;   // first parameter
+    uint32_t len;     // parameters in the chunk
+    uint32_t layer;
+};
+struct LayerSpan {
+    uint32_t first_chunk, n_chunks;
+};
+struct LayerPartial {
+    double dist2;     // sum of (theta - snap)^2
+    double msum;      // sum of m
+};
+struct LayerTables {
+    const LayerChunk* chunks;
+    const LayerSpan* spans;
+    LayerPartial* partials;
+    float* gaps;
+    uint32_t n_chunks, n_layers;
+};
+
 constexpr uint32_t kTableCap = 8192;       // arrivals per persistent launch
 constexpr uint32_t kDiagMaxBlocks = 2048;  // partials in the workspace
 
@@ -64,6 +86,10 @@ hipError_t launch_apply_dana(const StatePtrs& st, uint64_t N, uint32_t worker, c
                              bool keep_m, bool write_snap, const StepConst& c, hipStream_t stream);
 hipError_t launch_apply_adam(const StatePtrs& st, uint64_t N, uint32_t worker, const void* g, int grad_dtype, int mode,
                              bool keep_m, bool write_snap, const StepConst& c, hipStream_t stream);
+
+// Layer-wise / global Gap arrival: per-chunk reduction, per-layer Gap, update with one Gap per layer.
+hipError_t launch_apply_layerwise(const StatePtrs& st, uint64_t N, uint32_t worker, const void* g, int grad_dtype,
+                                  int mode, const LayerTables& lt, const StepConst& c, hipStream_t stream);
 
 // T arrivals replayed inside one launch, gradients generated in the kernel.
 // table: device array of T rows; k0: master step before the first row.
