@@ -47,6 +47,8 @@ def parse():
     p.add_argument("--workload", default="cfg3", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
     p.add_argument("--family", default="momentum", choices=["momentum", "dana", "adam"],
                    help="master algorithm family: Alg. 2-5, Alg. 6-8 or Alg. 9-11")
+    p.add_argument("--gap-scope", default="parameter", choices=["parameter", "layer", "global"],
+                   help="parameter-wise Gap (Eq. 5), layer-wise (Eq. 4, the workload's tensor table) or global (Def. 1)")
     p.add_argument("--mode", default="ga", choices=["ga", "ga_hinge", "sa", "sa_step", "asgd"])
     p.add_argument("--diag-every", type=int, default=250, help="Gap statistics every this many arrivals (0: never)")
     p.add_argument("--no-cpu-baseline", action="store_true")
@@ -98,8 +100,13 @@ def bench_fused(args, cfg, torch, ga, ga_inputs):
     src = ga.buffer_source(bufs, ga.GA_PICK_BY_WORKER if cfg["pick"] == "worker" else ga.GA_PICK_BY_ARRIVAL)
     sched = ga.ga_simulate_schedule(W, K + Wm + 1, ga_inputs.DIST_CODES[cfg["dist"]], cfg["sigma"], seed)
     eta = 0.01 if args.family == "adam" else cfg["eta"]
+    scope_kw = {}
+    if args.gap_scope == "global":
+        scope_kw = dict(gap_scope=ga.GA_GAP_GLOBAL)
+    elif args.gap_scope == "layer":
+        scope_kw = dict(layer_sizes=ga_inputs.tensor_sizes(N, cfg.get("n_tensors", 161), seed))
     M = ga.Master(N, W, eta=eta, gamma=cfg["gamma"], mode=args.mode, device=dev, family=args.family,
-                  track_gap=(args.diag_every > 0))
+                  track_gap=(args.diag_every > 0), **scope_kw)
     M.run_schedule(sched[:Wm], src)
     if args.diag_every > 0:
         M.diagnostics(int(sched[0]))
@@ -129,6 +136,9 @@ def bench_fused(args, cfg, torch, ga, ga_inputs):
         bpu += 12                                                   # gap tracking: m read + write, snapshot write
     if args.family != "momentum":
         bpu += 8                                                    # one more state array read and written
+    if args.gap_scope != "parameter":
+        bpu += 8                                                    # reduction pass re-reads theta, snapshot, m (12 B),
+                                                                    # the update pass no longer reads the snapshot (-4 B)
     achieved = bpu * N / (kernel_ms * 1e-3) / 1e9
     theta = M.theta()
     finite = bool(torch.isfinite(theta).all().item())
@@ -138,10 +148,11 @@ def bench_fused(args, cfg, torch, ga, ga_inputs):
             dst.copy_(theta)
         torch.cuda.synchronize()
     t = TRAFFIC.get((args.workload, args.mode))
-    traffic = t["bytes"] if t and t["kernels_sha256"] == kernels_hash() else None
+    traffic = t["bytes"] if t and t["kernels_sha256"] == kernels_hash() and args.gap_scope == "parameter" else None
     roof = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
             "traffic": traffic if args.family == "momentum" else None,
-            "kernel": "apply_kernel" if args.family == "momentum" else "family_apply_kernel", "bytes_per_update": bpu, "avg_launch_ms": kernel_ms,
+            "kernel": ("layer_partial_kernel + layer_gap_kernel + layer_apply_kernel" if args.gap_scope != "parameter"
+                       else "apply_kernel" if args.family == "momentum" else "family_apply_kernel"), "bytes_per_update": bpu, "avg_launch_ms": kernel_ms,
             "algorithmic_bytes_per_launch": bpu * N}
     desc = ("%s: N=%d float parameters, %d workers, %s iteration times, %d %s gradient buffers picked by %s, one "
             "fused-update launch per arrival, family %s, mode %s" % (args.workload, N, W, cfg["dist"], cfg["n_bufs"],
@@ -242,7 +253,7 @@ def main():
         "ms_per_step": wall / K * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": desc, "N": N, "n_workers": cfg["W"], "family": args.family, "mode": args.mode,
+        "config": {"workload": desc, "N": N, "n_workers": cfg["W"], "family": args.family, "mode": args.mode, "gap_scope": args.gap_scope,
                    "grad_dtype": cfg["grad_dtype"], "eta": cfg["eta"], "gamma": cfg["gamma"],
                    "diag_every": args.diag_every if fused else None, "seed": cfg["seed"]},
         "roofline": roof,

@@ -315,11 +315,13 @@ __global__ __launch_bounds__(kBlock) void family_apply_kernel(float* __restrict_
 // ---------------------------------------------------------------------------
 // Layer-wise and global Gap (Eq. 4, Def. 1).  Three launches per arrival:
 //   layer_partial_kernel   one block per chunk of a layer: sum (theta-snap)^2 and sum m in double
-//   layer_gap_kernel       one thread per layer adds its chunks in order and forms G_p
+//   layer_gap_kernel       one block per layer adds its chunk partials in a fixed order and forms G_p
 //   layer_apply_kernel     one block per chunk: the momentum update with ghat = g / G_p
 // A chunk never crosses a layer boundary; boundaries are arbitrary, so a chunk has a scalar
 // head and tail around its 16-byte aligned body.  Every sum has a fixed order.
 // ---------------------------------------------------------------------------
+constexpr int kLayerU = 4;   // 128-bit groups in flight per thread in the chunk kernels
+
 struct ChunkRange {
     uint64_t start, end;   // parameters [start, end)
     uint64_t a0, a1;       // aligned body [a0, a1), multiples of 4
@@ -349,11 +351,25 @@ __global__ __launch_bounds__(kBlock) void layer_partial_kernel(const float* __re
         ms += (double)mm;
     };
     for (uint64_t j = r.start + threadIdx.x; j < r.a0; j += kBlock) one(theta[j], snap[j], m[j]);
-    for (uint64_t q = (r.a0 >> 2) + threadIdx.x; q < (r.a1 >> 2); q += kBlock) {
-        const f32x4 th = load4<false>(theta, q);
-        const f32x4 s = load4<true>(snap, q);
-        const f32x4 mm = load4<true>(m, q);
-        one(th.x, s.x, mm.x); one(th.y, s.y, mm.y); one(th.z, s.z, mm.z); one(th.w, s.w, mm.w);
+    const uint64_t q_end = r.a1 >> 2;
+    for (uint64_t q0 = (r.a0 >> 2) + threadIdx.x; q0 < q_end; q0 += (uint64_t)kLayerU * kBlock) {
+        f32x4 th[kLayerU], sv[kLayerU], mm[kLayerU];
+#pragma unroll
+        for (int u = 0; u < kLayerU; ++u) {
+            const uint64_t q = q0 + (uint64_t)u * kBlock;
+            if (q < q_end) {
+                th[u] = load4<false>(theta, q);
+                sv[u] = load4<true>(snap, q);
+                mm[u] = load4<true>(m, q);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kLayerU; ++u) {
+            if (q0 + (uint64_t)u * kBlock < q_end) {
+                one(th[u].x, sv[u].x, mm[u].x); one(th[u].y, sv[u].y, mm[u].y);
+                one(th[u].z, sv[u].z, mm[u].z); one(th[u].w, sv[u].w, mm[u].w);
+            }
+        }
     }
     for (uint64_t j = r.a1 + threadIdx.x; j < r.end; j += kBlock) one(theta[j], snap[j], m[j]);
 
@@ -381,16 +397,33 @@ __global__ __launch_bounds__(kBlock) void layer_partial_kernel(const float* __re
 
 template <bool HINGE>
 __global__ __launch_bounds__(kBlock) void layer_gap_kernel(const LayerPartial* __restrict__ partials,
-                                                           const LayerSpan* __restrict__ spans, uint32_t n_layers,
-                                                           float inv_bc_prev, float eta_max, float eps,
-                                                           float* __restrict__ gaps) {
-    const uint32_t p = blockIdx.x * kBlock + threadIdx.x;
-    if (p >= n_layers) return;
-    const LayerSpan sp = spans[p];
+                                                           const LayerSpan* __restrict__ spans, float inv_bc_prev,
+                                                           float eta_max, float eps, float* __restrict__ gaps) {
+    // one block per layer: strided partial sums, 64-lane butterfly, then the waves in order
+    const LayerSpan sp = spans[blockIdx.x];
     double d2 = 0.0, ms = 0.0;
-    for (uint32_t i = 0; i < sp.n_chunks; ++i) {
+    for (uint32_t i = threadIdx.x; i < sp.n_chunks; i += kBlock) {
         d2 += partials[sp.first_chunk + i].dist2;
         ms += partials[sp.first_chunk + i].msum;
+    }
+    __shared__ double part[2][kBlock / 64];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        d2 += __shfl_xor(d2, off, 64);
+        ms += __shfl_xor(ms, off, 64);
+    }
+    if ((threadIdx.x & 63) == 0) {
+        part[0][threadIdx.x >> 6] = d2;
+        part[1][threadIdx.x >> 6] = ms;
+    }
+    __syncthreads();
+    if (threadIdx.x != 0) return;
+    d2 = part[0][0];
+    ms = part[1][0];
+#pragma unroll
+    for (int w = 1; w < kBlock / 64; ++w) {
+        d2 += part[0][w];
+        ms += part[1][w];
     }
     const float delta = (float)sqrt(d2);
     const float mhat = (float)ms * inv_bc_prev;
@@ -398,7 +431,7 @@ __global__ __launch_bounds__(kBlock) void layer_gap_kernel(const LayerPartial* _
     const float sum = root + eps;
     const float C = eta_max * sum;
     const float graw = delta / C;
-    gaps[p] = HINGE ? fmaxf(1.0f, graw) : 1.0f + graw;
+    gaps[blockIdx.x] = HINGE ? fmaxf(1.0f, graw) : 1.0f + graw;
 }
 
 __device__ __forceinline__ void layer_update_one(float& th, float& v, float& m, float g, float G, const StepConst& c) {
@@ -426,21 +459,36 @@ __global__ __launch_bounds__(kBlock) void layer_apply_kernel(float* __restrict__
         theta[j] = t1; v[j] = v1; m[j] = m1; snap[j] = t1;
     };
     for (uint64_t j = r.start + threadIdx.x; j < r.a0; j += kBlock) scalar(j);
-    for (uint64_t q = (r.a0 >> 2) + threadIdx.x; q < (r.a1 >> 2); q += kBlock) {
-        f32x4 th = load4<false>(theta, q);
-        f32x4 vv = load4<STREAM_V>(v, q);
-        f32x4 mm = load4<true>(m, q);
-        const f32x4 gg = load_g4<DT, ALIGNED>(g, q);
+    constexpr int U = 2;
+    const uint64_t q_end = r.a1 >> 2;
+    for (uint64_t q0 = (r.a0 >> 2) + threadIdx.x; q0 < q_end; q0 += (uint64_t)U * kBlock) {
+        f32x4 th[U], vv[U], mm[U], gg[U];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            float t1 = th[e], v1 = vv[e], m1 = mm[e];
-            layer_update_one(t1, v1, m1, gg[e], G, c);
-            th[e] = t1; vv[e] = v1; mm[e] = m1;
+        for (int u = 0; u < U; ++u) {
+            const uint64_t q = q0 + (uint64_t)u * kBlock;
+            if (q < q_end) {
+                th[u] = load4<false>(theta, q);
+                vv[u] = load4<STREAM_V>(v, q);
+                mm[u] = load4<true>(m, q);
+                gg[u] = load_g4<DT, ALIGNED>(g, q);
+            }
         }
-        store4<false>(theta, q, th);
-        store4<STREAM_V>(v, q, vv);
-        store4<true>(m, q, mm);
-        store4<true>(snap, q, th);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint64_t q = q0 + (uint64_t)u * kBlock;
+            if (q < q_end) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    float t1 = th[u][e], v1 = vv[u][e], m1 = mm[u][e];
+                    layer_update_one(t1, v1, m1, gg[u][e], G, c);
+                    th[u][e] = t1; vv[u][e] = v1; mm[u][e] = m1;
+                }
+                store4<false>(theta, q, th[u]);
+                store4<STREAM_V>(v, q, vv[u]);
+                store4<true>(m, q, mm[u]);
+                store4<true>(snap, q, th[u]);
+            }
+        }
     }
     for (uint64_t j = r.a1 + threadIdx.x; j < r.end; j += kBlock) scalar(j);
 }
@@ -901,14 +949,14 @@ hipError_t launch_apply_layerwise(const StatePtrs& st, uint64_t N, uint32_t work
                                   int mode, const LayerTables& lt, const StepConst& c, hipStream_t stream) {
     if (lt.n_chunks == 0 || lt.n_layers == 0) return hipErrorInvalidValue;
     float* snap = st.snaps + (uint64_t)worker * st.stride;
-    const dim3 block(kBlock), grid(lt.n_chunks), lgrid((lt.n_layers + kBlock - 1) / kBlock);
+    const dim3 block(kBlock), grid(lt.n_chunks), lgrid(lt.n_layers);
     hipLaunchKernelGGL(layer_partial_kernel, grid, block, 0, stream, st.theta, st.m, snap, lt.chunks, lt.partials);
     if (mode == GA_MODE_GA_HINGE)
-        hipLaunchKernelGGL(layer_gap_kernel<true>, lgrid, block, 0, stream, lt.partials, lt.spans, lt.n_layers,
-                           c.inv_bc_prev, c.eta_max, c.eps, lt.gaps);
+        hipLaunchKernelGGL(layer_gap_kernel<true>, lgrid, block, 0, stream, lt.partials, lt.spans, c.inv_bc_prev,
+                           c.eta_max, c.eps, lt.gaps);
     else
-        hipLaunchKernelGGL(layer_gap_kernel<false>, lgrid, block, 0, stream, lt.partials, lt.spans, lt.n_layers,
-                           c.inv_bc_prev, c.eta_max, c.eps, lt.gaps);
+        hipLaunchKernelGGL(layer_gap_kernel<false>, lgrid, block, 0, stream, lt.partials, lt.spans, c.inv_bc_prev,
+                           c.eta_max, c.eps, lt.gaps);
     const uintptr_t addr = reinterpret_cast<uintptr_t>(g);
     const bool stream_v = N > kKeepVMaxN;
 #define GA_LAYER_APPLY(DT, AL, SV)                                                                                  \
