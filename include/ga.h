@@ -112,10 +112,25 @@ enum ga_status {
 
 /* Iteration-time models of the arrival-schedule simulator. */
 enum ga_time_dist {
-    GA_DIST_EXP = 0,        /* Exp(mean 1) per iteration */
-    GA_DIST_LOGNORMAL = 1,  /* exp(sigma z) per iteration, z ~ N(0,1) */
-    GA_DIST_HETERO = 2      /* worker mean exp(sigma z_w), times Exp(1) per iteration */
+    GA_DIST_EXP = 0,          /* Exp(mean 1) per iteration */
+    GA_DIST_LOGNORMAL = 1,    /* exp(sigma z) per iteration, z ~ N(0,1) */
+    GA_DIST_HETERO = 2,       /* worker mean exp(sigma z_w), times Exp(1) per iteration */
+    GA_DIST_GAMMA_HOMO = 3,   /* Alg. 12: q = G(a_task, mean/a_task) once; time = G(a_mach, q/a_mach) */
+    GA_DIST_GAMMA_HETERO = 4  /* Alg. 13: p[w] = G(a_mach, mean/a_mach) per worker; time = G(a_task, p[w]/a_task) */
 };
+
+/* Time model for ga_simulate_schedule_ex / ga_simulate_speedup.  The gamma
+ * model is the one of App. C.3: a_task = 1/v_task^2, a_mach = 1/v_mach^2,
+ * mu_task = mu_mach = mean; the paper uses v_task = 0.1 and v_mach = 0.1
+ * (homogeneous) or 0.6 (heterogeneous).  G(alpha, scale) with alpha >= 1 is
+ * drawn with the Marsaglia-Tsang method from counter-based uniforms. */
+typedef struct ga_time_model {
+    int dist;       /* ga_time_dist */
+    double sigma;   /* LOGNORMAL, HETERO */
+    double mean;    /* GAMMA_*: > 0 */
+    double v_mach;  /* GAMMA_*: in (0, 1] */
+    double v_task;  /* GAMMA_*: in (0, 1] */
+} ga_time_model;
 
 enum ga_source_kind { GA_SRC_QUADRATIC_NOISE = 0, GA_SRC_BUFFERS = 1 };
 enum ga_pick { GA_PICK_BY_WORKER = 0, GA_PICK_BY_ARRIVAL = 1 };
@@ -218,6 +233,18 @@ void ga_config_init(ga_config* cfg);
  * GA_DIST_LOGNORMAL and GA_DIST_HETERO only. */
 int ga_simulate_schedule(uint32_t n_workers, uint64_t T, int dist, double sigma, uint64_t seed,
                          uint32_t* host_schedule);
+
+/* The same for any time model; host_finish_times (optional, T doubles)
+ * receives the finish time of every arrival. */
+int ga_simulate_schedule_ex(uint32_t n_workers, uint64_t T, const ga_time_model* model, uint64_t seed,
+                            uint32_t* host_schedule, double* host_finish_times);
+
+/* App. D: wall-clock time to process n_workers * iters batches with batch
+ * times from `model` and no communication cost.  SSGD waits in every iteration
+ * for the slowest worker; ASGD ends with arrival number n_workers * iters of
+ * the FIFO schedule above. */
+int ga_simulate_speedup(uint32_t n_workers, uint64_t iters, const ga_time_model* model, uint64_t seed,
+                        double* asgd_wall, double* ssgd_wall);
 
 /* Delay bookkeeping of Alg. 3 / Alg. 5 for T arrivals starting after master
  * step k0: tau_k = k - iter[i]; iter[i] = k.  host_iter (n_workers entries) is

@@ -17,7 +17,7 @@ _SRC = os.path.join(_HERE, "ga_oracle.cpp")
 _LIB = os.path.join(_HERE, "libga_oracle.so")
 
 MODE_ASGD, MODE_SA, MODE_SA_STEP, MODE_GA, MODE_GA_HINGE = range(5)
-DIST_EXP, DIST_LOGNORMAL, DIST_HETERO = range(3)
+DIST_EXP, DIST_LOGNORMAL, DIST_HETERO, DIST_GAMMA_HOMO, DIST_GAMMA_HETERO = range(5)
 
 CXXFLAGS = ["-O2", "-std=c++17", "-ffp-contract=off", "-fopenmp", "-fPIC", "-shared"]
 
@@ -56,6 +56,12 @@ def _declare(L):
     L.orc_iteration_time.restype = _f64
     L.orc_iteration_time.argtypes = [_int, _f64, _u64, _u32, _u64]
     L.orc_simulate_schedule.argtypes = [_u32, _u64, _int, _f64, _u64, _p, _p]
+    L.orc_iteration_time_gamma.restype = _f64
+    L.orc_iteration_time_gamma.argtypes = [_int, _f64, _f64, _f64, _u64, _u32, _u64]
+    L.orc_gamma_draw.restype = _f64
+    L.orc_gamma_draw.argtypes = [_f64, _f64, _u64, _u64]
+    L.orc_simulate_schedule_gamma.argtypes = [_u32, _u64, _int, _f64, _f64, _f64, _u64, _p, _p]
+    L.orc_speedup_times.argtypes = [_u32, _u64, _int, _f64, _f64, _f64, _u64, _p, _p]
     L.orc_schedule_from_times.argtypes = [_u32, _u64, _p, _u64, _p]
     L.orc_delays.argtypes = [_u32, _u64, _p, _u64, _p, _p]
     hyp = [_f64] * 5
@@ -123,6 +129,31 @@ def simulate_schedule(W, T, dist=DIST_EXP, sigma=1.0, seed=0, with_times=False):
     rc = lib().orc_simulate_schedule(W, T, dist, sigma, seed, _ptr(sched), _ptr(times))
     assert rc == 0
     return (sched, times) if with_times else sched
+
+
+def gamma_draw(alpha, scale, seed, n):
+    return lib().orc_gamma_draw(alpha, scale, seed, n)
+
+
+def iteration_time_gamma(dist, seed, w, n, mean=128.0, v_mach=0.1, v_task=0.1):
+    return lib().orc_iteration_time_gamma(dist, mean, v_mach, v_task, seed, w, n)
+
+
+def simulate_schedule_gamma(W, T, dist, seed=0, mean=128.0, v_mach=0.1, v_task=0.1, with_times=False):
+    """Arrival schedule under the gamma model of App. C.3 (Alg. 12: DIST_GAMMA_HOMO, Alg. 13: DIST_GAMMA_HETERO)."""
+    sched = np.empty(T, dtype=np.uint32)
+    times = np.empty(T, dtype=np.float64) if with_times else None
+    rc = lib().orc_simulate_schedule_gamma(W, T, dist, mean, v_mach, v_task, seed, _ptr(sched), _ptr(times))
+    assert rc == 0
+    return (sched, times) if with_times else sched
+
+
+def speedup_times(W, iters, dist, seed=0, mean=128.0, v_mach=0.1, v_task=0.1):
+    """(ASGD wall time, SSGD wall time) to process W*iters batches (App. D)."""
+    a, s = C.c_double(), C.c_double()
+    rc = lib().orc_speedup_times(W, iters, dist, mean, v_mach, v_task, seed, C.byref(a), C.byref(s))
+    assert rc == 0
+    return a.value, s.value
 
 
 def schedule_from_times(times, T):

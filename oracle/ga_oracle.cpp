@@ -14,6 +14,8 @@
 //   * DANA / DANA-SA / DANA-GA masters             -- Alg. 6, 7, 8 (App. C.1)
 //   * Adam / Adam-SA / Adam-GA masters             -- Alg. 9, 10, 11 (App. C.1)
 //   * layer-wise and global Gap                    -- Eq. 4 and Def. 1 (Sec. 4.3)
+//   * task execution times, gamma (CVB) model      -- Alg. 12, 13 (App. C.3)
+//   * ASGD-vs-SSGD speed-up simulation             -- App. D
 //   * master is a FIFO over worker arrivals        -- App. C.1
 // plus two pieces that are not in the paper and are defined by this project's
 // synthetic workloads: the counter-based noise generator used by the
@@ -33,7 +35,10 @@
 // invariance of the Gap; schedule closed forms (round robin, mean delay = W
 // for exponential times); DANA with one worker against a matrix-power closed
 // form and with gamma = 0 against the momentum master; Adam with one worker
-// against torch.optim.Adam; Adam-SA / Adam-GA steady-state step eta/tau.
+// against torch.optim.Adam; Adam-SA / Adam-GA steady-state step eta/tau;
+// layers of one parameter against the parameter-wise Gap; gamma variates
+// against scipy's gamma distribution and the tail probabilities printed in
+// App. C.3 (27.9 % / 1 %); speed-up ratios against the values printed in App. D.
 // Parity unpinned: the hinge penalty max(1, |d|/C) is this project's variant,
 // pinned only by its definition (equals the paper's form with "+1" replaced).
 
@@ -184,11 +189,21 @@ double noise_z_ref(uint64_t seed, uint64_t k, uint64_t j) {
 enum TimeDist {
     DIST_EXP = 0,         // Exp(mean 1), i.i.d. per iteration
     DIST_LOGNORMAL = 1,   // exp(sigma * z), i.i.d. per iteration
-    DIST_HETERO = 2       // per-worker mean exp(sigma * z_w), times Exp(1) per iteration
+    DIST_HETERO = 2,      // per-worker mean exp(sigma * z_w), times Exp(1) per iteration
+    DIST_GAMMA_HOMO = 3,  // Alg. 12: homogeneous machines
+    DIST_GAMMA_HETERO = 4 // Alg. 13: heterogeneous machines
+};
+
+// Parameters of the time model.  sigma: lognormal / hetero.  mean, v_mach, v_task: gamma model
+// (mu_task = mu_mach = mean; alpha_task = 1/v_task^2; alpha_mach = 1/v_mach^2; App. C.3).
+struct TimeModel {
+    int dist;
+    double sigma, mean, v_mach, v_task;
 };
 
 const uint32_t TAG_TIME = 0x54494D45u;   // counter word 3 of an iteration draw
 const uint32_t TAG_MEAN = 0x4D45414Eu;   // counter word 3 of a per-worker draw
+const uint32_t TAG_GAMMA = 0x47000000u;  // counter word 3 of a gamma draw: + 65536 * kind + attempt
 
 double u53(uint32_t lo, uint32_t hi) {
     const uint64_t r = ((uint64_t)hi << 32) | lo;
@@ -209,18 +224,60 @@ double worker_mean(double sigma, uint64_t seed, uint32_t w) {
     return std::exp(sigma * std_normal_from(x));
 }
 
-double iteration_time(int dist, double sigma, uint64_t seed, uint32_t w, uint64_t n) {
+// G(alpha, scale), alpha >= 1: Marsaglia and Tsang, "A simple method for generating gamma
+// variables" (ACM TOMS 26, 2000).  Attempt a of draw (c0, c1, c2, kind) uses the Philox block
+// with counter word 3 = TAG_GAMMA + 65536*kind + a: (x0,x1) and x2 give the normal
+// (Box-Muller radius and angle), x3 the acceptance uniform.
+double gamma_draw(double alpha, double scale, uint64_t seed, uint32_t c0, uint32_t c1, uint32_t c2, uint32_t kind) {
+    const uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+    const double d = alpha - 1.0 / 3.0;
+    const double c = 1.0 / std::sqrt(9.0 * d);
+    for (uint32_t attempt = 0; attempt < 65536; ++attempt) {
+        const uint32_t ctr[4] = {c0, c1, c2, TAG_GAMMA + 65536u * kind + attempt};
+        uint32_t x[4];
+        philox4x32_10(ctr, key, x);
+        const double radius = std::sqrt(-2.0 * std::log1p(-u53(x[0], x[1])));
+        const double z = radius * std::cos(6.283185307179586476925286766559 * (((double)x[2] + 0.5) / 4294967296.0));
+        const double ua = ((double)x[3] + 0.5) / 4294967296.0;
+        double v = 1.0 + c * z;
+        if (v <= 0.0) continue;
+        v = v * v * v;
+        if (std::log(ua) < 0.5 * z * z + d - d * v + d * std::log(v)) return d * v * scale;
+    }
+    return std::numeric_limits<double>::quiet_NaN();
+}
+
+// Alg. 12: q = G(alpha_task, mu/alpha_task), one draw for the whole run.
+double gamma_homo_q(const TimeModel& tm, uint64_t seed) {
+    const double alpha_task = 1.0 / (tm.v_task * tm.v_task);
+    return gamma_draw(alpha_task, tm.mean / alpha_task, seed, 0, 0, 0, 1);
+}
+// Alg. 13: p[j] = G(alpha_mach, mu/alpha_mach), one draw per machine.
+double gamma_hetero_p(const TimeModel& tm, uint64_t seed, uint32_t w) {
+    const double alpha_mach = 1.0 / (tm.v_mach * tm.v_mach);
+    return gamma_draw(alpha_mach, tm.mean / alpha_mach, seed, w, 0, 0, 2);
+}
+
+double iteration_time(const TimeModel& tm, uint64_t seed, uint32_t w, uint64_t n) {
+    if (tm.dist == DIST_GAMMA_HOMO) {          // time = G(alpha_mach, q/alpha_mach)
+        const double alpha_mach = 1.0 / (tm.v_mach * tm.v_mach);
+        return gamma_draw(alpha_mach, gamma_homo_q(tm, seed) / alpha_mach, seed, (uint32_t)n, (uint32_t)(n >> 32), w, 0);
+    }
+    if (tm.dist == DIST_GAMMA_HETERO) {        // time = G(alpha_task, p[w]/alpha_task)
+        const double alpha_task = 1.0 / (tm.v_task * tm.v_task);
+        return gamma_draw(alpha_task, gamma_hetero_p(tm, seed, w) / alpha_task, seed, (uint32_t)n, (uint32_t)(n >> 32), w, 0);
+    }
     const uint32_t ctr[4] = {(uint32_t)n, (uint32_t)(n >> 32), w, TAG_TIME};
     const uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
     uint32_t x[4];
     philox4x32_10(ctr, key, x);
-    switch (dist) {
+    switch (tm.dist) {
         case DIST_EXP:
             return -std::log1p(-u53(x[0], x[1]));
         case DIST_LOGNORMAL:
-            return std::exp(sigma * std_normal_from(x));
+            return std::exp(tm.sigma * std_normal_from(x));
         case DIST_HETERO:
-            return worker_mean(sigma, seed, w) * (-std::log1p(-u53(x[0], x[1])));
+            return worker_mean(tm.sigma, seed, w) * (-std::log1p(-u53(x[0], x[1])));
         default:
             return std::numeric_limits<double>::quiet_NaN();
     }
@@ -232,12 +289,12 @@ double iteration_time(int dist, double sigma, uint64_t seed, uint32_t w, uint64_
 // serves arrivals in order of finish time (FIFO, App. C.1), ties to the lowest
 // worker id; the update itself takes no time and the worker restarts at once.
 // ---------------------------------------------------------------------------
-void simulate_schedule(uint32_t W, uint64_t T, int dist, double sigma, uint64_t seed,
+void simulate_schedule(uint32_t W, uint64_t T, const TimeModel& tm, uint64_t seed,
                        uint32_t* schedule, double* finish_times) {
     typedef std::pair<double, uint32_t> Ev;   // (finish time, worker)
     std::priority_queue<Ev, std::vector<Ev>, std::greater<Ev>> pq;
     std::vector<uint64_t> n_done(W, 0);
-    for (uint32_t w = 0; w < W; ++w) pq.push(Ev(iteration_time(dist, sigma, seed, w, 0), w));
+    for (uint32_t w = 0; w < W; ++w) pq.push(Ev(iteration_time(tm, seed, w, 0), w));
     for (uint64_t k = 0; k < T; ++k) {
         const Ev ev = pq.top();
         pq.pop();
@@ -245,7 +302,7 @@ void simulate_schedule(uint32_t W, uint64_t T, int dist, double sigma, uint64_t 
         schedule[k] = w;
         if (finish_times) finish_times[k] = ev.first;
         n_done[w] += 1;
-        pq.push(Ev(ev.first + iteration_time(dist, sigma, seed, w, n_done[w]), w));
+        pq.push(Ev(ev.first + iteration_time(tm, seed, w, n_done[w]), w));
     }
 }
 
@@ -260,6 +317,33 @@ void delays_from_schedule(uint32_t W, uint64_t T, const uint32_t* schedule, uint
         tau[a] = k - iter[i];
         iter[i] = k;
     }
+}
+
+// App. D: wall-clock time to process W*iters batches.  SSGD: every iteration waits for the slowest
+// of the W workers.  ASGD: the master serves arrivals as they come (the schedule above); the run
+// ends with arrival number W*iters.  Batch times only, no communication.
+void speedup_times(uint32_t W, uint64_t iters, const TimeModel& tm, uint64_t seed, double* asgd_wall,
+                   double* ssgd_wall) {
+    double sync = 0.0;
+    for (uint64_t i = 0; i < iters; ++i) {
+        double slowest = 0.0;
+        for (uint32_t w = 0; w < W; ++w) slowest = std::fmax(slowest, iteration_time(tm, seed, w, i));
+        sync += slowest;
+    }
+    typedef std::pair<double, uint32_t> Ev;
+    std::priority_queue<Ev, std::vector<Ev>, std::greater<Ev>> pq;
+    std::vector<uint64_t> n_done(W, 0);
+    for (uint32_t w = 0; w < W; ++w) pq.push(Ev(iteration_time(tm, seed, w, 0), w));
+    double last = 0.0;
+    for (uint64_t k = 0; k < (uint64_t)W * iters; ++k) {
+        const Ev ev = pq.top();
+        pq.pop();
+        last = ev.first;
+        n_done[ev.second] += 1;
+        pq.push(Ev(ev.first + iteration_time(tm, seed, ev.second, n_done[ev.second]), ev.second));
+    }
+    *asgd_wall = last;
+    *ssgd_wall = sync;
 }
 
 // ---------------------------------------------------------------------------
@@ -632,13 +716,38 @@ void orc_noise_fill_ref(uint64_t seed, uint64_t k, uint64_t j0, uint64_t n, doub
 }
 
 double orc_iteration_time(int dist, double sigma, uint64_t seed, uint32_t w, uint64_t n) {
-    return iteration_time(dist, sigma, seed, w, n);
+    const TimeModel tm = {dist, sigma, 0.0, 0.0, 0.0};
+    return iteration_time(tm, seed, w, n);
+}
+double orc_iteration_time_gamma(int dist, double mean, double v_mach, double v_task, uint64_t seed, uint32_t w,
+                                uint64_t n) {
+    const TimeModel tm = {dist, 0.0, mean, v_mach, v_task};
+    return iteration_time(tm, seed, w, n);
+}
+double orc_gamma_draw(double alpha, double scale, uint64_t seed, uint64_t n) {
+    return gamma_draw(alpha, scale, seed, (uint32_t)n, (uint32_t)(n >> 32), 0, 3);
 }
 
 int orc_simulate_schedule(uint32_t W, uint64_t T, int dist, double sigma, uint64_t seed,
                           uint32_t* schedule, double* finish_times) {
     if (W == 0 || dist < DIST_EXP || dist > DIST_HETERO) return -1;
-    simulate_schedule(W, T, dist, sigma, seed, schedule, finish_times);
+    const TimeModel tm = {dist, sigma, 0.0, 0.0, 0.0};
+    simulate_schedule(W, T, tm, seed, schedule, finish_times);
+    return 0;
+}
+int orc_simulate_schedule_gamma(uint32_t W, uint64_t T, int dist, double mean, double v_mach, double v_task,
+                                uint64_t seed, uint32_t* schedule, double* finish_times) {
+    if (W == 0 || (dist != DIST_GAMMA_HOMO && dist != DIST_GAMMA_HETERO)) return -1;
+    if (!(mean > 0) || !(v_mach > 0 && v_mach <= 1) || !(v_task > 0 && v_task <= 1)) return -1;
+    const TimeModel tm = {dist, 0.0, mean, v_mach, v_task};
+    simulate_schedule(W, T, tm, seed, schedule, finish_times);
+    return 0;
+}
+int orc_speedup_times(uint32_t W, uint64_t iters, int dist, double mean, double v_mach, double v_task,
+                      uint64_t seed, double* asgd_wall, double* ssgd_wall) {
+    if (W == 0 || (dist != DIST_GAMMA_HOMO && dist != DIST_GAMMA_HETERO)) return -1;
+    const TimeModel tm = {dist, 0.0, mean, v_mach, v_task};
+    speedup_times(W, iters, tm, seed, asgd_wall, ssgd_wall);
     return 0;
 }
 

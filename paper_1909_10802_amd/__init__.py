@@ -21,7 +21,7 @@ GA_ARR_THETA, GA_ARR_V, GA_ARR_M, GA_ARR_SNAPSHOT, GA_ARR_WORKER_V, GA_ARR_ADAM_
 GA_GAP_PARAMETER, GA_GAP_LAYER, GA_GAP_GLOBAL = range(3)
 GA_F32, GA_BF16 = 0, 1
 GA_OK, GA_ERR_ARG, GA_ERR_WORKER, GA_ERR_ALIGN, GA_ERR_STATE, GA_ERR_HIP = 0, -1, -2, -3, -4, -5
-GA_DIST_EXP, GA_DIST_LOGNORMAL, GA_DIST_HETERO = range(3)
+GA_DIST_EXP, GA_DIST_LOGNORMAL, GA_DIST_HETERO, GA_DIST_GAMMA_HOMO, GA_DIST_GAMMA_HETERO = range(5)
 GA_SRC_QUADRATIC_NOISE, GA_SRC_BUFFERS = 0, 1
 GA_PICK_BY_WORKER, GA_PICK_BY_ARRIVAL = 0, 1
 
@@ -56,6 +56,11 @@ class ga_config(C.Structure):
                 ("host_layer_sizes", C.c_void_p)]
 
 
+class ga_time_model(C.Structure):
+    _fields_ = [("dist", C.c_int), ("sigma", C.c_double), ("mean", C.c_double), ("v_mach", C.c_double),
+                ("v_task", C.c_double)]
+
+
 class ga_arrival(C.Structure):
     _fields_ = [("worker", C.c_uint32), ("tau", C.c_float), ("lr", C.c_float), ("inv_bc_prev", C.c_float)]
 
@@ -67,6 +72,8 @@ _u64, _u32, _i, _f, _d, _p = C.c_uint64, C.c_uint32, C.c_int, C.c_float, C.c_dou
 # name -> (restype, argtypes); every symbol include/ga.h declares
 SIGNATURES = {
     "ga_simulate_schedule": (_i, [_u32, _u64, _i, _d, _u64, _p]),
+    "ga_simulate_schedule_ex": (_i, [_u32, _u64, C.POINTER(ga_time_model), _u64, _p, _p]),
+    "ga_simulate_speedup": (_i, [_u32, _u64, C.POINTER(ga_time_model), _u64, C.POINTER(_d), C.POINTER(_d)]),
     "ga_delays_from_schedule": (_i, [_u32, _u64, _p, _u64, _p, _p]),
     "ga_plan_arrivals": (_i, [_u32, _u64, _p, _u64, _p, _i, _f, _f, _p]),
     "ga_config_init": (None, [C.POINTER(ga_config)]),
@@ -155,6 +162,25 @@ def ga_simulate_schedule(n_workers, T, dist=GA_DIST_EXP, sigma=1.0, seed=0):
     out = np.empty(T, dtype=np.uint32)
     _check(lib().ga_simulate_schedule(n_workers, T, dist, sigma, seed, _np_ptr(out)))
     return out
+
+
+def time_model(dist, sigma=1.0, mean=128.0, v_mach=0.1, v_task=0.1):
+    return ga_time_model(dist, sigma, mean, v_mach, v_task)
+
+
+def ga_simulate_schedule_ex(n_workers, T, model, seed=0, with_times=False):
+    out = np.empty(T, dtype=np.uint32)
+    times = np.empty(T, dtype=np.float64) if with_times else None
+    _check(lib().ga_simulate_schedule_ex(n_workers, T, C.byref(model), seed, _np_ptr(out),
+                                         None if times is None else _np_ptr(times)))
+    return (out, times) if with_times else out
+
+
+def ga_simulate_speedup(n_workers, iters, model, seed=0):
+    """(ASGD wall time, SSGD wall time) for n_workers * iters batches."""
+    a, s = _d(), _d()
+    _check(lib().ga_simulate_speedup(n_workers, iters, C.byref(model), seed, C.byref(a), C.byref(s)))
+    return a.value, s.value
 
 
 def ga_delays_from_schedule(n_workers, schedule, k0=0, host_iter=None):

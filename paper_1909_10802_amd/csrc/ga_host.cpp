@@ -158,27 +158,89 @@ double normal_of(const Block4& b) {          // Box-Muller, double
 constexpr uint32_t kTagTime = 0x54494D45u;   // counter word 3: per-iteration draw
 constexpr uint32_t kTagMean = 0x4D45414Eu;   // counter word 3: per-worker draw
 
+constexpr uint32_t kTagGamma = 0x47000000u;  // counter word 3 of a gamma draw: + 65536 * kind + attempt
+
+// Gamma variate, shape >= 1 (Marsaglia & Tsang, ACM TOMS 26, 2000): squeeze-free form with one
+// normal and one uniform per attempt, both taken from the Philox block of that attempt.
+double gamma_variate(double shape, double scale, uint64_t seed, uint32_t c0, uint32_t c1, uint32_t c2, uint32_t kind) {
+    const double d = shape - 1.0 / 3.0;
+    const double c = 1.0 / std::sqrt(9.0 * d);
+    for (uint32_t attempt = 0; attempt < 65536; ++attempt) {
+        const Block4 b = philox_block(c0, c1, c2, kTagGamma + 65536u * kind + attempt, seed);
+        const double radius = std::sqrt(-2.0 * std::log1p(-unit53(b.w[0], b.w[1])));
+        const double z = radius * std::cos(6.283185307179586476925286766559 * (((double)b.w[2] + 0.5) / 4294967296.0));
+        const double accept = ((double)b.w[3] + 0.5) / 4294967296.0;
+        double v = 1.0 + c * z;
+        if (v <= 0.0) continue;
+        v = v * v * v;
+        if (std::log(accept) < 0.5 * z * z + d - d * v + d * std::log(v)) return d * v * scale;
+    }
+    return std::nan("");
+}
+
 class TimeModel {
   public:
-    TimeModel(int dist, double sigma, uint64_t seed, uint32_t W) : dist_(dist), sigma_(sigma), seed_(seed) {
-        if (dist == GA_DIST_HETERO) {
+    TimeModel(const ga_time_model& m, uint64_t seed, uint32_t W) : m_(m), seed_(seed) {
+        if (m.dist == GA_DIST_HETERO) {
             mean_.resize(W);
-            for (uint32_t w = 0; w < W; ++w) mean_[w] = std::exp(sigma * normal_of(philox_block(w, 0, 0, kTagMean, seed)));
+            for (uint32_t w = 0; w < W; ++w) mean_[w] = std::exp(m.sigma * normal_of(philox_block(w, 0, 0, kTagMean, seed)));
+        } else if (m.dist == GA_DIST_GAMMA_HOMO) {          // Alg. 12: one q for the whole run
+            a_task_ = 1.0 / (m.v_task * m.v_task);
+            a_mach_ = 1.0 / (m.v_mach * m.v_mach);
+            mean_.assign(1, gamma_variate(a_task_, m.mean / a_task_, seed, 0, 0, 0, 1));
+        } else if (m.dist == GA_DIST_GAMMA_HETERO) {        // Alg. 13: one p per machine
+            a_task_ = 1.0 / (m.v_task * m.v_task);
+            a_mach_ = 1.0 / (m.v_mach * m.v_mach);
+            mean_.resize(W);
+            for (uint32_t w = 0; w < W; ++w) mean_[w] = gamma_variate(a_mach_, m.mean / a_mach_, seed, w, 0, 0, 2);
         }
     }
     double draw(uint32_t w, uint64_t n) const {
+        if (m_.dist == GA_DIST_GAMMA_HOMO)
+            return gamma_variate(a_mach_, mean_[0] / a_mach_, seed_, (uint32_t)n, (uint32_t)(n >> 32), w, 0);
+        if (m_.dist == GA_DIST_GAMMA_HETERO)
+            return gamma_variate(a_task_, mean_[w] / a_task_, seed_, (uint32_t)n, (uint32_t)(n >> 32), w, 0);
         const Block4 b = philox_block((uint32_t)n, (uint32_t)(n >> 32), w, kTagTime, seed_);
-        if (dist_ == GA_DIST_LOGNORMAL) return std::exp(sigma_ * normal_of(b));
+        if (m_.dist == GA_DIST_LOGNORMAL) return std::exp(m_.sigma * normal_of(b));
         const double e = -std::log1p(-unit53(b.w[0], b.w[1]));
-        return dist_ == GA_DIST_HETERO ? mean_[w] * e : e;
+        return m_.dist == GA_DIST_HETERO ? mean_[w] * e : e;
     }
 
   private:
-    int dist_;
-    double sigma_;
+    ga_time_model m_;
     uint64_t seed_;
+    double a_task_ = 0.0, a_mach_ = 0.0;
     std::vector<double> mean_;
 };
+
+int check_time_model(const ga_time_model* m) {
+    if (!m) return fail(nullptr, GA_ERR_ARG, "time model is null");
+    if (m->dist < GA_DIST_EXP || m->dist > GA_DIST_GAMMA_HETERO) return fail(nullptr, GA_ERR_ARG, "unknown time distribution %d", m->dist);
+    if ((m->dist == GA_DIST_LOGNORMAL || m->dist == GA_DIST_HETERO) && !(m->sigma >= 0.0 && std::isfinite(m->sigma)))
+        return fail(nullptr, GA_ERR_ARG, "time model: sigma must be finite and >= 0");
+    if (m->dist == GA_DIST_GAMMA_HOMO || m->dist == GA_DIST_GAMMA_HETERO) {
+        if (!(m->mean > 0.0) || !std::isfinite(m->mean)) return fail(nullptr, GA_ERR_ARG, "time model: mean must be finite and > 0");
+        if (!(m->v_mach > 0.0 && m->v_mach <= 1.0) || !(m->v_task > 0.0 && m->v_task <= 1.0))
+            return fail(nullptr, GA_ERR_ARG, "time model: v_mach and v_task must be in (0, 1]");
+    }
+    return GA_OK;
+}
+
+// FIFO service of the workers' finish times; ties to the lowest id.  Calls visit(arrival, worker, time).
+template <typename Visit>
+void replay_arrivals(const TimeModel& model, uint32_t W, uint64_t T, Visit visit) {
+    std::vector<double> finish(W);
+    std::vector<uint64_t> done(W, 0);
+    for (uint32_t w = 0; w < W; ++w) finish[w] = model.draw(w, 0);
+    for (uint64_t a = 0; a < T; ++a) {
+        uint32_t first = 0;                     // earliest finish; strict '<' keeps the lowest id on ties
+        for (uint32_t w = 1; w < W; ++w)
+            if (finish[w] < finish[first]) first = w;
+        visit(a, first, finish[first]);
+        done[first] += 1;
+        finish[first] = finish[first] + model.draw(first, done[first]);
+    }
+}
 
 // ----------------------------------------------------------- per-arrival scalars
 ga_arrival make_row(uint32_t worker, uint64_t k, uint64_t tau, int mode, float eta_k, float beta) {
@@ -294,24 +356,45 @@ const char* ga_version(void) { return "0.1"; }
 const char* ga_last_error(const ga_ctx* ctx) { return ctx ? ctx->err.c_str() : g_create_error.c_str(); }
 
 // ------------------------------------------------------------------ host only
+int ga_simulate_schedule_ex(uint32_t n_workers, uint64_t T, const ga_time_model* model, uint64_t seed,
+                            uint32_t* host_schedule, double* host_finish_times) {
+    if (n_workers == 0 || (T > 0 && !host_schedule)) return fail(nullptr, GA_ERR_ARG, "simulate_schedule: bad argument");
+    const int rc = check_time_model(model);
+    if (rc != GA_OK) return rc;
+    const TimeModel tm(*model, seed, n_workers);
+    replay_arrivals(tm, n_workers, T, [&](uint64_t a, uint32_t w, double t) {
+        host_schedule[a] = w;
+        if (host_finish_times) host_finish_times[a] = t;
+    });
+    return GA_OK;
+}
+
 int ga_simulate_schedule(uint32_t n_workers, uint64_t T, int dist, double sigma, uint64_t seed,
                          uint32_t* host_schedule) {
-    if (n_workers == 0 || (T > 0 && !host_schedule)) return fail(nullptr, GA_ERR_ARG, "simulate_schedule: bad argument");
     if (dist < GA_DIST_EXP || dist > GA_DIST_HETERO) return fail(nullptr, GA_ERR_ARG, "simulate_schedule: unknown distribution");
-    if ((dist != GA_DIST_EXP) && !(sigma >= 0.0 && std::isfinite(sigma)))
-        return fail(nullptr, GA_ERR_ARG, "simulate_schedule: sigma must be finite and >= 0");
-    const TimeModel model(dist, sigma, seed, n_workers);
-    std::vector<double> finish(n_workers);
-    std::vector<uint64_t> done(n_workers, 0);
-    for (uint32_t w = 0; w < n_workers; ++w) finish[w] = model.draw(w, 0);
-    for (uint64_t a = 0; a < T; ++a) {
-        uint32_t first = 0;                     // earliest finish; strict '<' keeps the lowest id on ties
-        for (uint32_t w = 1; w < n_workers; ++w)
-            if (finish[w] < finish[first]) first = w;
-        host_schedule[a] = first;
-        done[first] += 1;
-        finish[first] = finish[first] + model.draw(first, done[first]);
+    const ga_time_model m = {dist, sigma, 0.0, 0.0, 0.0};
+    return ga_simulate_schedule_ex(n_workers, T, &m, seed, host_schedule, nullptr);
+}
+
+int ga_simulate_speedup(uint32_t n_workers, uint64_t iters, const ga_time_model* model, uint64_t seed,
+                        double* asgd_wall, double* ssgd_wall) {
+    if (n_workers == 0 || !asgd_wall || !ssgd_wall) return fail(nullptr, GA_ERR_ARG, "simulate_speedup: bad argument");
+    const int rc = check_time_model(model);
+    if (rc != GA_OK) return rc;
+    const TimeModel tm(*model, seed, n_workers);
+    double sync = 0.0;
+    for (uint64_t i = 0; i < iters; ++i) {          // SSGD: a barrier after every batch
+        double slowest = 0.0;
+        for (uint32_t w = 0; w < n_workers; ++w) {
+            const double t = tm.draw(w, i);
+            if (t > slowest) slowest = t;
+        }
+        sync += slowest;
     }
+    double last = 0.0;
+    replay_arrivals(tm, n_workers, (uint64_t)n_workers * iters, [&](uint64_t, uint32_t, double t) { last = t; });
+    *asgd_wall = last;
+    *ssgd_wall = sync;
     return GA_OK;
 }
 
