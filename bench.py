@@ -171,7 +171,8 @@ def bench_persistent(args, cfg, torch, ga, ga_inputs):
     a, ts = ga_inputs.device_curvatures(N, seed, dev), ga_inputs.device_optimum(N, seed, dev)
     src = ga.quadratic_source(a, ts, seed, 0.01, persistent=True)
     sched = ga.ga_simulate_schedule(W, K + Wm + 1, ga_inputs.DIST_CODES[cfg["dist"]], cfg["sigma"], seed)
-    M = ga.Master(N, W, eta=cfg["eta"], gamma=cfg["gamma"], mode=args.mode, device=dev)
+    eta = 0.01 if args.family == "adam" else cfg["eta"]
+    M = ga.Master(N, W, eta=eta, gamma=cfg["gamma"], mode=args.mode, device=dev, family=args.family)
     M.run_schedule(sched[:Wm], src)
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -184,19 +185,21 @@ def bench_persistent(args, cfg, torch, ga, ga_inputs):
     wall = time.perf_counter() - t0
     kernel_s = e0.elapsed_time(e1) * 1e-3                            # all chunks of the schedule
     ups = N * K / kernel_s
-    if args.mode in VALU_PER_UPDATE:
+    if args.mode in VALU_PER_UPDATE and args.family == "momentum":
         ach = ups * VALU_PER_UPDATE[args.mode] / 1e12
         roof = {"bound": "alu", "achieved": ach, "peak": ALU_PEAK_TLOPS, "unit": "T lane-op/s",
                 "frac": ach / ALU_PEAK_TLOPS, "traffic": None, "kernel": "persistent_kernel",
                 "valu_ops_per_update": VALU_PER_UPDATE[args.mode], "hbm_GBs_at_8B_per_update": 8 * ups / 1e9}
     else:
-        ach = 8 * ups / 1e9
+        bpu = 16 if args.family == "dana" else 8       # snapshot row (and DANA's worker momentum row) read + written
+        ach = bpu * ups / 1e9
         roof = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
-                "traffic": None, "kernel": "persistent_kernel", "bytes_per_update": 8}
+                "traffic": None, "kernel": "persistent_kernel", "bytes_per_update": bpu}
     roof["kernel_ms_total"] = kernel_s * 1e3
     theta = M.theta()
     desc = ("%s: N=%d float parameters, %d workers, %s iteration times, quadratic-plus-noise gradients generated in "
-            "the persistent multi-arrival kernel, mode %s" % (args.workload, N, W, cfg["dist"], args.mode))
+            "the persistent multi-arrival kernel, family %s, mode %s" % (args.workload, N, W, cfg["dist"], args.family,
+                                                                        args.mode))
     extra = {"theta_finite": bool(torch.isfinite(theta).all().item()),
              "mean_gap_last": None if last_diag is None else last_diag["mean_graw"] + 1.0}
     return wall, roof, desc, extra
@@ -241,8 +244,8 @@ def main():
         args.steps = cfg["T"]
     torch.cuda.set_device(0)
     fused = cfg["source"] == "buffers"
-    if not fused and args.family != "momentum":
-        sys.exit("bench.py: the persistent-kernel workloads exist for the momentum family only")
+    if not fused and args.gap_scope != "parameter":
+        sys.exit("bench.py: the persistent-kernel workloads use the parameter-wise Gap")
     wall, roof, desc, extra = (bench_fused if fused else bench_persistent)(args, cfg, torch, ga, ga_inputs)
     N, K = cfg["N"], args.steps
     out = {

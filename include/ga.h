@@ -144,7 +144,7 @@ enum ga_pick { GA_PICK_BY_WORKER = 0, GA_PICK_BY_ARRIVAL = 1 };
  *       g = a[j] * (theta_w[j] - theta_star[j]) + sigma * z(seed, k, j)
  *   with z the counter-based standard normal documented at ga_noise_fill.
  *   dev_a and dev_theta_star are device arrays of N floats, 16-byte aligned.
- *   persistent != 0 (MOMENTUM family only): all arrivals are replayed inside
+ *   persistent != 0 (parameter-wise Gap only): all arrivals are replayed inside
  *   one kernel per chunk of the schedule (no per-arrival launch); persistent == 0: one gradient launch
  *   and one update launch per arrival, through dev_scratch_g (N floats,
  *   16-byte aligned device buffer, required in that case only).
@@ -196,7 +196,8 @@ typedef struct ga_arrival {
  * divided by G_p.  GLOBAL is Def. 1: one layer holding all parameters.  The
  * two sums are accumulated in double and rounded once to float.  LAYER and
  * GLOBAL exist for the MOMENTUM family in the two GA modes, one arrival per
- * launch sequence (reduce, per-layer Gap, update); not in the persistent kernel. */
+ * launch sequence (reduce, per-layer Gap, update); not in the persistent kernel,
+ * which would need a grid-wide reduction per arrival. */
 enum ga_gap_scope { GA_GAP_PARAMETER = 0, GA_GAP_LAYER = 1, GA_GAP_GLOBAL = 2 };
 
 /* Full configuration of a master, for ga_create_ex.  Fill with ga_config_init

@@ -26,6 +26,7 @@ struct ga_ctx {
     hipStream_t stream = nullptr;
     ga::StatePtrs st{};
     ga_arrival* dev_table = nullptr;
+    ga::AdamRow* dev_adam_table = nullptr;
     ga::DiagPartial* dev_partials = nullptr;
     uint64_t k = 0;
     std::vector<uint64_t> iter;
@@ -64,7 +65,7 @@ uint64_t round_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
 struct Layout {
     uint64_t Np, n_rows;
     size_t off_theta, off_v, off_m, off_snaps, off_worker_v, off_v2, off_table, off_partials, total;
-    size_t off_chunks, off_spans, off_layer_partials, off_gaps;
+    size_t off_chunks, off_spans, off_layer_partials, off_gaps, off_adam_table;
 };
 
 // Chunks of at most kLayerChunk parameters, never across a layer boundary.  sizes == nullptr: one layer of N.
@@ -108,7 +109,8 @@ Layout layout_for(uint64_t N, uint32_t W, int family, uint64_t n_chunks = 0, uin
         L.n_rows += 1;
     }
     L.off_table = L.n_rows * row;
-    L.off_partials = L.off_table + round_up((uint64_t)ga::kTableCap * sizeof(ga_arrival), 256);
+    L.off_adam_table = L.off_table + round_up((uint64_t)ga::kTableCap * sizeof(ga_arrival), 256);
+    L.off_partials = L.off_adam_table + round_up((uint64_t)ga::kTableCap * sizeof(ga::AdamRow), 256);
     L.total = L.off_partials + round_up((uint64_t)(ga::kDiagMaxBlocks + 1) * sizeof(ga::DiagPartial), 256);
     L.off_chunks = L.total;
     L.off_spans = L.off_chunks + round_up(n_chunks * sizeof(ga::LayerChunk), 256);
@@ -295,6 +297,11 @@ ga::RunConst run_const(const ga_ctx* c, const ga_grad_source* src) {
     r.eps = c->eps;
     r.beta = c->beta;
     r.one_minus_beta = 1.0f - c->beta;
+    r.beta1 = c->beta1;
+    r.omb1 = 1.0f - c->beta1;
+    r.beta2 = c->beta2;
+    r.omb2 = 1.0f - c->beta2;
+    r.adam_eps = c->adam_eps;
     r.sigma = src->sigma;
     r.seed_lo = (uint32_t)src->seed;
     r.seed_hi = (uint32_t)(src->seed >> 32);
@@ -535,6 +542,7 @@ int ga_create_ex(ga_ctx** out, const ga_config* cfg, void* dev_workspace, size_t
     c->st.v2 = L.off_v2 ? reinterpret_cast<float*>(base + L.off_v2) : nullptr;
     c->st.stride = L.Np;
     c->dev_table = reinterpret_cast<ga_arrival*>(base + L.off_table);
+    c->dev_adam_table = reinterpret_cast<ga::AdamRow*>(base + L.off_adam_table);
     c->dev_partials = reinterpret_cast<ga::DiagPartial*>(base + L.off_partials);
     c->iter.assign(n_workers, 0);
     c->rows.reserve(ga::kTableCap);
@@ -662,8 +670,8 @@ int ga_run_schedule(ga_ctx* ctx, const uint32_t* host_schedule, uint64_t T, cons
     if (rc != GA_OK) return rc;
     const ga::RunConst rcst = run_const(ctx, src);
 
-    if (src->persistent && (ctx->family != GA_FAMILY_MOMENTUM || ctx->gap_scope != GA_GAP_PARAMETER))
-        return fail(ctx, GA_ERR_ARG, "run_schedule: the persistent kernel exists for the momentum family with the parameter-wise Gap only");
+    if (src->persistent && ctx->gap_scope != GA_GAP_PARAMETER)
+        return fail(ctx, GA_ERR_ARG, "run_schedule: the persistent kernel exists for the parameter-wise Gap only");
 
     if (!src->persistent) {
         // one gradient launch and one update launch per arrival; the worker reads its snapshot,
@@ -693,8 +701,17 @@ int ga_run_schedule(ga_ctx* ctx, const uint32_t* host_schedule, uint64_t T, cons
         hipError_t e = hipMemcpyAsync(ctx->dev_table, ctx->rows.data(), (size_t)n * sizeof(ga_arrival),
                                       hipMemcpyHostToDevice, ctx->stream);
         if (e != hipSuccess) return hip_fail(ctx, e, "table upload");
-        e = ga::launch_persistent(ctx->st, ctx->N, ctx->dev_table, n, ctx->k, src->dev_a, src->dev_theta_star, ctx->mode,
-                                  keeps_m(ctx), rcst, ctx->stream);
+        if (ctx->family == GA_FAMILY_ADAM) {
+            std::vector<ga::AdamRow> ar(n);
+            for (uint32_t a = 0; a < n; ++a) {
+                ar[a].inv_bc1 = inverse_bias_correction(ctx->beta1, ctx->k + a + 1);
+                ar[a].inv_bc2 = inverse_bias_correction(ctx->beta2, ctx->k + a + 1);
+            }
+            e = hipMemcpyAsync(ctx->dev_adam_table, ar.data(), (size_t)n * sizeof(ga::AdamRow), hipMemcpyHostToDevice, ctx->stream);
+            if (e != hipSuccess) return hip_fail(ctx, e, "table upload");
+        }
+        e = ga::launch_persistent(ctx->st, ctx->N, ctx->family, ctx->dev_table, ctx->dev_adam_table, n, ctx->k, src->dev_a,
+                                  src->dev_theta_star, ctx->mode, keeps_m(ctx), rcst, ctx->stream);
         if (e != hipSuccess) return hip_fail(ctx, e, "persistent launch");
         ctx->delays.insert(ctx->delays.end(), taus.begin(), taus.end());
         ctx->iter.swap(iter_after);

@@ -30,8 +30,14 @@ struct StepConst {
 // Scalars that are uniform over a whole schedule chunk.
 struct RunConst {
     float gamma, eta_max, eps, beta, one_minus_beta;
+    float beta1, omb1, beta2, omb2, adam_eps;   // ADAM
     float sigma;       // noise scale of the quadratic source
     uint32_t seed_lo, seed_hi;
+};
+
+// Per-arrival Adam bias corrections, parallel to the arrival table.
+struct AdamRow {
+    float inv_bc1, inv_bc2;   // (float)(1 / (1 - beta1^k)), (float)(1 / (1 - beta2^k))
 };
 
 // Reduction partial of the diagnostics kernel (one per block, then one total).
@@ -93,9 +99,9 @@ hipError_t launch_apply_layerwise(const StatePtrs& st, uint64_t N, uint32_t work
 
 // T arrivals replayed inside one launch, gradients generated in the kernel.
 // table: device array of T rows; k0: master step before the first row.
-hipError_t launch_persistent(const StatePtrs& st, uint64_t N, const ga_arrival* dev_table, uint32_t T, uint64_t k0,
-                             const float* a, const float* theta_star, int mode, bool keep_m, const RunConst& rc,
-                             hipStream_t stream);
+hipError_t launch_persistent(const StatePtrs& st, uint64_t N, int family, const ga_arrival* dev_table,
+                             const AdamRow* dev_adam_table, uint32_t T, uint64_t k0, const float* a,
+                             const float* theta_star, int mode, bool keep_m, const RunConst& rc, hipStream_t stream);
 
 // g_out = a * (snap_w - theta_star) + sigma * z(seed, k, j)
 hipError_t launch_quadratic_gradient(const StatePtrs& st, uint64_t N, uint32_t worker, const float* a,

@@ -622,17 +622,22 @@ __global__ __launch_bounds__(kBlock) void quadratic_gradient_kernel(const float*
 // Persistent multi-arrival kernel.  Thread = one group of four parameters.
 // theta, v, m, a, theta* stay in registers for the whole chunk; per arrival
 // the thread reads and rewrites only its 16 bytes of the arriving worker's
-// snapshot.  No thread ever needs another thread's data, so there is no
+// snapshot (DANA: and of that worker's momentum; Adam keeps m1 and v2 in
+// registers too).  No thread ever needs another thread's data, so there is no
 // grid-wide or block-wide synchronisation.  The snapshot of the next arrival
 // is requested before the arithmetic of the current one.
 // ---------------------------------------------------------------------------
-template <int MODE, bool KEEP_M>
-__global__ __launch_bounds__(kBlock) void persistent_kernel(float* __restrict__ theta, float* __restrict__ v,
-                                                            float* __restrict__ m, float* snaps, uint64_t stride,
+template <int FAMILY, int MODE, bool KEEP_M>
+__global__ __launch_bounds__(kBlock) void persistent_kernel(float* __restrict__ theta, float* __restrict__ x,
+                                                            float* __restrict__ m, float* snaps, float* worker_v,
+                                                            float* __restrict__ v2, uint64_t stride,
                                                             const float* __restrict__ a,
                                                             const float* __restrict__ ts,
-                                                            const ga_arrival* __restrict__ table, uint32_t T,
+                                                            const ga_arrival* __restrict__ table,
+                                                            const AdamRow* __restrict__ adam_table, uint32_t T,
                                                             uint64_t k0, uint64_t N, RunConst rc) {
+    constexpr bool DANA = (FAMILY == GA_FAMILY_DANA);
+    constexpr bool ADAM = (FAMILY == GA_FAMILY_ADAM);
     const uint64_t q = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
     const uint64_t j0 = 4 * q;
     if (j0 >= N || T == 0) return;
@@ -640,9 +645,11 @@ __global__ __launch_bounds__(kBlock) void persistent_kernel(float* __restrict__ 
 
     // state arrays are padded to a multiple of 64 floats: the 128-bit access is always in bounds
     f32x4 th = reinterpret_cast<const f32x4*>(theta)[q];
-    f32x4 vv = reinterpret_cast<const f32x4*>(v)[q];
+    f32x4 xx = reinterpret_cast<const f32x4*>(x)[q];          // v | sum_j v_j | m1
     f32x4 mm = {0.f, 0.f, 0.f, 0.f};
     if constexpr (KEEP_M) mm = reinterpret_cast<const f32x4*>(m)[q];
+    f32x4 yy = {0.f, 0.f, 0.f, 0.f};                          // ADAM: v2 (registers); DANA: v_i of the arriving worker
+    if constexpr (ADAM) yy = reinterpret_cast<const f32x4*>(v2)[q];
     f32x4 a4, t4;
     if (n_valid == 4) {
         a4 = reinterpret_cast<const f32x4*>(a)[q];
@@ -657,22 +664,32 @@ __global__ __launch_bounds__(kBlock) void persistent_kernel(float* __restrict__ 
     StepConst c = {};
     c.gamma = rc.gamma; c.eta_max = rc.eta_max; c.eps = rc.eps; c.beta = rc.beta;
     c.one_minus_beta = rc.one_minus_beta;
+    c.beta1 = rc.beta1; c.omb1 = rc.omb1; c.beta2 = rc.beta2; c.omb2 = rc.omb2; c.adam_eps = rc.adam_eps;
 
-    f32x4* const snap_q = reinterpret_cast<f32x4*>(snaps) + q;       // this thread's column
+    f32x4* const snap_q = reinterpret_cast<f32x4*>(snaps) + q;       // this thread's column of the snapshots
+    f32x4* const wv_q = reinterpret_cast<f32x4*>(worker_v) + q;      // DANA: and of the worker momenta
     const uint64_t stride4 = stride >> 2;
     ga_arrival row = table[0];
     f32x4 s = snap_q[(uint64_t)row.worker * stride4];
+    if constexpr (DANA) yy = wv_q[(uint64_t)row.worker * stride4];
 
     for (uint32_t t = 0; t < T; ++t) {
         const bool more = (t + 1 < T);
         ga_arrival next = row;
-        f32x4 s_next = s;
+        f32x4 s_next = s, y_next = yy;
         if (more) {
             next = table[t + 1];
             s_next = snap_q[(uint64_t)next.worker * stride4];
+            if constexpr (DANA) y_next = wv_q[(uint64_t)next.worker * stride4];
         }
         const uint64_t k = k0 + t + 1;
         c.lr = row.lr; c.tau = row.tau; c.inv_bc_prev = row.inv_bc_prev;
+        if constexpr (DANA) c.eta_gamma = row.lr * rc.gamma;
+        if constexpr (ADAM) {
+            const AdamRow ar = adam_table[t];
+            c.inv_bc1 = ar.inv_bc1;
+            c.inv_bc2 = ar.inv_bc2;
+        }
         const f32x4 z = noise4(rc.seed_lo, rc.seed_hi, q, k);
 
         f32x4 g;
@@ -680,17 +697,36 @@ __global__ __launch_bounds__(kBlock) void persistent_kernel(float* __restrict__ 
         g.y = quadratic_g(s.y, a4.y, t4.y, rc.sigma, z.y);
         g.z = quadratic_g(s.z, a4.z, t4.z, rc.sigma, z.z);
         g.w = quadratic_g(s.w, a4.w, t4.w, rc.sigma, z.w);
-        update4<MODE, KEEP_M>(th, vv, mm, s, g, c, n_valid);
 
-        snap_q[(uint64_t)row.worker * stride4] = th;     // padding lanes of th are never modified
-        // same worker twice in a row: its snapshot is what was just written
-        s = (next.worker == row.worker) ? th : s_next;
+        f32x4 out = s;                                       // what the worker is sent; padding lanes unchanged
+        if constexpr (FAMILY == GA_FAMILY_MOMENTUM) {
+            update4<MODE, KEEP_M>(th, xx, mm, s, g, c, n_valid);
+            out = th;
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if ((uint32_t)e < n_valid) {
+                    float t1 = th[e], x1 = xx[e], y1 = yy[e], m1 = mm[e];
+                    if constexpr (DANA) out[e] = dana_one<MODE, KEEP_M>(t1, x1, y1, m1, s[e], g[e], c);
+                    else out[e] = adam_one<MODE, KEEP_M>(t1, x1, y1, m1, s[e], g[e], c);
+                    th[e] = t1; xx[e] = x1; yy[e] = y1; mm[e] = m1;
+                }
+            }
+        }
+
+        snap_q[(uint64_t)row.worker * stride4] = out;
+        if constexpr (DANA) wv_q[(uint64_t)row.worker * stride4] = yy;
+        // same worker twice in a row: its rows are what was just written
+        const bool same = (next.worker == row.worker);
+        s = same ? out : s_next;
+        if constexpr (DANA) yy = same ? yy : y_next;
         row = next;
     }
 
     reinterpret_cast<f32x4*>(theta)[q] = th;
-    reinterpret_cast<f32x4*>(v)[q] = vv;
+    reinterpret_cast<f32x4*>(x)[q] = xx;
     if constexpr (KEEP_M) reinterpret_cast<f32x4*>(m)[q] = mm;
+    if constexpr (ADAM) reinterpret_cast<f32x4*>(v2)[q] = yy;
 }
 
 // ---------------------------------------------------------------------------
@@ -973,28 +1009,33 @@ hipError_t launch_apply_layerwise(const StatePtrs& st, uint64_t N, uint32_t work
     return hipGetLastError();
 }
 
-hipError_t launch_persistent(const StatePtrs& st, uint64_t N, const ga_arrival* dev_table, uint32_t T, uint64_t k0,
-                             const float* a, const float* theta_star, int mode, bool keep_m, const RunConst& rc,
-                             hipStream_t stream) {
+hipError_t launch_persistent(const StatePtrs& st, uint64_t N, int family, const ga_arrival* dev_table,
+                             const AdamRow* dev_adam_table, uint32_t T, uint64_t k0, const float* a,
+                             const float* theta_star, int mode, bool keep_m, const RunConst& rc, hipStream_t stream) {
     const uint64_t groups = (N + 3) >> 2;
     const uint64_t blocks = (groups + kBlock - 1) / kBlock;
     if (blocks == 0 || blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
     const dim3 grid((uint32_t)blocks), block(kBlock);
-#define GA_LAUNCH_PERSIST(MODE, KEEP)                                                                               \
-    hipLaunchKernelGGL((persistent_kernel<MODE, KEEP>), grid, block, 0, stream, st.theta, st.v, st.m, st.snaps,     \
-                       st.stride, a, theta_star, dev_table, T, k0, N, rc)
-    switch (mode) {
-        case GA_MODE_GA: GA_LAUNCH_PERSIST(GA_MODE_GA, true); break;
-        case GA_MODE_GA_HINGE: GA_LAUNCH_PERSIST(GA_MODE_GA_HINGE, true); break;
-        case GA_MODE_SA:
-            if (keep_m) GA_LAUNCH_PERSIST(GA_MODE_SA, true); else GA_LAUNCH_PERSIST(GA_MODE_SA, false);
-            break;
-        case GA_MODE_ASGD:
-        case GA_MODE_SA_STEP:
-            if (keep_m) GA_LAUNCH_PERSIST(GA_MODE_ASGD, true); else GA_LAUNCH_PERSIST(GA_MODE_ASGD, false);
-            break;
-        default: return hipErrorInvalidValue;
+#define GA_LAUNCH_PERSIST(FAM, MODE, KEEP)                                                                          \
+    hipLaunchKernelGGL((persistent_kernel<FAM, MODE, KEEP>), grid, block, 0, stream, st.theta, st.v, st.m, st.snaps, \
+                       st.worker_v, st.v2, st.stride, a, theta_star, dev_table, dev_adam_table, T, k0, N, rc)
+#define GA_PERSIST_MODES(FAM)                                                                                       \
+    switch (mode) {                                                                                                 \
+        case GA_MODE_GA: GA_LAUNCH_PERSIST(FAM, GA_MODE_GA, true); break;                                           \
+        case GA_MODE_GA_HINGE: GA_LAUNCH_PERSIST(FAM, GA_MODE_GA_HINGE, true); break;                               \
+        case GA_MODE_SA:                                                                                            \
+            if (keep_m) GA_LAUNCH_PERSIST(FAM, GA_MODE_SA, true); else GA_LAUNCH_PERSIST(FAM, GA_MODE_SA, false);   \
+            break;                                                                                                  \
+        case GA_MODE_ASGD:                                                                                          \
+        case GA_MODE_SA_STEP:                                                                                       \
+            if (keep_m) GA_LAUNCH_PERSIST(FAM, GA_MODE_ASGD, true); else GA_LAUNCH_PERSIST(FAM, GA_MODE_ASGD, false); \
+            break;                                                                                                  \
+        default: return hipErrorInvalidValue;                                                                       \
     }
+    if (family == GA_FAMILY_DANA) { GA_PERSIST_MODES(GA_FAMILY_DANA) }
+    else if (family == GA_FAMILY_ADAM) { GA_PERSIST_MODES(GA_FAMILY_ADAM) }
+    else { GA_PERSIST_MODES(GA_FAMILY_MOMENTUM) }
+#undef GA_PERSIST_MODES
 #undef GA_LAUNCH_PERSIST
     return hipGetLastError();
 }

@@ -97,20 +97,33 @@ def test_single_step(family, mode, N, dtype):
 
 @pytest.mark.parametrize("family", FAMILIES, ids=["dana", "adam"])
 @pytest.mark.parametrize("mode", PENALTIES, ids=[NAMES[m] for m in PENALTIES])
-def test_trajectory_quadratic(family, mode):
+@pytest.mark.parametrize("persistent", [False, True], ids=["per_arrival", "persistent"])
+def test_trajectory_quadratic(family, mode, persistent):
     N, W, T, seed = 20_003, 8, 200, 4
     eta = 0.1 if family == ga.GA_FAMILY_DANA else 0.01
     a, ts = ga_inputs.curvatures(N, seed), ga_inputs.optimum(N, seed)
     sched = ga.ga_simulate_schedule(W, T, seed=seed)
     M, O = make_pair(family, N, W, mode, eta, track=False)
     scratch = torch.empty(N, dtype=torch.float32, device=DEV)
-    M.run_schedule(sched, ga.quadratic_source(dev(a), dev(ts), seed, 0.01, False, scratch))
+    src = ga.quadratic_source(dev(a), dev(ts), seed, 0.01, persistent, scratch)
+    M.run_schedule(sched[:90], src)                       # two calls: the step counter and Adam's bias corrections carry over
+    M.run_schedule(sched[90:], src)
     O.run_quadratic(sched, a, ts, seed)
     compare(M, O, "%s %s quadratic" % (FNAME[family], NAMES[mode]), keep_m=mode in (3, 4))
     assert rel_l2(host(M.theta()), O.theta) <= RTOL_TRAJ_L2
-    with pytest.raises(ga.GaError) as e:                  # the persistent kernel is momentum-family only
-        M.run_schedule(sched[:3], ga.quadratic_source(dev(a), dev(ts), seed, 0.01, True))
-    assert e.value.status == ga.GA_ERR_ARG
+
+
+@pytest.mark.parametrize("family", FAMILIES, ids=["dana", "adam"])
+def test_persistent_repeated_worker_and_chunks(family):
+    N, W, seed = 1000 + 3, 3, 5
+    eta = 0.05 if family == ga.GA_FAMILY_DANA else 0.01
+    a, ts = ga_inputs.curvatures(N, seed), ga_inputs.optimum(N, seed)
+    rng = np.random.default_rng(2)
+    sched = np.concatenate([[0, 0, 0, 1, 1, 0, 2, 2, 2, 0], np.repeat(rng.integers(0, W, 4200), 2)]).astype(np.uint32)[:8192 + 21]
+    M, O = make_pair(family, N, W, ga.GA_MODE_GA, eta, track=False)
+    M.run_schedule(sched, ga.quadratic_source(dev(a), dev(ts), seed))
+    O.run_quadratic(sched, a, ts, seed)
+    compare(M, O, "%s repeats + chunks" % FNAME[family])
 
 
 @pytest.mark.parametrize("family", FAMILIES, ids=["dana", "adam"])
