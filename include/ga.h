@@ -363,6 +363,13 @@ int ga_set_bookkeeping(ga_ctx* ctx, uint64_t k, const uint64_t* host_iter);
  * it is reproducible bit for bit.  hip_stream as in ga_create. */
 int ga_noise_fill(uint64_t seed, uint64_t k, uint64_t j0, uint64_t n, float* dev_out, void* hip_stream);
 
+/* The Box-Muller transform of ga_noise_fill applied to caller-supplied random
+ * words: for i < n, (dev_zc[i], dev_zs[i]) = (r cos, r sin) from the word pair
+ * (dev_xa[i], dev_xb[i]).  Lets a test sweep every radius input (2^23 values of
+ * xa >> 9) and every angle input (2^25 values of xb >> 7) of the generator. */
+int ga_box_muller_raw(const uint32_t* dev_xa, const uint32_t* dev_xb, uint64_t n, float* dev_zc, float* dev_zs,
+                      void* hip_stream);
+
 /* Message of the last error on this context ("" if none).  ctx may be null:
  * then the message of the last failed ga_create on this thread. */
 const char* ga_last_error(const ga_ctx* ctx);

@@ -53,6 +53,7 @@ def _declare(L):
     L.orc_noise_fill_f32.argtypes = [_u64, _u64, _u64, _u64, _p]
     L.orc_noise_fill_ref.argtypes = [_u64, _u64, _u64, _u64, _p]
     L.orc_philox4x32_10.argtypes = [_p, _p, _p]
+    L.orc_box_muller_raw.argtypes = [_p, _p, _u64, _p, _p]
     L.orc_iteration_time.restype = _f64
     L.orc_iteration_time.argtypes = [_int, _f64, _u64, _u32, _u64]
     L.orc_simulate_schedule.argtypes = [_u32, _u64, _int, _f64, _u64, _p, _p]
@@ -111,6 +112,14 @@ def noise_f32(seed, k, j0, n):
     out = np.empty(n, dtype=np.float32)
     lib().orc_noise_fill_f32(seed, k, j0, n, _ptr(out))
     return out
+
+
+def box_muller_raw(xa, xb):
+    """(r cos, r sin) of the noise transform for raw Philox word pairs."""
+    xa, xb = _chk(np.ascontiguousarray(xa), np.uint32), _chk(np.ascontiguousarray(xb), np.uint32)
+    zc, zs = np.empty(xa.size, np.float32), np.empty(xa.size, np.float32)
+    lib().orc_box_muller_raw(_ptr(xa), _ptr(xb), xa.size, _ptr(zc), _ptr(zs))
+    return zc, zs
 
 
 def noise_ref(seed, k, j0, n):

@@ -117,9 +117,14 @@ NoiseBits noise_bits(uint64_t seed, uint64_t k, uint64_t j) {
     return b;
 }
 
-float noise_z_f32(uint64_t seed, uint64_t k, uint64_t j) {
-    const NoiseBits b = noise_bits(seed, k, j);
+float box_muller_f32(const NoiseBits& b);
 
+float noise_z_f32(uint64_t seed, uint64_t k, uint64_t j) {
+    return box_muller_f32(noise_bits(seed, k, j));
+}
+
+// The transform on one word pair; b.odd selects the sine.
+float box_muller_f32(const NoiseBits& b) {
     // radius
     const uint32_t M = 2u * (b.xa >> 9) + 1u;          // odd, below 2^24
     int e;
@@ -707,6 +712,19 @@ void orc_philox4x32_10(const uint32_t* ctr, const uint32_t* key, uint32_t* out) 
 
 float orc_noise_z_f32(uint64_t seed, uint64_t k, uint64_t j) { return noise_z_f32(seed, k, j); }
 double orc_noise_z_ref(uint64_t seed, uint64_t k, uint64_t j) { return noise_z_ref(seed, k, j); }
+
+void orc_box_muller_raw(const uint32_t* xa, const uint32_t* xb, uint64_t n, float* zc, float* zs) {
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < (int64_t)n; ++i) {
+        NoiseBits b;
+        b.xa = xa[i];
+        b.xb = xb[i];
+        b.odd = 0;
+        zc[i] = box_muller_f32(b);
+        b.odd = 1;
+        zs[i] = box_muller_f32(b);
+    }
+}
 
 void orc_noise_fill_f32(uint64_t seed, uint64_t k, uint64_t j0, uint64_t n, float* out) {
     for (uint64_t j = 0; j < n; ++j) out[j] = noise_z_f32(seed, k, j0 + j);

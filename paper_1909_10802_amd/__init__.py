@@ -107,6 +107,7 @@ SIGNATURES = {
     "ga_get_delays": (_i, [_p, _p, _u64, C.POINTER(_u64)]),
     "ga_set_bookkeeping": (_i, [_p, _u64, _p]),
     "ga_noise_fill": (_i, [_u64, _u64, _u64, _u64, _p, _p]),
+    "ga_box_muller_raw": (_i, [_p, _p, _u64, _p, _p, _p]),
     "ga_last_error": (C.c_char_p, [_p]),
     "ga_version": (C.c_char_p, []),
 }
@@ -391,6 +392,14 @@ def ga_noise_fill(seed, k, j0, n, dev_out, stream=None):
     import torch
     _check(lib().ga_noise_fill(seed, k, j0, n, _dev(dev_out, torch.float32, n), _stream_ptr(stream)))
     return dev_out
+
+
+def ga_box_muller_raw(dev_xa, dev_xb, dev_zc, dev_zs, stream=None):
+    import torch
+    n = dev_xa.numel()
+    assert dev_xb.numel() == n and dev_zc.numel() == n and dev_zs.numel() == n
+    _check(lib().ga_box_muller_raw(_dev(dev_xa, torch.int32), _dev(dev_xb, torch.int32), n, _dev(dev_zc, torch.float32),
+                                   _dev(dev_zs, torch.float32), _stream_ptr(stream)))
 
 
 def ga_version():

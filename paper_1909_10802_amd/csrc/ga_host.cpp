@@ -845,6 +845,13 @@ int ga_set_bookkeeping(ga_ctx* ctx, uint64_t k, const uint64_t* host_iter) {
     return GA_OK;
 }
 
+int ga_box_muller_raw(const uint32_t* dev_xa, const uint32_t* dev_xb, uint64_t n, float* dev_zc, float* dev_zs,
+                      void* hip_stream) {
+    if (n > 0 && (!dev_xa || !dev_xb || !dev_zc || !dev_zs)) return fail(nullptr, GA_ERR_ARG, "box_muller_raw: null argument");
+    const hipError_t e = ga::launch_box_muller_raw(dev_xa, dev_xb, n, dev_zc, dev_zs, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? GA_OK : hip_fail(nullptr, e, "box_muller_raw launch");
+}
+
 int ga_noise_fill(uint64_t seed, uint64_t k, uint64_t j0, uint64_t n, float* dev_out, void* hip_stream) {
     if (n > 0 && !dev_out) return fail(nullptr, GA_ERR_ARG, "noise_fill: output is null");
     const hipError_t e = ga::launch_noise_fill(seed, k, j0, n, dev_out, static_cast<hipStream_t>(hip_stream));

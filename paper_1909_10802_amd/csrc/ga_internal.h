@@ -112,6 +112,8 @@ hipError_t launch_quadratic_gradient(const StatePtrs& st, uint64_t N, uint32_t w
 hipError_t launch_diagnostics(const StatePtrs& st, uint64_t N, uint32_t worker, float inv_bc, float eta_max,
                               float eps, DiagPartial* dev_partials, hipStream_t stream);
 
+hipError_t launch_box_muller_raw(const uint32_t* xa, const uint32_t* xb, uint64_t n, float* zc, float* zs,
+                                 hipStream_t stream);
 hipError_t launch_noise_fill(uint64_t seed, uint64_t k, uint64_t j0, uint64_t n, float* out, hipStream_t stream);
 
 // dst[0..n) = value;  dst[r][0..n) = src[0..n) for r < rows (row stride in floats).

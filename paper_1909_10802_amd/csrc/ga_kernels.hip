@@ -501,17 +501,42 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
                                               uint32_t k1, uint32_t (&x)[4]) {
 #pragma unroll
     for (int r = 0; r < 10; ++r) {
-        const uint32_t hi0 = __umulhi(0xD2511F53u, c0);
-        const uint32_t lo0 = 0xD2511F53u * c0;
-        const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2);
-        const uint32_t lo1 = 0xCD9E8D57u * c2;
-        const uint32_t n0 = hi1 ^ c1 ^ k0;
-        const uint32_t n2 = hi0 ^ c3 ^ k1;
-        c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
+        // one 32x32->64 multiply gives the high and the low word (v_mad_u64_u32)
+        const uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+        const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        c0 = n0; c1 = (uint32_t)p1; c2 = n2; c3 = (uint32_t)p0;
         k0 += 0x9E3779B9u;
         k1 += 0xBB67AE85u;
     }
     x[0] = c0; x[1] = c1; x[2] = c2; x[3] = c3;
+}
+
+// Correctly rounded a / b and sqrt(x) for operands that are known to be normal, far from the
+// ends of the exponent range (a may be zero).  Same iteration as the general expansion of '/'
+// and sqrtf (reciprocal, two residual corrections; root, +-1 ulp residual test) without its
+// operand scaling and special-case fix-up, which cannot trigger in that range.
+__device__ __forceinline__ float div_normal_range(float a, float b) {
+    float r = __builtin_amdgcn_rcpf(b);
+    const float e0 = fmaf(-b, r, 1.0f);
+    r = fmaf(e0, r, r);
+    float q = a * r;
+    const float e1 = fmaf(-b, q, a);
+    q = fmaf(e1, r, q);
+    const float e2 = fmaf(-b, q, a);
+    return fmaf(e2, r, q);
+}
+
+__device__ __forceinline__ float sqrt_normal_range(float x) {
+    const float s = __builtin_amdgcn_sqrtf(x);
+    const float s_dn = __uint_as_float(__float_as_uint(s) - 1u);
+    const float s_up = __uint_as_float(__float_as_uint(s) + 1u);
+    const float r_dn = fmaf(-s_dn, s, x);
+    const float r_up = fmaf(-s_up, s, x);
+    float out = (r_dn <= 0.0f) ? s_dn : s;
+    out = (r_up > 0.0f) ? s_up : out;
+    return out;
 }
 
 // (xa, xb) -> (r cos(angle), r sin(angle)); see ga_noise_fill in include/ga.h.
@@ -526,9 +551,9 @@ __device__ __forceinline__ void box_muller_pair(uint32_t xa, uint32_t xb, float&
         e -= 1;
     }
     const float E = (float)(e - 24);
-    const float num = t - 1.0f;
-    const float den = t + 1.0f;
-    const float s = num / den;
+    const float num = t - 1.0f;                                 // in [-0.293, 0.415], zero or at least 2^-24
+    const float den = t + 1.0f;                                 // in [1.707, 2.415]
+    const float s = div_normal_range(num, den);
     const float s2 = s * s;
     float P = fmaf(s2, 1.0f / 9.0f, 1.0f / 7.0f);
     P = fmaf(s2, P, 1.0f / 5.0f);
@@ -537,7 +562,7 @@ __device__ __forceinline__ void box_muller_pair(uint32_t xa, uint32_t xb, float&
     const float L = fmaf(s3, P, s);                             // atanh(s)
     const float twoL = 2.0f * L;
     const float lnu = fmaf(E, 0.693147180559945f, twoL);
-    const float r = sqrtf(-2.0f * lnu);
+    const float r = sqrt_normal_range(-2.0f * lnu);             // argument in [1.1e-7, 33.3]
 
     // angle = quad * pi/2 + phi, phi in (-pi/4, pi/4)
     const uint32_t quad = xb >> 30;
@@ -590,6 +615,17 @@ __global__ __launch_bounds__(kBlock) void noise_fill_kernel(uint32_t seed_lo, ui
     const f32x4 z = noise4(seed_lo, seed_hi, j >> 2, k);
     const uint32_t lane = (uint32_t)(j & 3);
     out[i] = lane == 0 ? z.x : lane == 1 ? z.y : lane == 2 ? z.z : z.w;
+}
+
+__global__ __launch_bounds__(kBlock) void box_muller_raw_kernel(const uint32_t* __restrict__ xa,
+                                                                const uint32_t* __restrict__ xb, uint64_t n,
+                                                                float* __restrict__ zc, float* __restrict__ zs) {
+    const uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (i >= n) return;
+    float c, s;
+    box_muller_pair(xa[i], xb[i], c, s);
+    zc[i] = c;
+    zs[i] = s;
 }
 
 __global__ __launch_bounds__(kBlock) void quadratic_gradient_kernel(const float* __restrict__ snap,
@@ -1060,6 +1096,15 @@ hipError_t launch_diagnostics(const StatePtrs& st, uint64_t N, uint32_t worker, 
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(diag_final_kernel, dim3(1), dim3(kBlock), 0, stream, dev_partials, grid,
                        dev_partials + kDiagMaxBlocks);
+    return hipGetLastError();
+}
+
+hipError_t launch_box_muller_raw(const uint32_t* xa, const uint32_t* xb, uint64_t n, float* zc, float* zs,
+                                 hipStream_t stream) {
+    if (n == 0) return hipSuccess;
+    const uint64_t blocks = (n + kBlock - 1) / kBlock;
+    if (blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(box_muller_raw_kernel, dim3((uint32_t)blocks), dim3(kBlock), 0, stream, xa, xb, n, zc, zs);
     return hipGetLastError();
 }
 

@@ -27,6 +27,21 @@ def test_noise_bit_exact(seed, k, j0, n):
     assert bits_equal(host(out), oracle.noise_f32(seed, k, j0, n)) == 0
 
 
+def test_noise_transform_exhaustive():
+    # every radius input (the 2^23 values of xa >> 9) and every angle input (the 2^25 values of xb >> 7)
+    def run(xa, xb):
+        zc, zs = torch.empty(xa.size, dtype=torch.float32, device=DEV), torch.empty(xa.size, dtype=torch.float32, device=DEV)
+        ga.ga_box_muller_raw(dev(xa.view(np.int32)), dev(xb.view(np.int32)), zc, zs)
+        rc, rs = oracle.box_muller_raw(xa, xb)
+        assert bits_equal(host(zc), rc) == 0 and bits_equal(host(zs), rs) == 0
+    m = np.arange(1 << 23, dtype=np.uint32)
+    for xb in (0x00000000, 0x5A5A5A5A, 0xFFFFFFFF):
+        run(m << np.uint32(9), np.full(m.size, xb, np.uint32))
+    for lo in range(0, 1 << 25, 1 << 23):
+        f = np.arange(lo, lo + (1 << 23), dtype=np.uint32)
+        run(np.full(f.size, 0x9E3779B9, np.uint32), f << np.uint32(7))
+
+
 # ------------------------------------------------------------------ single step, teacher forced
 @pytest.mark.parametrize("mode", MODES, ids=[MODE_NAMES[m] for m in MODES])
 @pytest.mark.parametrize("N", SIZES)
