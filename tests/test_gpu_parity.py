@@ -177,7 +177,9 @@ def test_quadratic_gradient_entry_point():
     M.run_schedule(np.array([0, 1, 2, 1], np.uint32), src)
     g = torch.empty(N, dtype=torch.float32, device=DEV)
     ga.ga_quadratic_gradient(M.ctx, 2, src, g)
-    ref = oracle.quadratic_gradient(host(M.snapshot(2)), a, ts, seed, k=5)
+    O = oracle.Master(N, W, oracle.MODE_GA, oracle.Hyper())
+    O.run_quadratic(np.array([0, 1, 2, 1], np.uint32), a, ts, seed)
+    ref = oracle.quadratic_gradient(O.snaps[2], a, ts, seed, k=5)
     assert bits_equal(host(g), ref) == 0
     assert M.k == 4                                            # state untouched
 
@@ -329,3 +331,24 @@ def test_untracked_modes_skip_m_and_snapshots(mode):
     compare_masters(M, O, "untracked " + MODE_NAMES[mode], snaps=False, keep_m=False)
     th, v, m, sn = gpu_state(M)
     assert not m.any() and not sn.any()
+
+
+@pytest.mark.parametrize("N", [1, 2, 3, 5, 64, 65])
+def test_persistent_tiny_vectors(N):
+    # fewer parameters than one 128-bit group, and the padding boundary of the state rows
+    W, T, seed = 3, 40, 6
+    a, ts = ga_inputs.curvatures(N, seed), ga_inputs.optimum(N, seed)
+    sched = ga.ga_simulate_schedule(W, T, seed=seed)
+    da = torch.zeros(((N + 3) // 4) * 4, dtype=torch.float32, device=DEV)[:N]
+    dts = torch.zeros(((N + 3) // 4) * 4, dtype=torch.float32, device=DEV)[:N]
+    da.copy_(dev(a))
+    dts.copy_(dev(ts))
+    for family, Oc, eta in [(ga.GA_FAMILY_MOMENTUM, oracle.Master, 0.1), (ga.GA_FAMILY_DANA, oracle.DanaMaster, 0.1),
+                            (ga.GA_FAMILY_ADAM, oracle.AdamMaster, 0.01)]:
+        M = ga.Master(N, W, eta=eta, mode=ga.GA_MODE_GA, family=family)
+        M.run_schedule(sched, ga.quadratic_source(da, dts, seed))
+        O = Oc(N, W, oracle.MODE_GA, oracle.Hyper(eta, 0.0 if family == ga.GA_FAMILY_ADAM else 0.9))
+        O.run_quadratic(sched, a, ts, seed)
+        assert bits_equal(host(M.theta()), O.theta) == 0, (N, family)
+        for w in range(W):
+            assert bits_equal(host(M.snapshot(w)), O.snaps[w]) == 0
