@@ -68,6 +68,7 @@ def _declare(L):
     hyp = [_f64] * 5
     for sfx in ("f32", "f64"):
         getattr(L, "orc_step_" + sfx).argtypes = [_u64, _p, _p, _p, _p, _p, _int, _u64, _u64, *hyp, _int]
+        getattr(L, "orc_step_nag_" + sfx).argtypes = [_u64, _p, _p, _p, _p, _p, _int, _u64, _u64, *hyp, _int]
         getattr(L, "orc_dana_step_" + sfx).argtypes = [_u64, _p, _p, _p, _p, _p, _p, _int, _u64, _u64, *hyp, _int]
         getattr(L, "orc_adam_step_" + sfx).argtypes = [_u64, _p, _p, _p, _p, _p, _p, _int, _u64, _u64,
                                                        _f64, _f64, _f64, _f64, _f64, _f64, _f64, _int]
@@ -199,13 +200,13 @@ class Hyper:
         return (self.eta_k, self.eta_max, self.gamma, self.beta, self.eps)
 
 
-def step(theta, v, m, snap_i, g, mode, k, tau, hyper, track_gap=False):
+def step(theta, v, m, snap_i, g, mode, k, tau, hyper, track_gap=False, nesterov=False):
     """One arrival, in place on theta, v, m, snap_i."""
     s = _sfx(theta.dtype)
     n = theta.size
     for a in (theta, v, m, snap_i, g):
         _chk(a, theta.dtype, n)
-    getattr(lib(), "orc_step_" + s)(n, _ptr(theta), _ptr(v), _ptr(m), _ptr(snap_i), _ptr(g), mode, k, tau,
+    getattr(lib(), ("orc_step_nag_" if nesterov else "orc_step_") + s)(n, _ptr(theta), _ptr(v), _ptr(m), _ptr(snap_i), _ptr(g), mode, k, tau,
                                     *hyper.args(), int(track_gap))
 
 
@@ -236,9 +237,10 @@ def gap_statistics(theta, m, snap_i, k, hyper):
 class Master:
     """State of one parameter-server master, advanced by the oracle routines."""
 
-    def __init__(self, N, W, mode, hyper, dtype=np.float32, theta0=None, track_gap=False):
+    def __init__(self, N, W, mode, hyper, dtype=np.float32, theta0=None, track_gap=False, nesterov=False):
         self.N, self.W, self.mode, self.hyper, self.dtype = N, W, mode, hyper, np.dtype(dtype)
         self.track_gap = track_gap
+        self.nesterov = nesterov
         self.theta = np.zeros(N, dtype) if theta0 is None else np.array(theta0, dtype=dtype)
         self.v = np.zeros(N, dtype)
         self.m = np.zeros(N, dtype)
@@ -251,12 +253,17 @@ class Master:
         self.k += 1
         tau = self.k - int(self.iter[worker])
         step(self.theta, self.v, self.m, self.snaps[worker], np.ascontiguousarray(g, dtype=self.dtype), self.mode,
-             self.k, tau, self.hyper, self.track_gap)
+             self.k, tau, self.hyper, self.track_gap, self.nesterov)
         self.iter[worker] = self.k
         self.tau_log.append(tau)
         return tau
 
     def run_quadratic(self, schedule, a, theta_star, seed, sigma=0.01, idx=None):
+        if self.nesterov:                               # arrival by arrival (the C loop is heavy-ball only)
+            for w in schedule:
+                w = int(w)
+                self.apply(w, quadratic_gradient(self.snaps[w], a, theta_star, seed, self.k + 1, sigma, idx))
+            return np.array(self.tau_log[-len(schedule):], dtype=np.uint64)
         s = _sfx(self.dtype)
         schedule = _chk(np.ascontiguousarray(schedule, dtype=np.uint32), np.uint32)
         T = schedule.size
@@ -273,6 +280,11 @@ class Master:
         return tau
 
     def run_buffers(self, schedule, bufs, pick_by_worker=True):
+        if self.nesterov:
+            for w in schedule:
+                w = int(w)
+                self.apply(w, bufs[w % len(bufs)] if pick_by_worker else bufs[self.k % len(bufs)])
+            return np.array(self.tau_log[-len(schedule):], dtype=np.uint64)
         s = _sfx(self.dtype)
         schedule = _chk(np.ascontiguousarray(schedule, dtype=np.uint32), np.uint32)
         T = schedule.size

@@ -14,6 +14,7 @@
 //   * DANA / DANA-SA / DANA-GA masters             -- Alg. 6, 7, 8 (App. C.1)
 //   * Adam / Adam-SA / Adam-GA masters             -- Alg. 9, 10, 11 (App. C.1)
 //   * layer-wise and global Gap                    -- Eq. 4 and Def. 1 (Sec. 4.3)
+//   * Nesterov form of the momentum masters        -- Sec. 2 and Sec. 6 name NAG; form: see master_step
 //   * task execution times, gamma (CVB) model      -- Alg. 12, 13 (App. C.3)
 //   * ASGD-vs-SSGD speed-up simulation             -- App. D
 //   * master is a FIFO over worker arrivals        -- App. C.1
@@ -38,7 +39,8 @@
 // against torch.optim.Adam; Adam-SA / Adam-GA steady-state step eta/tau;
 // layers of one parameter against the parameter-wise Gap; gamma variates
 // against scipy's gamma distribution and the tail probabilities printed in
-// App. C.3 (27.9 % / 1 %); speed-up ratios against the values printed in App. D.
+// App. C.3 (27.9 % / 1 %); speed-up ratios against the values printed in App. D;
+// the Nesterov form with one worker against torch.optim.SGD(nesterov=True).
 // Parity unpinned: the hinge penalty max(1, |d|/C) is this project's variant,
 // pinned only by its definition (equals the paper's form with "+1" replaced).
 
@@ -387,9 +389,13 @@ R coefficient_C(R m, R inv_bc_prev, R eta_max, R eps) {
 
 // One arrival of worker i (gradient g, delay tau, master step k >= 1) applied to
 // all n parameters.  snap_i is theta^i: what the master last sent to worker i.
+// nesterov: the experiments of Sec. 6 use "a NAG optimizer" but the paper writes
+// every master in heavy-ball form; the Nesterov form taken here is the common one,
+//   v <- gamma v + g-hat ;  d = g-hat + gamma v ;  theta <- theta - eta d,
+// and Alg. 14 then follows d, the step actually taken.
 template <typename R>
 void master_step(uint64_t n, R* theta, R* v, R* m, R* snap_i, const R* g, int mode, uint64_t k,
-                 uint64_t tau, const Hyper<R>& h, int track_gap) {
+                 uint64_t tau, const Hyper<R>& h, int track_gap, int nesterov = 0) {
     const bool gap_mode = (mode == MODE_GA || mode == MODE_GA_HINGE);
     const bool keep_m = gap_mode || track_gap;
     const R inv_bc_prev = inverse_bias_correction<R>(h.beta, k - 1);
@@ -413,13 +419,18 @@ void master_step(uint64_t n, R* theta, R* v, R* m, R* snap_i, const R* g, int mo
         }
         const R gv = h.gamma * v[j];
         const R v_new = gv + g_hat;                                // v_{k+1}
-        const R step = lr * v_new;
+        R dir = v_new;                                             // update vector
+        if (nesterov) {
+            const R look = h.gamma * v_new;
+            dir = g_hat + look;
+        }
+        const R step = lr * dir;
         const R theta_new = theta[j] - step;                       // theta_{k+1}
         v[j] = v_new;
         theta[j] = theta_new;
         if (keep_m) {                                              // Alg. 14
             const R bm = h.beta * m[j];
-            const R vv = v_new * v_new;
+            const R vv = dir * dir;
             const R add = one_minus_beta * vv;
             m[j] = bm + add;
         }
@@ -853,6 +864,19 @@ int orc_step_layerwise_f64(uint64_t n, double* theta, double* v, double* m, doub
     master_step_layerwise<double>(n, theta, v, m, snap_i, g, layer_sizes, P, mode, k,
                                   make_hyper<double>(eta_k, eta_max, gamma, beta, eps), gaps_out);
     return 0;
+}
+
+void orc_step_nag_f32(uint64_t n, float* theta, float* v, float* m, float* snap_i, const float* g,
+                      int mode, uint64_t k, uint64_t tau, double eta_k, double eta_max, double gamma,
+                      double beta, double eps, int track_gap) {
+    master_step<float>(n, theta, v, m, snap_i, g, mode, k, tau,
+                       make_hyper<float>(eta_k, eta_max, gamma, beta, eps), track_gap, 1);
+}
+void orc_step_nag_f64(uint64_t n, double* theta, double* v, double* m, double* snap_i, const double* g,
+                      int mode, uint64_t k, uint64_t tau, double eta_k, double eta_max, double gamma,
+                      double beta, double eps, int track_gap) {
+    master_step<double>(n, theta, v, m, snap_i, g, mode, k, tau,
+                        make_hyper<double>(eta_k, eta_max, gamma, beta, eps), track_gap, 1);
 }
 
 void orc_quadratic_gradient_f32(uint64_t n, float* g, const float* snap_i, const float* a,

@@ -31,6 +31,21 @@ def test_library_exports_every_declared_symbol():
     assert ga.ga_version() == "0.1"
 
 
+def test_header_is_plain_c_and_usable_from_c(tmp_path):
+    import subprocess
+    inc = os.path.join(ROOT, "include")
+    for cc, std in (("gcc", "-std=c99"), ("g++", "-std=c++11")):
+        subprocess.check_call([cc, std, "-Wall", "-Wextra", "-pedantic", "-Werror", "-I" + inc, "-fsyntax-only",
+                               "-x", "c" if cc == "gcc" else "c++", os.path.join(inc, "ga.h")])
+    exe = str(tmp_path / "c_abi_client")
+    libdir = os.path.dirname(ga.LIB_PATH)
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-I" + inc,
+                           os.path.join(ROOT, "tests", "c_abi_client.c"), "-o", exe, "-L" + libdir, "-lga",
+                           "-Wl,-rpath," + libdir, "-Wl,-rpath,/opt/rocm/lib"])
+    out = subprocess.run([exe], stdout=subprocess.PIPE, text=True)
+    assert out.returncode == 0 and "c client ok" in out.stdout, out.stdout
+
+
 def test_struct_layouts_match_the_header():
     assert C.sizeof(ga.ga_arrival) == 16 and ga.ARRIVAL_DTYPE.itemsize == 16
     assert C.sizeof(ga.ga_diag) == 32

@@ -224,3 +224,44 @@ def test_global_gap_is_scale_free_and_uniform():
     ratio = g / (L.v - 0.9 * v0)
     assert np.allclose(ratio[:50], L.last_gaps[0], rtol=1e-9) and np.allclose(ratio[50:], L.last_gaps[1], rtol=1e-9)
     assert abs(L.last_gaps[0] - L.last_gaps[1]) > 1e-6
+
+
+# ------------------------------------------------------------------ Nesterov form
+def test_nesterov_single_worker_matches_torch_sgd():
+    N, T, lr, gamma = 30, 150, 0.05, 0.9
+    a, ts = quad_inputs(N, 11, np.float64)
+    M = Master(N, 1, MODE_GA, Hyper(lr, gamma, f32=False), np.float64, nesterov=True)
+    M.run_quadratic(np.zeros(T, np.uint32), a, ts, seed=0, sigma=0.0)
+    p = torch.zeros(N, dtype=torch.float64, requires_grad=True)
+    opt = torch.optim.SGD([p], lr=lr, momentum=gamma, nesterov=True)
+    ta, tts = torch.from_numpy(a), torch.from_numpy(ts)
+    for _ in range(T):
+        opt.zero_grad()
+        (0.5 * (ta * (p - tts) ** 2).sum()).backward()
+        opt.step()
+    assert np.allclose(M.theta, p.detach().numpy(), rtol=1e-11, atol=1e-13)
+    H = Master(N, 1, MODE_GA, Hyper(lr, gamma, f32=False), np.float64)
+    H.run_quadratic(np.zeros(T, np.uint32), a, ts, seed=0, sigma=0.0)
+    assert not np.allclose(H.theta, M.theta, rtol=1e-4)              # it is not the heavy-ball trajectory
+
+
+@pytest.mark.parametrize("mode", [MODE_ASGD, MODE_SA, MODE_GA, MODE_GA_HINGE])
+def test_nesterov_without_momentum_is_plain(mode):
+    N, W, T = 200, 4, 80
+    a, ts = quad_inputs(N, 13, np.float32)
+    sched = oracle.simulate_schedule(W, T, seed=13)
+    A = Master(N, W, mode, Hyper(0.1, 0.0), np.float32, nesterov=True)
+    B = Master(N, W, mode, Hyper(0.1, 0.0), np.float32)
+    A.run_quadratic(sched, a, ts, seed=1)
+    B.run_quadratic(sched, a, ts, seed=1)
+    assert np.array_equal(A.theta, B.theta) and np.array_equal(A.snaps, B.snaps)
+
+
+def test_nesterov_gap_penalty_fixed_point():
+    # same construction as for the heavy-ball master, gamma = 0.5: with every penalised gradient equal to
+    # c/G the update vector settles at d = (c/G)(1 + gamma/(1-gamma)); C follows d, so Graw = W-1 and G = W.
+    N, W, T, eta, gamma = 3, 5, 2500, 0.05, 0.5
+    c = np.array([0.4, -1.5, 3.0])
+    M = Master(N, W, MODE_GA, Hyper(eta, gamma, beta=0.9, eps=1e-12, f32=False), np.float64, nesterov=True)
+    M.run_buffers((np.arange(T) % W).astype(np.uint32), np.ascontiguousarray(c[None, :]))
+    assert np.allclose(M.v, (c / W) / (1 - gamma), rtol=1e-6)
