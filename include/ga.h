@@ -217,6 +217,10 @@ typedef struct ga_config {
     uint32_t n_layers;                 /* GA_GAP_LAYER: number of layers */
     const uint64_t* host_layer_sizes;  /* GA_GAP_LAYER: n_layers sizes (each > 0) summing to N; read during
                                           ga_workspace_bytes_ex / ga_create_ex only */
+    int nesterov;    /* MOMENTUM family: Nesterov form of the step (Sec. 6 trains with NAG; the paper
+                        prints the masters in heavy-ball form only):
+                          v = gamma * v + ghat ;  d = ghat + gamma * v ;  theta = theta - lr * d,
+                        and Alg. 14 follows d.  Default 0 (heavy ball, as printed). */
 } ga_config;
 
 /* ------------------------------------------------------------------ host only

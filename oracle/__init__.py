@@ -72,7 +72,7 @@ def _declare(L):
         getattr(L, "orc_dana_step_" + sfx).argtypes = [_u64, _p, _p, _p, _p, _p, _p, _int, _u64, _u64, *hyp, _int]
         getattr(L, "orc_adam_step_" + sfx).argtypes = [_u64, _p, _p, _p, _p, _p, _p, _int, _u64, _u64,
                                                        _f64, _f64, _f64, _f64, _f64, _f64, _f64, _int]
-        getattr(L, "orc_step_layerwise_" + sfx).argtypes = [_u64, _p, _p, _p, _p, _p, _p, _u32, _int, _u64, *hyp, _p]
+        getattr(L, "orc_step_layerwise_" + sfx).argtypes = [_u64, _p, _p, _p, _p, _p, _p, _u32, _int, _u64, *hyp, _p, _int]
         getattr(L, "orc_quadratic_gradient_" + sfx).argtypes = [_u64, _p, _p, _p, _p, _p, _u64, _u64, _f64]
         getattr(L, "orc_gap_statistics_" + sfx).argtypes = [_u64, _p, _p, _p, _u64, _f64, _f64, _f64, _p, _p, _p, _p]
         getattr(L, "orc_run_quadratic_" + sfx).argtypes = [
@@ -307,8 +307,8 @@ class Master:
 class LayerwiseMaster(Master):
     """Gap-Aware master with one Gap per layer (Eq. 4); a single layer gives the global Gap (Def. 1)."""
 
-    def __init__(self, N, W, mode, hyper, layer_sizes=None, dtype=np.float32, theta0=None):
-        super().__init__(N, W, mode, hyper, dtype, theta0)
+    def __init__(self, N, W, mode, hyper, layer_sizes=None, dtype=np.float32, theta0=None, nesterov=False):
+        super().__init__(N, W, mode, hyper, dtype, theta0, nesterov=nesterov)
         assert mode in (MODE_GA, MODE_GA_HINGE)
         self.layer_sizes = np.array([N] if layer_sizes is None else layer_sizes, dtype=np.uint64)
         assert int(self.layer_sizes.sum()) == N
@@ -321,7 +321,7 @@ class LayerwiseMaster(Master):
         rc = getattr(lib(), "orc_step_layerwise_" + _sfx(self.dtype))(
             self.N, _ptr(self.theta), _ptr(self.v), _ptr(self.m), _ptr(self.snaps[worker]),
             _ptr(_chk(g, self.dtype, self.N)), _ptr(self.layer_sizes), self.layer_sizes.size, self.mode, self.k,
-            *self.hyper.args(), _ptr(self.last_gaps))
+            *self.hyper.args(), _ptr(self.last_gaps), int(self.nesterov))
         assert rc == 0
         self.iter[worker] = self.k
         self.tau_log.append(tau)

@@ -567,7 +567,7 @@ void adam_step(uint64_t n, R* theta, R* m1, R* v2, R* c, R* snap_i, const R* g, 
 // ---------------------------------------------------------------------------
 template <typename R>
 void master_step_layerwise(uint64_t n, R* theta, R* v, R* m, R* snap_i, const R* g, const uint64_t* layer_sizes,
-                           uint32_t P, int mode, uint64_t k, const Hyper<R>& h, R* gaps_out) {
+                           uint32_t P, int mode, uint64_t k, const Hyper<R>& h, R* gaps_out, int nesterov) {
     const R inv_bc_prev = inverse_bias_correction<R>(h.beta, k - 1);
     const R one_minus_beta = (R)1 - h.beta;
     uint64_t start = 0;
@@ -591,12 +591,17 @@ void master_step_layerwise(uint64_t n, R* theta, R* v, R* m, R* snap_i, const R*
             const R g_hat = g[j] / G;
             const R gv = h.gamma * v[j];
             const R v_new = gv + g_hat;
-            const R step = h.eta_k * v_new;
+            R dir = v_new;
+            if (nesterov) {                                  // see master_step
+                const R look = h.gamma * v_new;
+                dir = g_hat + look;
+            }
+            const R step = h.eta_k * dir;
             const R theta_new = theta[j] - step;
             v[j] = v_new;
             theta[j] = theta_new;
             const R bm = h.beta * m[j];
-            const R vv = v_new * v_new;
+            const R vv = dir * dir;
             const R add = one_minus_beta * vv;
             m[j] = bm + add;
             snap_i[j] = theta_new;
@@ -847,22 +852,22 @@ void orc_adam_step_f64(uint64_t n, double* theta, double* m1, double* v2, double
 
 int orc_step_layerwise_f32(uint64_t n, float* theta, float* v, float* m, float* snap_i, const float* g,
                            const uint64_t* layer_sizes, uint32_t P, int mode, uint64_t k, double eta_k,
-                           double eta_max, double gamma, double beta, double eps, float* gaps_out) {
+                           double eta_max, double gamma, double beta, double eps, float* gaps_out, int nesterov) {
     uint64_t total = 0;
     for (uint32_t p = 0; p < P; ++p) total += layer_sizes[p];
     if (total != n || (mode != MODE_GA && mode != MODE_GA_HINGE)) return -1;
     master_step_layerwise<float>(n, theta, v, m, snap_i, g, layer_sizes, P, mode, k,
-                                 make_hyper<float>(eta_k, eta_max, gamma, beta, eps), gaps_out);
+                                 make_hyper<float>(eta_k, eta_max, gamma, beta, eps), gaps_out, nesterov);
     return 0;
 }
 int orc_step_layerwise_f64(uint64_t n, double* theta, double* v, double* m, double* snap_i, const double* g,
                            const uint64_t* layer_sizes, uint32_t P, int mode, uint64_t k, double eta_k,
-                           double eta_max, double gamma, double beta, double eps, double* gaps_out) {
+                           double eta_max, double gamma, double beta, double eps, double* gaps_out, int nesterov) {
     uint64_t total = 0;
     for (uint32_t p = 0; p < P; ++p) total += layer_sizes[p];
     if (total != n || (mode != MODE_GA && mode != MODE_GA_HINGE)) return -1;
     master_step_layerwise<double>(n, theta, v, m, snap_i, g, layer_sizes, P, mode, k,
-                                  make_hyper<double>(eta_k, eta_max, gamma, beta, eps), gaps_out);
+                                  make_hyper<double>(eta_k, eta_max, gamma, beta, eps), gaps_out, nesterov);
     return 0;
 }
 

@@ -53,7 +53,7 @@ class ga_config(C.Structure):
                 ("eta", C.c_float), ("gamma", C.c_float), ("beta", C.c_float), ("eps", C.c_float),
                 ("adam_beta1", C.c_float), ("adam_beta2", C.c_float), ("adam_eps", C.c_float),
                 ("track_gap", C.c_int), ("gap_scope", C.c_int), ("n_layers", C.c_uint32),
-                ("host_layer_sizes", C.c_void_p)]
+                ("host_layer_sizes", C.c_void_p), ("nesterov", C.c_int)]
 
 
 class ga_time_model(C.Structure):
@@ -412,14 +412,16 @@ class Master:
 
     def __init__(self, N, n_workers, eta=0.1, gamma=0.9, mode=GA_MODE_GA, device="cuda:0", stream=None,
                  beta=None, eps=None, eta_max=None, track_gap=False, theta0=None, family=GA_FAMILY_MOMENTUM,
-                 adam_beta1=0.9, adam_beta2=0.999, adam_eps=1e-8, gap_scope=GA_GAP_PARAMETER, layer_sizes=None):
+                 adam_beta1=0.9, adam_beta2=0.999, adam_eps=1e-8, gap_scope=GA_GAP_PARAMETER, layer_sizes=None,
+                 nesterov=False):
         import torch
         self.N, self.W, self.mode = N, n_workers, MODES.get(mode, mode)
         self.family = FAMILIES.get(family, family)
         self.device = torch.device(device)
         cfg = ga_config_init(N=N, n_workers=n_workers, family=self.family, mode=self.mode, eta=eta, gamma=gamma,
                              adam_beta1=adam_beta1, adam_beta2=adam_beta2, adam_eps=adam_eps,
-                             track_gap=int(track_gap), gap_scope=gap_scope, layer_sizes=layer_sizes)
+                             track_gap=int(track_gap), gap_scope=gap_scope, layer_sizes=layer_sizes,
+                             nesterov=int(nesterov))
         self.n_layers = 0 if cfg.gap_scope == GA_GAP_PARAMETER else (1 if cfg.gap_scope == GA_GAP_GLOBAL else cfg.n_layers)
         if beta is not None:
             cfg.beta = beta

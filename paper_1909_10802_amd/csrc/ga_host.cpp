@@ -23,6 +23,7 @@ struct ga_ctx {
     float eta_max = 0.f, lr = 0.f, gamma = 0.f, beta = 0.999f, eps = 1e-8f;
     float beta1 = 0.9f, beta2 = 0.999f, adam_eps = 1e-8f;
     bool track_gap = false;
+    bool nesterov = false;
     hipStream_t stream = nullptr;
     ga::StatePtrs st{};
     ga_arrival* dev_table = nullptr;
@@ -326,13 +327,13 @@ int apply_one(ga_ctx* ctx, uint32_t worker, const void* dev_grad, int dtype, boo
     const ga::StepConst sc = step_const(ctx, row, k);
     hipError_t e;
     if (ctx->gap_scope != GA_GAP_PARAMETER)
-        e = ga::launch_apply_layerwise(ctx->st, ctx->N, worker, dev_grad, dtype, ctx->mode, ctx->layers, sc, ctx->stream);
+        e = ga::launch_apply_layerwise(ctx->st, ctx->N, worker, dev_grad, dtype, ctx->mode, ctx->nesterov, ctx->layers, sc, ctx->stream);
     else if (ctx->family == GA_FAMILY_DANA)
         e = ga::launch_apply_dana(ctx->st, ctx->N, worker, dev_grad, dtype, ctx->mode, keeps_m(ctx), write_snap, sc, ctx->stream);
     else if (ctx->family == GA_FAMILY_ADAM)
         e = ga::launch_apply_adam(ctx->st, ctx->N, worker, dev_grad, dtype, ctx->mode, keeps_m(ctx), write_snap, sc, ctx->stream);
     else
-        e = ga::launch_apply(ctx->st, ctx->N, worker, dev_grad, dtype, ctx->mode, keeps_m(ctx), write_snap, sc, ctx->stream);
+        e = ga::launch_apply(ctx->st, ctx->N, worker, dev_grad, dtype, ctx->mode, ctx->nesterov, keeps_m(ctx), write_snap, sc, ctx->stream);
     if (e != hipSuccess) return hip_fail(ctx, e, "apply launch");
     ctx->k = k;
     ctx->iter[worker] = k;
@@ -454,6 +455,7 @@ void ga_config_init(ga_config* cfg) {
     cfg->gap_scope = GA_GAP_PARAMETER;
     cfg->n_layers = 0;
     cfg->host_layer_sizes = nullptr;
+    cfg->nesterov = 0;
 }
 
 // Number of layers and chunks a configuration asks for; false if the layer description is invalid.
@@ -498,6 +500,8 @@ int ga_create_ex(ga_ctx** out, const ga_config* cfg, void* dev_workspace, size_t
     if (!valid_mode(cfg->mode)) return fail(nullptr, GA_ERR_ARG, "create: unknown mode %d", cfg->mode);
     if (cfg->mode == GA_MODE_SA_STEP && cfg->family != GA_FAMILY_MOMENTUM)
         return fail(nullptr, GA_ERR_ARG, "create: GA_MODE_SA_STEP exists for the momentum family only");
+    if (cfg->nesterov && cfg->family != GA_FAMILY_MOMENTUM)
+        return fail(nullptr, GA_ERR_ARG, "create: the Nesterov form exists for the momentum family only");
     if (!(cfg->beta >= 0.f && cfg->beta < 1.f)) return fail(nullptr, GA_ERR_ARG, "create: beta must be in [0,1)");
     if (!(cfg->eps > 0.f) || !std::isfinite(cfg->eps)) return fail(nullptr, GA_ERR_ARG, "create: eps must be finite and > 0");
     if (cfg->family == GA_FAMILY_ADAM) {
@@ -532,6 +536,7 @@ int ga_create_ex(ga_ctx** out, const ga_config* cfg, void* dev_workspace, size_t
     c->beta2 = cfg->adam_beta2;
     c->adam_eps = cfg->adam_eps;
     c->track_gap = cfg->track_gap != 0;
+    c->nesterov = cfg->nesterov != 0;
     c->stream = static_cast<hipStream_t>(hip_stream);
     char* base = static_cast<char*>(dev_workspace);
     c->st.theta = reinterpret_cast<float*>(base + L.off_theta);
@@ -711,7 +716,7 @@ int ga_run_schedule(ga_ctx* ctx, const uint32_t* host_schedule, uint64_t T, cons
             if (e != hipSuccess) return hip_fail(ctx, e, "table upload");
         }
         e = ga::launch_persistent(ctx->st, ctx->N, ctx->family, ctx->dev_table, ctx->dev_adam_table, n, ctx->k, src->dev_a,
-                                  src->dev_theta_star, ctx->mode, keeps_m(ctx), rcst, ctx->stream);
+                                  src->dev_theta_star, ctx->mode, ctx->nesterov, keeps_m(ctx), rcst, ctx->stream);
         if (e != hipSuccess) return hip_fail(ctx, e, "persistent launch");
         ctx->delays.insert(ctx->delays.end(), taus.begin(), taus.end());
         ctx->iter.swap(iter_after);

@@ -85,7 +85,7 @@ struct StatePtrs {
 // Fused update of one arrival.  g: N values of grad_dtype.  In the GA modes m
 // and the snapshot are always maintained; elsewhere keep_m / write_snap decide.
 hipError_t launch_apply(const StatePtrs& st, uint64_t N, uint32_t worker, const void* g, int grad_dtype, int mode,
-                        bool keep_m, bool write_snap, const StepConst& c, hipStream_t stream);
+                        bool nesterov, bool keep_m, bool write_snap, const StepConst& c, hipStream_t stream);
 
 // DANA (Alg. 6-8) and Adam (Alg. 9-11) fused updates of one arrival; mode is ASGD, SA, GA or GA_HINGE.
 hipError_t launch_apply_dana(const StatePtrs& st, uint64_t N, uint32_t worker, const void* g, int grad_dtype, int mode,
@@ -95,13 +95,15 @@ hipError_t launch_apply_adam(const StatePtrs& st, uint64_t N, uint32_t worker, c
 
 // Layer-wise / global Gap arrival: per-chunk reduction, per-layer Gap, update with one Gap per layer.
 hipError_t launch_apply_layerwise(const StatePtrs& st, uint64_t N, uint32_t worker, const void* g, int grad_dtype,
-                                  int mode, const LayerTables& lt, const StepConst& c, hipStream_t stream);
+                                  int mode, bool nesterov, const LayerTables& lt, const StepConst& c,
+                                  hipStream_t stream);
 
 // T arrivals replayed inside one launch, gradients generated in the kernel.
 // table: device array of T rows; k0: master step before the first row.
 hipError_t launch_persistent(const StatePtrs& st, uint64_t N, int family, const ga_arrival* dev_table,
                              const AdamRow* dev_adam_table, uint32_t T, uint64_t k0, const float* a,
-                             const float* theta_star, int mode, bool keep_m, const RunConst& rc, hipStream_t stream);
+                             const float* theta_star, int mode, bool nesterov, bool keep_m, const RunConst& rc,
+                             hipStream_t stream);
 
 // g_out = a * (snap_w - theta_star) + sigma * z(seed, k, j)
 hipError_t launch_quadratic_gradient(const StatePtrs& st, uint64_t N, uint32_t worker, const float* a,

@@ -52,11 +52,18 @@ __device__ __forceinline__ void store4(float* __restrict__ base, uint64_t q, con
 // ---------------------------------------------------------------------------
 // One parameter, one arrival.
 // ---------------------------------------------------------------------------
+// Template parameter MODE: the ga_mode in the low four bits, bit 4 selects the Nesterov form of
+// the momentum master.
+constexpr int kNesterov = 16;
+constexpr int penalty_mode(int mode) { return mode & 15; }
+constexpr bool is_nesterov(int mode) { return (mode & kNesterov) != 0; }
+constexpr bool is_gap(int mode) { return penalty_mode(mode) == GA_MODE_GA || penalty_mode(mode) == GA_MODE_GA_HINGE; }
+
 // The factor the gradient is divided by: the Gap G (Eq. 5, with C from the Alg. 14 state
 // as arrival k-1 left it), the delay (Alg. 5 / 7 / 10), or 1.
 template <int MODE>
 __device__ __forceinline__ float penalty_of(float th, float s, float cstate, const StepConst& c) {
-    if constexpr (MODE == GA_MODE_GA || MODE == GA_MODE_GA_HINGE) {
+    if constexpr (is_gap(MODE)) {
         const float diff = th - s;
         const float delta = fabsf(diff);
         const float mhat = cstate * c.inv_bc_prev;
@@ -64,8 +71,8 @@ __device__ __forceinline__ float penalty_of(float th, float s, float cstate, con
         const float sum = root + c.eps;
         const float C = c.eta_max * sum;
         const float graw = delta / C;
-        return (MODE == GA_MODE_GA) ? 1.0f + graw : fmaxf(1.0f, graw);
-    } else if constexpr (MODE == GA_MODE_SA) {
+        return (penalty_mode(MODE) == GA_MODE_GA) ? 1.0f + graw : fmaxf(1.0f, graw);
+    } else if constexpr (penalty_mode(MODE) == GA_MODE_SA) {
         return c.tau;
     } else {
         return 1.0f;
@@ -80,18 +87,24 @@ __device__ __forceinline__ float second_moment(float m, float x, const StepConst
     return bm + add;
 }
 
-// MOMENTUM family (Alg. 2-5), one parameter, one arrival.
+// MOMENTUM family (Alg. 2-5), one parameter, one arrival.  Nesterov form: the step uses
+// d = ghat + gamma * v_new instead of v_new, and Alg. 14 follows d.
 template <int MODE, bool KEEP_M>
 __device__ __forceinline__ void update_one(float& th, float& v, float& m, float s, float g, const StepConst& c) {
     float ghat = g;
-    if constexpr (MODE != GA_MODE_ASGD) ghat = g / penalty_of<MODE>(th, s, m, c);
+    if constexpr (penalty_mode(MODE) != GA_MODE_ASGD) ghat = g / penalty_of<MODE>(th, s, m, c);
     const float gv = c.gamma * v;
     const float vn = gv + ghat;
-    const float step = c.lr * vn;
+    float dir = vn;
+    if constexpr (is_nesterov(MODE)) {
+        const float look = c.gamma * vn;
+        dir = ghat + look;
+    }
+    const float step = c.lr * dir;
     const float tn = th - step;
     v = vn;
     th = tn;
-    if constexpr (KEEP_M) m = second_moment(m, vn, c);
+    if constexpr (KEEP_M) m = second_moment(m, dir, c);
 }
 
 // DANA family (Alg. 6-8).  x = sum_j v_j, y = v_i of the arriving worker; returns the look-ahead snapshot.
@@ -99,7 +112,7 @@ template <int MODE, bool KEEP_M>
 __device__ __forceinline__ float dana_one(float& th, float& x, float& y, float& m, float s, float g,
                                           const StepConst& c) {
     float ghat = g;
-    if constexpr (MODE != GA_MODE_ASGD) ghat = g / penalty_of<MODE>(th, s, m, c);
+    if constexpr (penalty_mode(MODE) != GA_MODE_ASGD) ghat = g / penalty_of<MODE>(th, s, m, c);
     const float v_old = y;
     const float gv = c.gamma * v_old;
     const float vn = gv + ghat;
@@ -120,7 +133,7 @@ template <int MODE, bool KEEP_M>
 __device__ __forceinline__ float adam_one(float& th, float& x, float& y, float& m, float s, float g,
                                           const StepConst& c) {
     float coef = c.omb1;
-    if constexpr (MODE != GA_MODE_ASGD) coef = c.omb1 / penalty_of<MODE>(th, s, m, c);
+    if constexpr (penalty_mode(MODE) != GA_MODE_ASGD) coef = c.omb1 / penalty_of<MODE>(th, s, m, c);
     const float b1m = c.beta1 * x;
     const float cg = coef * g;
     const float m1n = b1m + cg;
@@ -203,7 +216,7 @@ template <int MODE, int DT, bool KEEP_M, bool SNAP, bool ALIGNED, bool STREAM_V,
 __global__ __launch_bounds__(kBlock) void apply_kernel(float* __restrict__ theta, float* __restrict__ v,
                                                        float* __restrict__ m, float* __restrict__ snap,
                                                        const void* __restrict__ g, uint64_t N, StepConst c) {
-    constexpr bool GAP = (MODE == GA_MODE_GA || MODE == GA_MODE_GA_HINGE);
+    constexpr bool GAP = is_gap(MODE);
     const uint64_t n4 = N >> 2;
     const uint64_t base = (uint64_t)blockIdx.x * (kBlock * U) + threadIdx.x;
 
@@ -258,7 +271,7 @@ __global__ __launch_bounds__(kBlock) void family_apply_kernel(float* __restrict_
                                                               float* __restrict__ y, float* __restrict__ m,
                                                               float* __restrict__ snap,
                                                               const void* __restrict__ g, uint64_t N, StepConst c) {
-    constexpr bool GAP = (MODE == GA_MODE_GA || MODE == GA_MODE_GA_HINGE);
+    constexpr bool GAP = is_gap(MODE);
     const uint64_t n4 = N >> 2;
     const uint64_t base = (uint64_t)blockIdx.x * (kBlock * U) + threadIdx.x;
 
@@ -434,17 +447,23 @@ __global__ __launch_bounds__(kBlock) void layer_gap_kernel(const LayerPartial* _
     gaps[blockIdx.x] = HINGE ? fmaxf(1.0f, graw) : 1.0f + graw;
 }
 
+template <bool NAG>
 __device__ __forceinline__ void layer_update_one(float& th, float& v, float& m, float g, float G, const StepConst& c) {
     const float ghat = g / G;
     const float gv = c.gamma * v;
     const float vn = gv + ghat;
-    const float step = c.lr * vn;
+    float dir = vn;
+    if constexpr (NAG) {
+        const float look = c.gamma * vn;
+        dir = ghat + look;
+    }
+    const float step = c.lr * dir;
     th = th - step;
     v = vn;
-    m = second_moment(m, vn, c);
+    m = second_moment(m, dir, c);
 }
 
-template <int DT, bool ALIGNED, bool STREAM_V>
+template <int DT, bool ALIGNED, bool STREAM_V, bool NAG>
 __global__ __launch_bounds__(kBlock) void layer_apply_kernel(float* __restrict__ theta, float* __restrict__ v,
                                                              float* __restrict__ m, float* __restrict__ snap,
                                                              const void* __restrict__ g,
@@ -455,7 +474,7 @@ __global__ __launch_bounds__(kBlock) void layer_apply_kernel(float* __restrict__
     const float G = gaps[ch.layer];
     auto scalar = [&](uint64_t j) {
         float t1 = theta[j], v1 = v[j], m1 = m[j];
-        layer_update_one(t1, v1, m1, load_g1<DT>(g, j), G, c);
+        layer_update_one<NAG>(t1, v1, m1, load_g1<DT>(g, j), G, c);
         theta[j] = t1; v[j] = v1; m[j] = m1; snap[j] = t1;
     };
     for (uint64_t j = r.start + threadIdx.x; j < r.a0; j += kBlock) scalar(j);
@@ -480,7 +499,7 @@ __global__ __launch_bounds__(kBlock) void layer_apply_kernel(float* __restrict__
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     float t1 = th[u][e], v1 = vv[u][e], m1 = mm[u][e];
-                    layer_update_one(t1, v1, m1, gg[u][e], G, c);
+                    layer_update_one<NAG>(t1, v1, m1, gg[u][e], G, c);
                     th[u][e] = t1; vv[u][e] = v1; mm[u][e] = m1;
                 }
                 store4<false>(theta, q, th[u]);
@@ -1000,9 +1019,10 @@ hipError_t launch_apply_adam(const StatePtrs& st, uint64_t N, uint32_t worker, c
 }
 
 hipError_t launch_apply(const StatePtrs& st, uint64_t N, uint32_t worker, const void* g, int grad_dtype, int mode,
-                        bool keep_m, bool write_snap, const StepConst& c, hipStream_t stream) {
+                        bool nesterov, bool keep_m, bool write_snap, const StepConst& c, hipStream_t stream) {
     float* snap = st.snaps + (uint64_t)worker * st.stride;
-    switch (mode) {
+    if (mode == GA_MODE_SA_STEP) mode = GA_MODE_ASGD;   // the step-size penalty is already folded into c.lr
+    switch (mode | (nesterov ? kNesterov : 0)) {
         case GA_MODE_GA:
             return launch_apply_m<GA_MODE_GA, true, true>(st, snap, g, grad_dtype, N, c, stream);
         case GA_MODE_GA_HINGE:
@@ -1010,15 +1030,23 @@ hipError_t launch_apply(const StatePtrs& st, uint64_t N, uint32_t worker, const 
         case GA_MODE_SA:
             return launch_apply_opt<GA_MODE_SA>(st, snap, g, grad_dtype, N, c, keep_m, write_snap, stream);
         case GA_MODE_ASGD:
-        case GA_MODE_SA_STEP:   // the step-size penalty is already folded into c.lr
             return launch_apply_opt<GA_MODE_ASGD>(st, snap, g, grad_dtype, N, c, keep_m, write_snap, stream);
+        case GA_MODE_GA | kNesterov:
+            return launch_apply_m<GA_MODE_GA | kNesterov, true, true>(st, snap, g, grad_dtype, N, c, stream);
+        case GA_MODE_GA_HINGE | kNesterov:
+            return launch_apply_m<GA_MODE_GA_HINGE | kNesterov, true, true>(st, snap, g, grad_dtype, N, c, stream);
+        case GA_MODE_SA | kNesterov:
+            return launch_apply_opt<GA_MODE_SA | kNesterov>(st, snap, g, grad_dtype, N, c, keep_m, write_snap, stream);
+        case GA_MODE_ASGD | kNesterov:
+            return launch_apply_opt<GA_MODE_ASGD | kNesterov>(st, snap, g, grad_dtype, N, c, keep_m, write_snap, stream);
         default:
             return hipErrorInvalidValue;
     }
 }
 
 hipError_t launch_apply_layerwise(const StatePtrs& st, uint64_t N, uint32_t worker, const void* g, int grad_dtype,
-                                  int mode, const LayerTables& lt, const StepConst& c, hipStream_t stream) {
+                                  int mode, bool nesterov, const LayerTables& lt, const StepConst& c,
+                                  hipStream_t stream) {
     if (lt.n_chunks == 0 || lt.n_layers == 0) return hipErrorInvalidValue;
     float* snap = st.snaps + (uint64_t)worker * st.stride;
     const dim3 block(kBlock), grid(lt.n_chunks), lgrid(lt.n_layers);
@@ -1032,8 +1060,14 @@ hipError_t launch_apply_layerwise(const StatePtrs& st, uint64_t N, uint32_t work
     const uintptr_t addr = reinterpret_cast<uintptr_t>(g);
     const bool stream_v = N > kKeepVMaxN;
 #define GA_LAYER_APPLY(DT, AL, SV)                                                                                  \
-    hipLaunchKernelGGL((layer_apply_kernel<DT, AL, SV>), grid, block, 0, stream, st.theta, st.v, st.m, snap, g,     \
-                       lt.chunks, lt.gaps, c)
+    do {                                                                                                            \
+        if (nesterov)                                                                                               \
+            hipLaunchKernelGGL((layer_apply_kernel<DT, AL, SV, true>), grid, block, 0, stream, st.theta, st.v, st.m, \
+                               snap, g, lt.chunks, lt.gaps, c);                                                     \
+        else                                                                                                        \
+            hipLaunchKernelGGL((layer_apply_kernel<DT, AL, SV, false>), grid, block, 0, stream, st.theta, st.v,     \
+                               st.m, snap, g, lt.chunks, lt.gaps, c);                                               \
+    } while (0)
     if (grad_dtype == GA_F32) {
         if ((addr & 15u) == 0) { if (stream_v) GA_LAYER_APPLY(GA_F32, true, true); else GA_LAYER_APPLY(GA_F32, true, false); }
         else { if (stream_v) GA_LAYER_APPLY(GA_F32, false, true); else GA_LAYER_APPLY(GA_F32, false, false); }
@@ -1047,7 +1081,8 @@ hipError_t launch_apply_layerwise(const StatePtrs& st, uint64_t N, uint32_t work
 
 hipError_t launch_persistent(const StatePtrs& st, uint64_t N, int family, const ga_arrival* dev_table,
                              const AdamRow* dev_adam_table, uint32_t T, uint64_t k0, const float* a,
-                             const float* theta_star, int mode, bool keep_m, const RunConst& rc, hipStream_t stream) {
+                             const float* theta_star, int mode, bool nesterov, bool keep_m, const RunConst& rc,
+                             hipStream_t stream) {
     const uint64_t groups = (N + 3) >> 2;
     const uint64_t blocks = (groups + kBlock - 1) / kBlock;
     if (blocks == 0 || blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
@@ -1055,22 +1090,25 @@ hipError_t launch_persistent(const StatePtrs& st, uint64_t N, int family, const 
 #define GA_LAUNCH_PERSIST(FAM, MODE, KEEP)                                                                          \
     hipLaunchKernelGGL((persistent_kernel<FAM, MODE, KEEP>), grid, block, 0, stream, st.theta, st.v, st.m, st.snaps, \
                        st.worker_v, st.v2, st.stride, a, theta_star, dev_table, dev_adam_table, T, k0, N, rc)
-#define GA_PERSIST_MODES(FAM)                                                                                       \
+#define GA_PERSIST_MODES(FAM, NAG)                                                                                  \
     switch (mode) {                                                                                                 \
-        case GA_MODE_GA: GA_LAUNCH_PERSIST(FAM, GA_MODE_GA, true); break;                                           \
-        case GA_MODE_GA_HINGE: GA_LAUNCH_PERSIST(FAM, GA_MODE_GA_HINGE, true); break;                               \
+        case GA_MODE_GA: GA_LAUNCH_PERSIST(FAM, GA_MODE_GA | NAG, true); break;                                     \
+        case GA_MODE_GA_HINGE: GA_LAUNCH_PERSIST(FAM, GA_MODE_GA_HINGE | NAG, true); break;                         \
         case GA_MODE_SA:                                                                                            \
-            if (keep_m) GA_LAUNCH_PERSIST(FAM, GA_MODE_SA, true); else GA_LAUNCH_PERSIST(FAM, GA_MODE_SA, false);   \
+            if (keep_m) GA_LAUNCH_PERSIST(FAM, GA_MODE_SA | NAG, true);                                             \
+            else GA_LAUNCH_PERSIST(FAM, GA_MODE_SA | NAG, false);                                                   \
             break;                                                                                                  \
         case GA_MODE_ASGD:                                                                                          \
         case GA_MODE_SA_STEP:                                                                                       \
-            if (keep_m) GA_LAUNCH_PERSIST(FAM, GA_MODE_ASGD, true); else GA_LAUNCH_PERSIST(FAM, GA_MODE_ASGD, false); \
+            if (keep_m) GA_LAUNCH_PERSIST(FAM, GA_MODE_ASGD | NAG, true);                                           \
+            else GA_LAUNCH_PERSIST(FAM, GA_MODE_ASGD | NAG, false);                                                 \
             break;                                                                                                  \
         default: return hipErrorInvalidValue;                                                                       \
     }
-    if (family == GA_FAMILY_DANA) { GA_PERSIST_MODES(GA_FAMILY_DANA) }
-    else if (family == GA_FAMILY_ADAM) { GA_PERSIST_MODES(GA_FAMILY_ADAM) }
-    else { GA_PERSIST_MODES(GA_FAMILY_MOMENTUM) }
+    if (family == GA_FAMILY_DANA) { GA_PERSIST_MODES(GA_FAMILY_DANA, 0) }
+    else if (family == GA_FAMILY_ADAM) { GA_PERSIST_MODES(GA_FAMILY_ADAM, 0) }
+    else if (nesterov) { GA_PERSIST_MODES(GA_FAMILY_MOMENTUM, kNesterov) }
+    else { GA_PERSIST_MODES(GA_FAMILY_MOMENTUM, 0) }
 #undef GA_PERSIST_MODES
 #undef GA_LAUNCH_PERSIST
     return hipGetLastError();

@@ -50,7 +50,7 @@ def test_struct_layouts_match_the_header():
     assert C.sizeof(ga.ga_arrival) == 16 and ga.ARRIVAL_DTYPE.itemsize == 16
     assert C.sizeof(ga.ga_diag) == 32
     assert ga.ga_grad_source.dev_a.offset == 8 and ga.ga_grad_source.seed.offset == 24
-    assert C.sizeof(ga.ga_config) == 72 and ga.ga_config.eta.offset == 20 and ga.ga_config.track_gap.offset == 48
+    assert C.sizeof(ga.ga_config) == 80 and ga.ga_config.eta.offset == 20 and ga.ga_config.track_gap.offset == 48
     cfg = ga.ga_config_init()
     assert (cfg.family, cfg.mode, cfg.track_gap, cfg.gap_scope, cfg.n_layers, cfg.host_layer_sizes) == (0, 3, 0, 0, 0, None)
     assert np.allclose([cfg.eta, cfg.gamma, cfg.beta, cfg.eps, cfg.adam_beta1, cfg.adam_beta2, cfg.adam_eps],

@@ -352,3 +352,43 @@ def test_persistent_tiny_vectors(N):
         assert bits_equal(host(M.theta()), O.theta) == 0, (N, family)
         for w in range(W):
             assert bits_equal(host(M.snapshot(w)), O.snaps[w]) == 0
+
+
+@pytest.mark.parametrize("mode", [ga.GA_MODE_ASGD, ga.GA_MODE_SA, ga.GA_MODE_SA_STEP, ga.GA_MODE_GA, ga.GA_MODE_GA_HINGE],
+                         ids=["asgd", "sa", "sa_step", "ga", "ga_hinge"])
+@pytest.mark.parametrize("path", ["persistent", "per_arrival", "buffers"])
+def test_nesterov_form(mode, path):
+    N, W, T, seed = 10_003, 6, 150, 12
+    a, ts = ga_inputs.curvatures(N, seed), ga_inputs.optimum(N, seed)
+    sched = ga.ga_simulate_schedule(W, T, seed=seed)
+    M = ga.Master(N, W, eta=0.05, mode=mode, nesterov=True, track_gap=True)
+    O = oracle.Master(N, W, mode, oracle.Hyper(0.05, 0.9), nesterov=True, track_gap=True)
+    if path == "buffers":
+        bufs = ga_inputs.gradient_buffers(W, N, seed, 0.2)
+        M.run_schedule(sched, ga.buffer_source([dev(b) for b in bufs]))
+        O.run_buffers(sched, bufs)
+    else:
+        g = torch.empty(N, dtype=torch.float32, device=DEV)
+        M.run_schedule(sched, ga.quadratic_source(dev(a), dev(ts), seed, 0.01, path == "persistent", g))
+        O.run_quadratic(sched, a, ts, seed)
+    compare_masters(M, O, "nesterov %s %s" % (MODE_NAMES[mode], path))
+
+
+def test_nesterov_layerwise_and_errors():
+    N, W, T, seed = 5000, 4, 60, 3
+    layers = [1000, 1500, 2500]
+    bufs = ga_inputs.gradient_buffers(W, N, seed, 0.2)
+    sched = ga.ga_simulate_schedule(W, T, seed=seed)
+    M = ga.Master(N, W, mode=ga.GA_MODE_GA, nesterov=True, layer_sizes=layers)
+    M.run_schedule(sched, ga.buffer_source([dev(b) for b in bufs]))
+    O = oracle.LayerwiseMaster(N, W, oracle.MODE_GA, oracle.Hyper(), layers, nesterov=True)
+    O.run_buffers(sched, bufs)
+    compare_masters(M, O, "nesterov layer-wise")
+    H = oracle.LayerwiseMaster(N, W, oracle.MODE_GA, oracle.Hyper(), layers)
+    H.run_buffers(sched, bufs)
+    assert not np.array_equal(H.theta, O.theta)
+    with pytest.raises(ga.GaError):
+        ga.Master(N, W, family=ga.GA_FAMILY_DANA, nesterov=True)
+    with pytest.raises(ga.GaError):
+        ga.Master(N, W, family=ga.GA_FAMILY_ADAM, nesterov=True)
+    assert torch.isfinite(M.theta()).all()
