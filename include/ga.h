@@ -251,6 +251,11 @@ int ga_simulate_schedule_ex(uint32_t n_workers, uint64_t T, const ga_time_model*
 int ga_simulate_speedup(uint32_t n_workers, uint64_t iters, const ga_time_model* model, uint64_t seed,
                         double* asgd_wall, double* ssgd_wall);
 
+/* Gradual warm-up of App. C.5: the step size starts at eta / n_workers and
+ * rises linearly to eta at master step warmup_steps.  Writes eta_k for the T
+ * steps k = k0+1 .. k0+T (evaluated in double, rounded to float). */
+int ga_warmup_lr(float eta, uint32_t n_workers, uint64_t warmup_steps, uint64_t k0, uint64_t T, float* host_eta);
+
 /* Delay bookkeeping of Alg. 3 / Alg. 5 for T arrivals starting after master
  * step k0: tau_k = k - iter[i]; iter[i] = k.  host_iter (n_workers entries) is
  * read and updated; host_tau receives T delays. */
@@ -316,6 +321,13 @@ int ga_apply(ga_ctx* ctx, uint32_t worker_id, const void* dev_grad, int grad_dty
 
 /* T arrivals in the order of host_schedule (worker ids), gradients from src. */
 int ga_run_schedule(ga_ctx* ctx, const uint32_t* host_schedule, uint64_t T, const ga_grad_source* src);
+
+/* The same with a step size per arrival: arrival a of this call uses
+ * eta_k = host_eta[a] (T values, each finite and > 0); eta_max and the step
+ * size set by ga_set_lr are not changed.  host_eta may be null (then this is
+ * ga_run_schedule). */
+int ga_run_schedule_lr(ga_ctx* ctx, const uint32_t* host_schedule, uint64_t T, const ga_grad_source* src,
+                       const float* host_eta);
 
 /* Write the quadratic-plus-noise gradient that worker_id would deliver at the
  * next arrival (step k+1) to dev_g_out (N floats, 16-byte aligned).  State is

@@ -92,6 +92,8 @@ SIGNATURES = {
     "ga_set_theta": (_i, [_p, _p]),
     "ga_apply": (_i, [_p, _u32, _p, _i]),
     "ga_run_schedule": (_i, [_p, _p, _u64, C.POINTER(ga_grad_source)]),
+    "ga_run_schedule_lr": (_i, [_p, _p, _u64, C.POINTER(ga_grad_source), _p]),
+    "ga_warmup_lr": (_i, [_f, _u32, _u64, _u64, _u64, _p]),
     "ga_quadratic_gradient": (_i, [_p, _u32, C.POINTER(ga_grad_source), _p]),
     "ga_diagnostics": (_i, [_p, _u32, C.POINTER(ga_diag)]),
     "ga_get_theta": (_i, [_p, _p]),
@@ -328,6 +330,19 @@ def ga_run_schedule(ctx, host_schedule, src, T=None):
     T = host_schedule.size if T is None else T
     assert T <= host_schedule.size
     _check(lib().ga_run_schedule(ctx, _np_ptr(host_schedule), T, C.byref(src)), ctx)
+
+
+def ga_run_schedule_lr(ctx, host_schedule, src, host_eta):
+    host_schedule = np.ascontiguousarray(host_schedule, dtype=np.uint32)
+    host_eta = np.ascontiguousarray(host_eta, dtype=np.float32)
+    assert host_eta.size == host_schedule.size
+    _check(lib().ga_run_schedule_lr(ctx, _np_ptr(host_schedule), host_schedule.size, C.byref(src), _np_ptr(host_eta)), ctx)
+
+
+def ga_warmup_lr(eta, n_workers, warmup_steps, k0, T):
+    out = np.empty(T, dtype=np.float32)
+    _check(lib().ga_warmup_lr(eta, n_workers, warmup_steps, k0, T, _np_ptr(out)))
+    return out
 
 
 def ga_quadratic_gradient(ctx, worker_id, src, dev_g_out):

@@ -257,12 +257,12 @@ ga_arrival make_row(uint32_t worker, uint64_t k, uint64_t tau, int mode, float e
 
 // Rows (and integer delays) of T arrivals after step k0.  Arguments are already validated.
 void plan(uint64_t T, const uint32_t* schedule, uint64_t k0, uint64_t* iter, int mode, float eta_k, float beta,
-          ga_arrival* rows, uint64_t* taus) {
+          ga_arrival* rows, uint64_t* taus, const float* eta_table = nullptr) {
     for (uint64_t a = 0; a < T; ++a) {
         const uint64_t k = k0 + a + 1;
         const uint32_t w = schedule[a];
         const uint64_t tau = k - iter[w];
-        rows[a] = make_row(w, k, tau, mode, eta_k, beta);
+        rows[a] = make_row(w, k, tau, mode, eta_table ? eta_table[a] : eta_k, beta);
         if (taus) taus[a] = tau;
         iter[w] = k;
     }
@@ -320,10 +320,10 @@ int check_quadratic_source(ga_ctx* ctx, const ga_grad_source* src) {
 }
 
 // One arrival through the fused kernel; the bookkeeping is committed only if the launch succeeded.
-int apply_one(ga_ctx* ctx, uint32_t worker, const void* dev_grad, int dtype, bool write_snap) {
+int apply_one(ga_ctx* ctx, uint32_t worker, const void* dev_grad, int dtype, bool write_snap, float eta_k) {
     const uint64_t k = ctx->k + 1;
     const uint64_t tau = k - ctx->iter[worker];
-    const ga_arrival row = make_row(worker, k, tau, ctx->mode, ctx->lr, ctx->beta);
+    const ga_arrival row = make_row(worker, k, tau, ctx->mode, eta_k, ctx->beta);
     const ga::StepConst sc = step_const(ctx, row, k);
     hipError_t e;
     if (ctx->gap_scope != GA_GAP_PARAMETER)
@@ -403,6 +403,19 @@ int ga_simulate_speedup(uint32_t n_workers, uint64_t iters, const ga_time_model*
     replay_arrivals(tm, n_workers, (uint64_t)n_workers * iters, [&](uint64_t, uint32_t, double t) { last = t; });
     *asgd_wall = last;
     *ssgd_wall = sync;
+    return GA_OK;
+}
+
+int ga_warmup_lr(float eta, uint32_t n_workers, uint64_t warmup_steps, uint64_t k0, uint64_t T, float* host_eta) {
+    if (!(eta > 0.f) || !std::isfinite(eta) || n_workers == 0 || (T > 0 && !host_eta))
+        return fail(nullptr, GA_ERR_ARG, "warmup_lr: bad argument");
+    const double lo = (double)eta / (double)n_workers;
+    for (uint64_t a = 0; a < T; ++a) {
+        const uint64_t k = k0 + a + 1;
+        double x = (double)eta;
+        if (k < warmup_steps) x = lo + ((double)eta - lo) * ((double)k / (double)warmup_steps);
+        host_eta[a] = (float)x;
+    }
     return GA_OK;
 }
 
@@ -642,12 +655,21 @@ int ga_apply(ga_ctx* ctx, uint32_t worker_id, const void* dev_grad, int grad_dty
     if (grad_dtype != GA_F32 && grad_dtype != GA_BF16) return fail(ctx, GA_ERR_ARG, "apply: unknown gradient dtype %d", grad_dtype);
     if (grad_dtype == GA_F32 && ((uintptr_t)dev_grad & 3u)) return fail(ctx, GA_ERR_ALIGN, "apply: float gradient must be 4-byte aligned");
     if (grad_dtype == GA_BF16 && ((uintptr_t)dev_grad & 1u)) return fail(ctx, GA_ERR_ALIGN, "apply: bfloat16 gradient must be 2-byte aligned");
-    return apply_one(ctx, worker_id, dev_grad, grad_dtype, is_gap_mode(ctx->mode) || ctx->track_gap);
+    return apply_one(ctx, worker_id, dev_grad, grad_dtype, is_gap_mode(ctx->mode) || ctx->track_gap, ctx->lr);
 }
 
 int ga_run_schedule(ga_ctx* ctx, const uint32_t* host_schedule, uint64_t T, const ga_grad_source* src) {
+    return ga_run_schedule_lr(ctx, host_schedule, T, src, nullptr);
+}
+
+int ga_run_schedule_lr(ga_ctx* ctx, const uint32_t* host_schedule, uint64_t T, const ga_grad_source* src,
+                       const float* host_eta) {
     if (!ctx) return GA_ERR_ARG;
     if (!src || (T > 0 && !host_schedule)) return fail(ctx, GA_ERR_ARG, "run_schedule: null argument");
+    if (host_eta)
+        for (uint64_t a = 0; a < T; ++a)
+            if (!(host_eta[a] > 0.f) || !std::isfinite(host_eta[a]))
+                return fail(ctx, GA_ERR_ARG, "run_schedule: eta[%llu] must be finite and > 0", (unsigned long long)a);
     for (uint64_t a = 0; a < T; ++a)
         if (host_schedule[a] >= ctx->W)
             return fail(ctx, GA_ERR_WORKER, "run_schedule: schedule[%llu] = %u >= n_workers %u", (unsigned long long)a, host_schedule[a], ctx->W);
@@ -664,7 +686,7 @@ int ga_run_schedule(ga_ctx* ctx, const uint32_t* host_schedule, uint64_t T, cons
         for (uint64_t a = 0; a < T; ++a) {
             const uint32_t w = host_schedule[a];
             const uint64_t b = (src->pick == GA_PICK_BY_WORKER) ? w % src->n_bufs : ctx->k % src->n_bufs;
-            const int rc = apply_one(ctx, w, src->host_dev_bufs[b], src->dtype, write_snap);
+            const int rc = apply_one(ctx, w, src->host_dev_bufs[b], src->dtype, write_snap, host_eta ? host_eta[a] : ctx->lr);
             if (rc != GA_OK) return rc;
         }
         return GA_OK;
@@ -688,7 +710,7 @@ int ga_run_schedule(ga_ctx* ctx, const uint32_t* host_schedule, uint64_t T, cons
             const hipError_t e = ga::launch_quadratic_gradient(ctx->st, ctx->N, w, src->dev_a, src->dev_theta_star,
                                                                ctx->k + 1, rcst, src->dev_scratch_g, ctx->stream);
             if (e != hipSuccess) return hip_fail(ctx, e, "gradient launch");
-            rc = apply_one(ctx, w, src->dev_scratch_g, GA_F32, true);
+            rc = apply_one(ctx, w, src->dev_scratch_g, GA_F32, true, host_eta ? host_eta[a] : ctx->lr);
             if (rc != GA_OK) return rc;
         }
         return GA_OK;
@@ -701,7 +723,7 @@ int ga_run_schedule(ga_ctx* ctx, const uint32_t* host_schedule, uint64_t T, cons
         std::vector<uint64_t> taus(n);
         ctx->rows.resize(n);
         plan(n, host_schedule + done, ctx->k, iter_after.data(), ctx->mode, ctx->lr, ctx->beta, ctx->rows.data(),
-             taus.data());
+             taus.data(), host_eta ? host_eta + done : nullptr);
         // pageable source: the runtime has consumed ctx->rows when the call returns
         hipError_t e = hipMemcpyAsync(ctx->dev_table, ctx->rows.data(), (size_t)n * sizeof(ga_arrival),
                                       hipMemcpyHostToDevice, ctx->stream);

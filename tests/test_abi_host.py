@@ -149,3 +149,17 @@ def test_workspace_size_and_create_validation():
     assert L.ga_get_theta(None, fake) == ga.GA_ERR_ARG
     assert L.ga_step(None) == 0
     L.ga_destroy(None)
+
+
+def test_warmup_schedule():
+    # App. C.5: start at eta / N, reach eta linearly at the end of the warm-up, constant afterwards
+    eta, W, steps = np.float32(0.1), 8, 50
+    lr = ga.ga_warmup_lr(float(eta), W, steps, 0, 80)
+    k = np.arange(1, 81, dtype=np.float64)
+    lo = float(eta) / W
+    expect = np.where(k < steps, lo + (float(eta) - lo) * k / steps, float(eta)).astype(np.float32)
+    assert np.array_equal(lr, expect)
+    assert lr[0] > lo and np.all(np.diff(lr[:steps]) > 0) and np.all(lr[steps - 1:] == eta)
+    assert np.array_equal(ga.ga_warmup_lr(float(eta), W, steps, 30, 50), lr[30:])
+    with pytest.raises(ga.GaError):
+        ga.ga_warmup_lr(0.0, W, steps, 0, 4)

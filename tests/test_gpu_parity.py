@@ -392,3 +392,30 @@ def test_nesterov_layerwise_and_errors():
     with pytest.raises(ga.GaError):
         ga.Master(N, W, family=ga.GA_FAMILY_ADAM, nesterov=True)
     assert torch.isfinite(M.theta()).all()
+
+
+@pytest.mark.parametrize("mode", [ga.GA_MODE_GA, ga.GA_MODE_SA_STEP], ids=["ga", "sa_step"])
+@pytest.mark.parametrize("path", ["persistent", "per_arrival", "buffers"])
+def test_per_arrival_step_sizes(mode, path):
+    # warm-up schedule (App. C.5): eta_k per arrival while eta_max stays at the peak value
+    N, W, T, seed = 8_001, 8, 120, 4
+    a, ts = ga_inputs.curvatures(N, seed), ga_inputs.optimum(N, seed)
+    sched = ga.ga_simulate_schedule(W, T, seed=seed)
+    lr = ga.ga_warmup_lr(0.1, W, 80, 0, T)
+    M = ga.Master(N, W, eta=0.1, mode=mode, track_gap=True)
+    O = oracle.Master(N, W, mode, oracle.Hyper(0.1, 0.9), track_gap=True)
+    bufs = ga_inputs.gradient_buffers(W, N, seed, 0.2)
+    g = torch.empty(N, dtype=torch.float32, device=DEV)
+    if path == "buffers":
+        src = ga.buffer_source([dev(b) for b in bufs])
+    else:
+        src = ga.quadratic_source(dev(a), dev(ts), seed, 0.01, path == "persistent", g)
+    ga.ga_run_schedule_lr(M.ctx, sched[:50], src, lr[:50])
+    ga.ga_run_schedule_lr(M.ctx, sched[50:], src, lr[50:])
+    for k, w in enumerate(sched):
+        w = int(w)
+        O.hyper.eta_k = float(lr[k])
+        O.apply(w, bufs[w] if path == "buffers" else oracle.quadratic_gradient(O.snaps[w], a, ts, seed, O.k + 1))
+    compare_masters(M, O, "warm-up %s %s" % (MODE_NAMES[mode], path))
+    with pytest.raises(ga.GaError):
+        ga.ga_run_schedule_lr(M.ctx, sched[:2], src, np.array([0.1, -1.0], np.float32))
