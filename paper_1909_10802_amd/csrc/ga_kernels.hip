@@ -682,7 +682,69 @@ __global__ __launch_bounds__(kBlock) void quadratic_gradient_kernel(const float*
 // grid-wide or block-wide synchronisation.  The snapshot of the next arrival
 // is requested before the arithmetic of the current one.
 // ---------------------------------------------------------------------------
-template <int FAMILY, int MODE, bool KEEP_M>
+// E consecutive floats held in registers; E = 4, 2 or 1 (one 128-, 64- or 32-bit access).
+template <int E>
+struct Pack {
+    float x[E];
+};
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+template <int E>
+__device__ __forceinline__ Pack<E> pack_load(const float* base, uint64_t idx) {   // idx counts packs
+    Pack<E> r;
+    if constexpr (E == 4) {
+        const f32x4 t = reinterpret_cast<const f32x4*>(base)[idx];
+        r.x[0] = t.x; r.x[1] = t.y; r.x[2] = t.z; r.x[3] = t.w;
+    } else if constexpr (E == 2) {
+        const f32x2 t = reinterpret_cast<const f32x2*>(base)[idx];
+        r.x[0] = t.x; r.x[1] = t.y;
+    } else {
+        r.x[0] = base[idx];
+    }
+    return r;
+}
+
+template <int E>
+__device__ __forceinline__ void pack_store(float* base, uint64_t idx, const Pack<E>& r) {
+    if constexpr (E == 4) reinterpret_cast<f32x4*>(base)[idx] = f32x4{r.x[0], r.x[1], r.x[2], r.x[3]};
+    else if constexpr (E == 2) reinterpret_cast<f32x2*>(base)[idx] = f32x2{r.x[0], r.x[1]};
+    else base[idx] = r.x[0];
+}
+
+template <int E>
+__device__ __forceinline__ Pack<E> pack_zero() {
+    Pack<E> r;
+#pragma unroll
+    for (int e = 0; e < E; ++e) r.x[e] = 0.0f;
+    return r;
+}
+
+// z for parameters j0 .. j0+E-1 (j0 a multiple of E) at master step k.  The Philox block of
+// floor(j0/4) is computed by every thread that needs a part of it.
+template <int E>
+__device__ __forceinline__ Pack<E> noise_pack(uint32_t seed_lo, uint32_t seed_hi, uint64_t j0, uint64_t k) {
+    const uint64_t q = j0 >> 2;
+    uint32_t x[4];
+    philox4x32_10((uint32_t)q, (uint32_t)(q >> 32), (uint32_t)k, (uint32_t)(k >> 32), seed_lo, seed_hi, x);
+    Pack<E> z;
+    if constexpr (E == 4) {
+        box_muller_pair(x[0], x[1], z.x[0], z.x[1]);
+        box_muller_pair(x[2], x[3], z.x[2], z.x[3]);
+    } else {
+        const bool upper = ((j0 >> 1) & 1) != 0;
+        float zc, zs;
+        box_muller_pair(upper ? x[2] : x[0], upper ? x[3] : x[1], zc, zs);
+        if constexpr (E == 2) {
+            z.x[0] = zc;
+            z.x[1] = zs;
+        } else {
+            z.x[0] = (j0 & 1) ? zs : zc;
+        }
+    }
+    return z;
+}
+
+template <int FAMILY, int MODE, bool KEEP_M, int E>
 __global__ __launch_bounds__(kBlock) void persistent_kernel(float* __restrict__ theta, float* __restrict__ x,
                                                             float* __restrict__ m, float* snaps, float* worker_v,
                                                             float* __restrict__ v2, uint64_t stride,
@@ -693,27 +755,30 @@ __global__ __launch_bounds__(kBlock) void persistent_kernel(float* __restrict__ 
                                                             uint64_t k0, uint64_t N, RunConst rc) {
     constexpr bool DANA = (FAMILY == GA_FAMILY_DANA);
     constexpr bool ADAM = (FAMILY == GA_FAMILY_ADAM);
-    const uint64_t q = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
-    const uint64_t j0 = 4 * q;
+    const uint64_t p = (uint64_t)blockIdx.x * kBlock + threadIdx.x;   // pack index
+    const uint64_t j0 = (uint64_t)E * p;
     if (j0 >= N || T == 0) return;
-    const uint32_t n_valid = (N - j0 >= 4) ? 4u : (uint32_t)(N - j0);
+    const uint32_t n_valid = (N - j0 >= (uint64_t)E) ? (uint32_t)E : (uint32_t)(N - j0);
 
-    // state arrays are padded to a multiple of 64 floats: the 128-bit access is always in bounds
-    f32x4 th = reinterpret_cast<const f32x4*>(theta)[q];
-    f32x4 xx = reinterpret_cast<const f32x4*>(x)[q];          // v | sum_j v_j | m1
-    f32x4 mm = {0.f, 0.f, 0.f, 0.f};
-    if constexpr (KEEP_M) mm = reinterpret_cast<const f32x4*>(m)[q];
-    f32x4 yy = {0.f, 0.f, 0.f, 0.f};                          // ADAM: v2 (registers); DANA: v_i of the arriving worker
-    if constexpr (ADAM) yy = reinterpret_cast<const f32x4*>(v2)[q];
-    f32x4 a4, t4;
-    if (n_valid == 4) {
-        a4 = reinterpret_cast<const f32x4*>(a)[q];
-        t4 = reinterpret_cast<const f32x4*>(ts)[q];
+    // state arrays are padded to a multiple of 64 floats: the vector access is always in bounds
+    Pack<E> th = pack_load<E>(theta, p);
+    Pack<E> xx = pack_load<E>(x, p);                           // v | sum_j v_j | m1
+    Pack<E> mm = pack_zero<E>();
+    if constexpr (KEEP_M) mm = pack_load<E>(m, p);
+    Pack<E> yy = pack_zero<E>();                               // ADAM: v2 (registers); DANA: v_i of the arriving worker
+    if constexpr (ADAM) yy = pack_load<E>(v2, p);
+    Pack<E> a4 = pack_zero<E>(), t4 = pack_zero<E>();
+    if (n_valid == (uint32_t)E) {
+        a4 = pack_load<E>(a, p);
+        t4 = pack_load<E>(ts, p);
     } else {   // caller arrays hold exactly N floats
-        a4.x = a[j0];                          t4.x = ts[j0];
-        a4.y = n_valid > 1 ? a[j0 + 1] : 0.f;  t4.y = n_valid > 1 ? ts[j0 + 1] : 0.f;
-        a4.z = n_valid > 2 ? a[j0 + 2] : 0.f;  t4.z = n_valid > 2 ? ts[j0 + 2] : 0.f;
-        a4.w = 0.f;                            t4.w = 0.f;
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            if ((uint32_t)e < n_valid) {
+                a4.x[e] = a[j0 + e];
+                t4.x[e] = ts[j0 + e];
+            }
+        }
     }
 
     StepConst c = {};
@@ -721,21 +786,18 @@ __global__ __launch_bounds__(kBlock) void persistent_kernel(float* __restrict__ 
     c.one_minus_beta = rc.one_minus_beta;
     c.beta1 = rc.beta1; c.omb1 = rc.omb1; c.beta2 = rc.beta2; c.omb2 = rc.omb2; c.adam_eps = rc.adam_eps;
 
-    f32x4* const snap_q = reinterpret_cast<f32x4*>(snaps) + q;       // this thread's column of the snapshots
-    f32x4* const wv_q = reinterpret_cast<f32x4*>(worker_v) + q;      // DANA: and of the worker momenta
-    const uint64_t stride4 = stride >> 2;
     ga_arrival row = table[0];
-    f32x4 s = snap_q[(uint64_t)row.worker * stride4];
-    if constexpr (DANA) yy = wv_q[(uint64_t)row.worker * stride4];
+    Pack<E> s = pack_load<E>(snaps + (uint64_t)row.worker * stride, p);   // this thread's column of the snapshots
+    if constexpr (DANA) yy = pack_load<E>(worker_v + (uint64_t)row.worker * stride, p);
 
     for (uint32_t t = 0; t < T; ++t) {
         const bool more = (t + 1 < T);
         ga_arrival next = row;
-        f32x4 s_next = s, y_next = yy;
+        Pack<E> s_next = s, y_next = yy;
         if (more) {
             next = table[t + 1];
-            s_next = snap_q[(uint64_t)next.worker * stride4];
-            if constexpr (DANA) y_next = wv_q[(uint64_t)next.worker * stride4];
+            s_next = pack_load<E>(snaps + (uint64_t)next.worker * stride, p);
+            if constexpr (DANA) y_next = pack_load<E>(worker_v + (uint64_t)next.worker * stride, p);
         }
         const uint64_t k = k0 + t + 1;
         c.lr = row.lr; c.tau = row.tau; c.inv_bc_prev = row.inv_bc_prev;
@@ -745,32 +807,28 @@ __global__ __launch_bounds__(kBlock) void persistent_kernel(float* __restrict__ 
             c.inv_bc1 = ar.inv_bc1;
             c.inv_bc2 = ar.inv_bc2;
         }
-        const f32x4 z = noise4(rc.seed_lo, rc.seed_hi, q, k);
+        const Pack<E> z = noise_pack<E>(rc.seed_lo, rc.seed_hi, j0, k);
 
-        f32x4 g;
-        g.x = quadratic_g(s.x, a4.x, t4.x, rc.sigma, z.x);
-        g.y = quadratic_g(s.y, a4.y, t4.y, rc.sigma, z.y);
-        g.z = quadratic_g(s.z, a4.z, t4.z, rc.sigma, z.z);
-        g.w = quadratic_g(s.w, a4.w, t4.w, rc.sigma, z.w);
-
-        f32x4 out = s;                                       // what the worker is sent; padding lanes unchanged
-        if constexpr (FAMILY == GA_FAMILY_MOMENTUM) {
-            update4<MODE, KEEP_M>(th, xx, mm, s, g, c, n_valid);
-            out = th;
-        } else {
+        Pack<E> out = s;                                     // what the worker is sent; padding lanes unchanged
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                if ((uint32_t)e < n_valid) {
-                    float t1 = th[e], x1 = xx[e], y1 = yy[e], m1 = mm[e];
-                    if constexpr (DANA) out[e] = dana_one<MODE, KEEP_M>(t1, x1, y1, m1, s[e], g[e], c);
-                    else out[e] = adam_one<MODE, KEEP_M>(t1, x1, y1, m1, s[e], g[e], c);
-                    th[e] = t1; xx[e] = x1; yy[e] = y1; mm[e] = m1;
+        for (int e = 0; e < E; ++e) {
+            if ((uint32_t)e < n_valid) {
+                const float g = quadratic_g(s.x[e], a4.x[e], t4.x[e], rc.sigma, z.x[e]);
+                float t1 = th.x[e], x1 = xx.x[e], y1 = yy.x[e], m1 = mm.x[e];
+                if constexpr (DANA) {
+                    out.x[e] = dana_one<MODE, KEEP_M>(t1, x1, y1, m1, s.x[e], g, c);
+                } else if constexpr (ADAM) {
+                    out.x[e] = adam_one<MODE, KEEP_M>(t1, x1, y1, m1, s.x[e], g, c);
+                } else {
+                    update_one<MODE, KEEP_M>(t1, x1, m1, s.x[e], g, c);
+                    out.x[e] = t1;
                 }
+                th.x[e] = t1; xx.x[e] = x1; yy.x[e] = y1; mm.x[e] = m1;
             }
         }
 
-        snap_q[(uint64_t)row.worker * stride4] = out;
-        if constexpr (DANA) wv_q[(uint64_t)row.worker * stride4] = yy;
+        pack_store<E>(snaps + (uint64_t)row.worker * stride, p, out);
+        if constexpr (DANA) pack_store<E>(worker_v + (uint64_t)row.worker * stride, p, yy);
         // same worker twice in a row: its rows are what was just written
         const bool same = (next.worker == row.worker);
         s = same ? out : s_next;
@@ -778,10 +836,10 @@ __global__ __launch_bounds__(kBlock) void persistent_kernel(float* __restrict__ 
         row = next;
     }
 
-    reinterpret_cast<f32x4*>(theta)[q] = th;
-    reinterpret_cast<f32x4*>(x)[q] = xx;
-    if constexpr (KEEP_M) reinterpret_cast<f32x4*>(m)[q] = mm;
-    if constexpr (ADAM) reinterpret_cast<f32x4*>(v2)[q] = yy;
+    pack_store<E>(theta, p, th);
+    pack_store<E>(x, p, xx);
+    if constexpr (KEEP_M) pack_store<E>(m, p, mm);
+    if constexpr (ADAM) pack_store<E>(v2, p, yy);
 }
 
 // ---------------------------------------------------------------------------
@@ -904,6 +962,11 @@ uint32_t blocks_for(uint64_t items, uint64_t per_block, uint32_t cap) {
 // Dispatch of the apply kernel over (mode, dtype, keep_m, aligned).
 // ---------------------------------------------------------------------------
 constexpr int kApplyU = 2;
+// below this many parameters the persistent kernel gives each thread 2 instead of 4 of them
+#ifndef GA_PERSIST_WIDE_MIN_N
+#define GA_PERSIST_WIDE_MIN_N (1ull << 21)
+#endif
+constexpr uint64_t kPersistWideMinN = GA_PERSIST_WIDE_MIN_N;
 
 // theta and v together must fit the memory-side cache with room to spare for v to be kept in it
 constexpr uint64_t kKeepVMaxN = (uint64_t)208 * 1024 * 1024 / 8;
@@ -1083,13 +1146,24 @@ hipError_t launch_persistent(const StatePtrs& st, uint64_t N, int family, const 
                              const AdamRow* dev_adam_table, uint32_t T, uint64_t k0, const float* a,
                              const float* theta_star, int mode, bool nesterov, bool keep_m, const RunConst& rc,
                              hipStream_t stream) {
-    const uint64_t groups = (N + 3) >> 2;
-    const uint64_t blocks = (groups + kBlock - 1) / kBlock;
+    // Four parameters per thread share one Philox block; short vectors use two per thread (the block is
+    // then computed twice) so that every SIMD still has several wavefronts to switch between.
+    const int ept = (N >= kPersistWideMinN) ? 4 : 2;
+    const uint64_t packs = (N + ept - 1) / ept;
+    const uint64_t blocks = (packs + kBlock - 1) / kBlock;
     if (blocks == 0 || blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
     const dim3 grid((uint32_t)blocks), block(kBlock);
 #define GA_LAUNCH_PERSIST(FAM, MODE, KEEP)                                                                          \
-    hipLaunchKernelGGL((persistent_kernel<FAM, MODE, KEEP>), grid, block, 0, stream, st.theta, st.v, st.m, st.snaps, \
-                       st.worker_v, st.v2, st.stride, a, theta_star, dev_table, dev_adam_table, T, k0, N, rc)
+    do {                                                                                                            \
+        if (ept == 4)                                                                                               \
+            hipLaunchKernelGGL((persistent_kernel<FAM, MODE, KEEP, 4>), grid, block, 0, stream, st.theta, st.v,     \
+                               st.m, st.snaps, st.worker_v, st.v2, st.stride, a, theta_star, dev_table,             \
+                               dev_adam_table, T, k0, N, rc);                                                       \
+        else                                                                                                        \
+            hipLaunchKernelGGL((persistent_kernel<FAM, MODE, KEEP, 2>), grid, block, 0, stream, st.theta, st.v,     \
+                               st.m, st.snaps, st.worker_v, st.v2, st.stride, a, theta_star, dev_table,             \
+                               dev_adam_table, T, k0, N, rc);                                                       \
+    } while (0)
 #define GA_PERSIST_MODES(FAM, NAG)                                                                                  \
     switch (mode) {                                                                                                 \
         case GA_MODE_GA: GA_LAUNCH_PERSIST(FAM, GA_MODE_GA | NAG, true); break;                                     \
