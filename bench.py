@@ -26,11 +26,11 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 ALU_PEAK_TLOPS = 78.65         # fp32 vector 157.3 TFLOP/s / 2 flop per lane-operation
 # VALU lane-operations per parameter-update of the persistent kernel (SQ_INSTS_VALU * 64 / updates, profiles/)
-VALU_PER_UPDATE = {"ga": 105.7, "ga_hinge": 105.7}
+VALU_PER_UPDATE = {"ga": 106.7, "ga_hinge": 106.7}
 # HBM-side bytes per fused-update launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE scaled by a copy of
 # known size; profiles/apply_kernel_cfg3.md), valid for the kernel source with this hash only
 TRAFFIC = {
-    ("cfg3", "ga"): {"bytes": 919952188, "read": 511031080, "written": 408921108, "kernels_sha256": "d528a7f674a4ce73"},
+    ("cfg3", "ga"): {"bytes": 919956539, "read": 511035070, "written": 408921469, "kernels_sha256": "fb7694344ce44456"},
 }
 BYTES_PER_UPDATE = {           # algorithmic bytes per parameter per arrival, fused update
     ("ga", "f32"): 36, ("ga", "bf16"): 34, ("ga_hinge", "f32"): 36, ("ga_hinge", "bf16"): 34,
