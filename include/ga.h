@@ -370,6 +370,19 @@ int ga_get_delays(const ga_ctx* ctx, uint64_t* host_out, uint64_t max_n, uint64_
  * with the ga_put_* calls).  Every iter[i] must be <= k. */
 int ga_set_bookkeeping(ga_ctx* ctx, uint64_t k, const uint64_t* host_iter);
 
+/* Checkpoint.  The device state of a context (theta, v, m, the W snapshots and
+ * the family's extra arrays, in the workspace's own padded layout) is
+ * ga_state_bytes(ctx) bytes.  ga_export_state copies it to dev_dst (device
+ * buffer of at least that size, 16-byte aligned) and writes the host
+ * bookkeeping: *k and host_iter[n_workers].  ga_import_state restores both into
+ * a context created with the same N, n_workers, family and gap scope
+ * (GA_ERR_ARG if `bytes` differs from ga_state_bytes, or an iter[i] > k).
+ * Hyper-parameters are not part of the checkpoint.  Running on after an
+ * import gives bit for bit the trajectory of the uninterrupted run. */
+size_t ga_state_bytes(const ga_ctx* ctx);
+int ga_export_state(ga_ctx* ctx, void* dev_dst, size_t bytes, uint64_t* k, uint64_t* host_iter);
+int ga_import_state(ga_ctx* ctx, const void* dev_src, size_t bytes, uint64_t k, const uint64_t* host_iter);
+
 /* Fill dev_out[0..n) with z(seed, k, j0 + j), the standard-normal noise of the
  * quadratic source.  One Philox4x32-10 block (Salmon et al., SC'11) with
  * counter (floor(j/4), k) and key seed serves parameters 4q..4q+3: words

@@ -108,6 +108,9 @@ SIGNATURES = {
     "ga_get_iter": (_i, [_p, _p]),
     "ga_get_delays": (_i, [_p, _p, _u64, C.POINTER(_u64)]),
     "ga_set_bookkeeping": (_i, [_p, _u64, _p]),
+    "ga_state_bytes": (C.c_size_t, [_p]),
+    "ga_export_state": (_i, [_p, _p, C.c_size_t, C.POINTER(_u64), _p]),
+    "ga_import_state": (_i, [_p, _p, C.c_size_t, _u64, _p]),
     "ga_noise_fill": (_i, [_u64, _u64, _u64, _u64, _p, _p]),
     "ga_box_muller_raw": (_i, [_p, _p, _u64, _p, _p, _p]),
     "ga_last_error": (C.c_char_p, [_p]),
@@ -401,6 +404,25 @@ def ga_get_delays(ctx):
 def ga_set_bookkeeping(ctx, k, host_iter):
     host_iter = np.ascontiguousarray(host_iter, dtype=np.uint64)
     _check(lib().ga_set_bookkeeping(ctx, k, _np_ptr(host_iter)), ctx)
+
+
+def ga_state_bytes(ctx):
+    return lib().ga_state_bytes(ctx)
+
+
+def ga_export_state(ctx, n_workers, dev_dst):
+    """Copy the device state into dev_dst (uint8 CUDA tensor); returns (k, iter)."""
+    import torch
+    k = _u64()
+    it = np.empty(n_workers, dtype=np.uint64)
+    _check(lib().ga_export_state(ctx, _dev(dev_dst, torch.uint8), dev_dst.numel(), C.byref(k), _np_ptr(it)), ctx)
+    return k.value, it
+
+
+def ga_import_state(ctx, dev_src, k, host_iter):
+    import torch
+    host_iter = np.ascontiguousarray(host_iter, dtype=np.uint64)
+    _check(lib().ga_import_state(ctx, _dev(dev_src, torch.uint8), dev_src.numel(), k, _np_ptr(host_iter)), ctx)
 
 
 def ga_noise_fill(seed, k, j0, n, dev_out, stream=None):

@@ -28,6 +28,7 @@ struct ga_ctx {
     ga::StatePtrs st{};
     ga_arrival* dev_table = nullptr;
     ga::AdamRow* dev_adam_table = nullptr;
+    size_t state_bytes = 0;        // theta .. last state row, contiguous in the workspace
     ga::DiagPartial* dev_partials = nullptr;
     uint64_t k = 0;
     std::vector<uint64_t> iter;
@@ -566,6 +567,7 @@ int ga_create_ex(ga_ctx** out, const ga_config* cfg, void* dev_workspace, size_t
     c->rows.reserve(ga::kTableCap);
 
     c->gap_scope = cfg->gap_scope;
+    c->state_bytes = (size_t)L.n_rows * L.Np * sizeof(float);
     // all state rows are contiguous: one fill
     hipError_t e = ga::launch_fill(c->st.theta, L.n_rows * L.Np, 0.0f, c->stream);
     if (e == hipSuccess && n_layers > 0) {
@@ -877,6 +879,32 @@ int ga_box_muller_raw(const uint32_t* dev_xa, const uint32_t* dev_xb, uint64_t n
     if (n > 0 && (!dev_xa || !dev_xb || !dev_zc || !dev_zs)) return fail(nullptr, GA_ERR_ARG, "box_muller_raw: null argument");
     const hipError_t e = ga::launch_box_muller_raw(dev_xa, dev_xb, n, dev_zc, dev_zs, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? GA_OK : hip_fail(nullptr, e, "box_muller_raw launch");
+}
+
+size_t ga_state_bytes(const ga_ctx* ctx) { return ctx ? ctx->state_bytes : 0; }
+
+int ga_export_state(ga_ctx* ctx, void* dev_dst, size_t bytes, uint64_t* k, uint64_t* host_iter) {
+    if (!ctx) return GA_ERR_ARG;
+    if (!dev_dst || !k || !host_iter) return fail(ctx, GA_ERR_ARG, "export_state: null argument");
+    if (bytes < ctx->state_bytes) return fail(ctx, GA_ERR_ARG, "export_state: buffer has %zu bytes, %zu needed", bytes, ctx->state_bytes);
+    const hipError_t e = hipMemcpyAsync(dev_dst, ctx->st.theta, ctx->state_bytes, hipMemcpyDeviceToDevice, ctx->stream);
+    if (e != hipSuccess) return hip_fail(ctx, e, "export_state copy");
+    *k = ctx->k;
+    std::memcpy(host_iter, ctx->iter.data(), ctx->W * sizeof(uint64_t));
+    return GA_OK;
+}
+
+int ga_import_state(ga_ctx* ctx, const void* dev_src, size_t bytes, uint64_t k, const uint64_t* host_iter) {
+    if (!ctx) return GA_ERR_ARG;
+    if (!dev_src || !host_iter) return fail(ctx, GA_ERR_ARG, "import_state: null argument");
+    if (bytes != ctx->state_bytes) return fail(ctx, GA_ERR_ARG, "import_state: checkpoint has %zu bytes, this context %zu", bytes, ctx->state_bytes);
+    for (uint32_t w = 0; w < ctx->W; ++w)
+        if (host_iter[w] > k) return fail(ctx, GA_ERR_ARG, "import_state: iter[%u] is ahead of k", w);
+    const hipError_t e = hipMemcpyAsync(ctx->st.theta, dev_src, ctx->state_bytes, hipMemcpyDeviceToDevice, ctx->stream);
+    if (e != hipSuccess) return hip_fail(ctx, e, "import_state copy");
+    ctx->k = k;
+    ctx->iter.assign(host_iter, host_iter + ctx->W);
+    return GA_OK;
 }
 
 int ga_noise_fill(uint64_t seed, uint64_t k, uint64_t j0, uint64_t n, float* dev_out, void* hip_stream) {

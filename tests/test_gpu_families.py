@@ -209,3 +209,32 @@ def test_resnet50_size_sampled(family):
     del M, bufs
     gc.collect()
     torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("family", [ga.GA_FAMILY_MOMENTUM, ga.GA_FAMILY_DANA, ga.GA_FAMILY_ADAM], ids=["momentum", "dana", "adam"])
+def test_export_import_state_resumes_bit_identically(family):
+    N, W, T, seed = 30_001, 5, 140, 8
+    eta = 0.01 if family == ga.GA_FAMILY_ADAM else 0.1
+    a, ts = ga_inputs.curvatures(N, seed), ga_inputs.optimum(N, seed)
+    sched = ga.ga_simulate_schedule(W, T, seed=seed)
+    src = ga.quadratic_source(dev(a), dev(ts), seed)
+    A = ga.Master(N, W, eta=eta, mode=ga.GA_MODE_GA, family=family)
+    A.run_schedule(sched, src)
+    B = ga.Master(N, W, eta=eta, mode=ga.GA_MODE_GA, family=family)
+    B.run_schedule(sched[:60], src)
+    ckpt = torch.empty(ga.ga_state_bytes(B.ctx), dtype=torch.uint8, device=DEV)
+    k, it = ga.ga_export_state(B.ctx, W, ckpt)
+    assert k == 60 and np.array_equal(it, B.iter())
+    C2 = ga.Master(N, W, eta=eta, mode=ga.GA_MODE_GA, family=family)
+    ga.ga_import_state(C2.ctx, ckpt, k, it)
+    C2.run_schedule(sched[60:], src)
+    assert bits_equal(host(A.theta()), host(C2.theta())) == 0 and bits_equal(host(A.m()), host(C2.m())) == 0
+    for w in range(W):
+        assert bits_equal(host(A.snapshot(w)), host(C2.snapshot(w))) == 0
+    assert C2.k == A.k and np.array_equal(C2.iter(), A.iter())
+    other = ga.Master(N + 64, W, eta=eta, mode=ga.GA_MODE_GA, family=family)
+    with pytest.raises(ga.GaError) as e:
+        ga.ga_import_state(other.ctx, ckpt, k, it)
+    assert e.value.status == ga.GA_ERR_ARG
+    with pytest.raises(ga.GaError):
+        ga.ga_import_state(C2.ctx, ckpt, 3, np.full(W, 9, np.uint64))
