@@ -230,8 +230,8 @@ def cpu_baseline_quadratic(cfg, mode, n_slice, n_steps):
 def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on one GPU only (the master update shards by parameter range with no "
-              "exchange; see DESIGN.md). Run with --gpus 1.", file=sys.stderr)
+        print("bench.py: this library runs on one GPU only (the master update would shard by parameter range with "
+              "no exchange between shards, but that is not implemented). Run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
 
     import torch
