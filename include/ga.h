@@ -21,7 +21,8 @@
  *   - "dev" pointers are device (HBM) addresses, "host" pointers are host
  *     addresses.  The library never allocates or frees device memory: every
  *     device buffer, including the workspace, belongs to the caller and must
- *     stay valid until ga_destroy.  The library owns only the host-side ga_ctx.
+ *     stay valid until ga_destroy.  The library owns only the host-side ga_ctx
+ *     (with a few hundred KB of pinned host memory for staging the arrival table).
  *   - Every call that touches the device enqueues on the HIP stream given to
  *     ga_create and returns without waiting, unless stated otherwise.
  *   - Every function returning int returns a ga_status.  On any error nothing
@@ -319,7 +320,10 @@ int ga_set_theta(ga_ctx* ctx, const float* dev_theta0);
  * parameter. */
 int ga_apply(ga_ctx* ctx, uint32_t worker_id, const void* dev_grad, int grad_dtype);
 
-/* T arrivals in the order of host_schedule (worker ids), gradients from src. */
+/* T arrivals in the order of host_schedule (worker ids), gradients from src.
+ * All arguments are checked before the first arrival (then nothing has
+ * changed on error); if a HIP call fails later (GA_ERR_HIP), the arrivals
+ * enqueued before it stay applied and recorded: ga_step tells how many. */
 int ga_run_schedule(ga_ctx* ctx, const uint32_t* host_schedule, uint64_t T, const ga_grad_source* src);
 
 /* The same with a step size per arrival: arrival a of this call uses

@@ -33,7 +33,12 @@ struct ga_ctx {
     uint64_t k = 0;
     std::vector<uint64_t> iter;
     std::vector<uint64_t> delays;
-    std::vector<ga_arrival> rows;   // staging for one chunk of the table
+    // pinned staging for one chunk of the arrival table (and Adam's rows); `staged` is recorded after
+    // the upload so that the next chunk does not overwrite rows that are still being copied
+    ga_arrival* rows = nullptr;
+    ga::AdamRow* adam_rows = nullptr;
+    hipEvent_t staged = nullptr;
+    bool staged_pending = false;
     int gap_scope = GA_GAP_PARAMETER;
     ga::LayerTables layers{};
     std::vector<ga::LayerChunk> host_chunks;   // uploaded at create; kept for the lifetime of the context
@@ -564,7 +569,6 @@ int ga_create_ex(ga_ctx** out, const ga_config* cfg, void* dev_workspace, size_t
     c->dev_adam_table = reinterpret_cast<ga::AdamRow*>(base + L.off_adam_table);
     c->dev_partials = reinterpret_cast<ga::DiagPartial*>(base + L.off_partials);
     c->iter.assign(n_workers, 0);
-    c->rows.reserve(ga::kTableCap);
 
     c->gap_scope = cfg->gap_scope;
     c->state_bytes = (size_t)L.n_rows * L.Np * sizeof(float);
@@ -586,9 +590,12 @@ int ga_create_ex(ga_ctx** out, const ga_config* cfg, void* dev_workspace, size_t
         if (e == hipSuccess)
             e = hipMemcpyAsync(dspans, c->host_spans.data(), (size_t)n_layers * sizeof(ga::LayerSpan), hipMemcpyHostToDevice, c->stream);
     }
+    if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void**>(&c->rows), ga::kTableCap * sizeof(ga_arrival), hipHostMallocDefault);
+    if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void**>(&c->adam_rows), ga::kTableCap * sizeof(ga::AdamRow), hipHostMallocDefault);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&c->staged, hipEventDisableTiming);
     if (e != hipSuccess) {
-        const int rc = hip_fail(nullptr, e, "create: initial fill");
-        delete c;
+        const int rc = hip_fail(nullptr, e, "create: initial fill or host staging");
+        ga_destroy(c);
         return rc;
     }
     *out = c;
@@ -607,7 +614,14 @@ int ga_create(ga_ctx** out, uint64_t N, uint32_t n_workers, float eta, float gam
     return ga_create_ex(out, &cfg, dev_workspace, workspace_bytes, hip_stream);
 }
 
-void ga_destroy(ga_ctx* ctx) { delete ctx; }
+void ga_destroy(ga_ctx* ctx) {
+    if (!ctx) return;
+    if (ctx->staged_pending) (void)hipEventSynchronize(ctx->staged);
+    if (ctx->staged) (void)hipEventDestroy(ctx->staged);
+    if (ctx->rows) (void)hipHostFree(ctx->rows);
+    if (ctx->adam_rows) (void)hipHostFree(ctx->adam_rows);
+    delete ctx;
+}
 
 int ga_set_beta_eps(ga_ctx* ctx, float beta, float eps) {
     if (!ctx) return GA_ERR_ARG;
@@ -723,22 +737,27 @@ int ga_run_schedule_lr(ga_ctx* ctx, const uint32_t* host_schedule, uint64_t T, c
         const uint32_t n = (uint32_t)((T - done < ga::kTableCap) ? (T - done) : ga::kTableCap);
         std::vector<uint64_t> iter_after = ctx->iter;
         std::vector<uint64_t> taus(n);
-        ctx->rows.resize(n);
-        plan(n, host_schedule + done, ctx->k, iter_after.data(), ctx->mode, ctx->lr, ctx->beta, ctx->rows.data(),
-             taus.data(), host_eta ? host_eta + done : nullptr);
-        // pageable source: the runtime has consumed ctx->rows when the call returns
-        hipError_t e = hipMemcpyAsync(ctx->dev_table, ctx->rows.data(), (size_t)n * sizeof(ga_arrival),
-                                      hipMemcpyHostToDevice, ctx->stream);
+        hipError_t e = hipSuccess;
+        if (ctx->staged_pending) {               // the previous upload from the staging rows must have finished
+            e = hipEventSynchronize(ctx->staged);
+            if (e != hipSuccess) return hip_fail(ctx, e, "table staging");
+            ctx->staged_pending = false;
+        }
+        plan(n, host_schedule + done, ctx->k, iter_after.data(), ctx->mode, ctx->lr, ctx->beta, ctx->rows, taus.data(),
+             host_eta ? host_eta + done : nullptr);
+        e = hipMemcpyAsync(ctx->dev_table, ctx->rows, (size_t)n * sizeof(ga_arrival), hipMemcpyHostToDevice, ctx->stream);
         if (e != hipSuccess) return hip_fail(ctx, e, "table upload");
         if (ctx->family == GA_FAMILY_ADAM) {
-            std::vector<ga::AdamRow> ar(n);
             for (uint32_t a = 0; a < n; ++a) {
-                ar[a].inv_bc1 = inverse_bias_correction(ctx->beta1, ctx->k + a + 1);
-                ar[a].inv_bc2 = inverse_bias_correction(ctx->beta2, ctx->k + a + 1);
+                ctx->adam_rows[a].inv_bc1 = inverse_bias_correction(ctx->beta1, ctx->k + a + 1);
+                ctx->adam_rows[a].inv_bc2 = inverse_bias_correction(ctx->beta2, ctx->k + a + 1);
             }
-            e = hipMemcpyAsync(ctx->dev_adam_table, ar.data(), (size_t)n * sizeof(ga::AdamRow), hipMemcpyHostToDevice, ctx->stream);
+            e = hipMemcpyAsync(ctx->dev_adam_table, ctx->adam_rows, (size_t)n * sizeof(ga::AdamRow), hipMemcpyHostToDevice, ctx->stream);
             if (e != hipSuccess) return hip_fail(ctx, e, "table upload");
         }
+        e = hipEventRecord(ctx->staged, ctx->stream);
+        if (e != hipSuccess) return hip_fail(ctx, e, "table staging");
+        ctx->staged_pending = true;
         e = ga::launch_persistent(ctx->st, ctx->N, ctx->family, ctx->dev_table, ctx->dev_adam_table, n, ctx->k, src->dev_a,
                                   src->dev_theta_star, ctx->mode, ctx->nesterov, keeps_m(ctx), rcst, ctx->stream);
         if (e != hipSuccess) return hip_fail(ctx, e, "persistent launch");
