@@ -163,3 +163,59 @@ def test_warmup_schedule():
     assert np.array_equal(ga.ga_warmup_lr(float(eta), W, steps, 30, 50), lr[30:])
     with pytest.raises(ga.GaError):
         ga.ga_warmup_lr(0.0, W, steps, 0, 4)
+
+
+def test_bookkeeping_matches_oracle_on_random_schedules():
+    from hypothesis import given, settings, strategies as st
+
+    @settings(max_examples=60, deadline=None)
+    @given(st.integers(1, 40), st.lists(st.integers(0, 10_000), min_size=0, max_size=300), st.integers(0, 1000),
+           st.sampled_from([ga.GA_MODE_ASGD, ga.GA_MODE_SA, ga.GA_MODE_SA_STEP, ga.GA_MODE_GA, ga.GA_MODE_GA_HINGE]))
+    def check(W, raw, k0, mode):
+        sched = (np.array(raw, dtype=np.uint64) % W).astype(np.uint32)
+        rng = np.random.default_rng(len(raw) + W)
+        it0 = rng.integers(0, k0 + 1, W).astype(np.uint64)
+        tau, it = ga.ga_delays_from_schedule(W, sched, k0, it0.copy())
+        tau_o, it_o = oracle.delays(W, sched, k0, it0.copy())
+        assert np.array_equal(tau, tau_o) and np.array_equal(it, it_o)
+        rows = ga.ga_plan_arrivals(W, sched, k0, it0.copy(), mode, 0.05, 0.99)
+        assert np.array_equal(rows["tau"], tau_o.astype(np.float32)) and np.array_equal(rows["worker"], sched)
+        assert np.all(tau_o >= 1)
+
+    check()
+
+
+def test_oracle_is_clean_under_address_and_undefined_sanitizers(tmp_path):
+    # host code only: the oracle rebuilt with -fsanitize and driven through a short trajectory of every master
+    import subprocess
+    import sys
+    lib = str(tmp_path / "libga_oracle_san.so")
+    subprocess.check_call(["g++", "-O1", "-g", "-std=c++17", "-ffp-contract=off", "-fopenmp", "-fPIC", "-shared",
+                           "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined", "-o", lib,
+                           os.path.join(ROOT, "oracle", "ga_oracle.cpp")])
+    script = r'''
+import sys, numpy as np
+sys.path.insert(0, %r)
+import oracle
+oracle._LIB = %r
+oracle.build = lambda force=False: oracle._LIB
+N, W, T = 1003, 5, 60
+a = np.linspace(0.1, 1, N).astype(np.float32); ts = np.cos(np.arange(N)).astype(np.float32)
+sched = oracle.simulate_schedule(W, T, oracle.DIST_HETERO, 1.5, 3)
+for cls, kw in [(oracle.Master, {}), (oracle.Master, {"nesterov": True}), (oracle.DanaMaster, {}), (oracle.AdamMaster, {})]:
+    for mode in (oracle.MODE_SA, oracle.MODE_GA, oracle.MODE_GA_HINGE):
+        M = cls(N, W, mode, oracle.Hyper(0.01, 0.9), **kw)
+        M.run_quadratic(sched, a, ts, 7)
+        M.gap_statistics(1)
+L = oracle.LayerwiseMaster(N, W, oracle.MODE_GA, oracle.Hyper(), [3, 500, 500])
+L.run_quadratic(sched, a, ts, 7)
+oracle.simulate_schedule_gamma(8, 200, oracle.DIST_GAMMA_HETERO, 1, 128.0, 0.6, 0.1)
+oracle.speedup_times(4, 50, oracle.DIST_GAMMA_HOMO, 1)
+oracle.box_muller_raw(np.arange(100, dtype=np.uint32) << np.uint32(9), np.arange(100, dtype=np.uint32) * np.uint32(40503))
+print("sanitized oracle ok")
+''' % (ROOT, lib)
+    asan = subprocess.check_output(["gcc", "-print-file-name=libasan.so"], text=True).strip()
+    ubsan = subprocess.check_output(["gcc", "-print-file-name=libubsan.so"], text=True).strip()
+    env = dict(os.environ, LD_PRELOAD=asan + " " + ubsan, ASAN_OPTIONS="detect_leaks=0")
+    out = subprocess.run([sys.executable, "-c", script], env=env, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    assert out.returncode == 0 and "sanitized oracle ok" in out.stdout, out.stdout[-3000:]
