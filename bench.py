@@ -55,7 +55,7 @@ def parse():
     p.add_argument("--calibration-copy", action="store_true",
                    help="after the timed region run three plain device copies of N floats (known size: 4N bytes read, "
                         "4N written) so that a counter profile of this command can be scaled")
-    p.add_argument("--cpu-slice", type=int, default=1 << 22, help="parameters in the CPU-oracle sample")
+    p.add_argument("--cpu-slice", type=int, default=1 << 23, help="parameters in the CPU-oracle sample")
     p.add_argument("--cpu-steps", type=int, default=2000, help="arrivals in the CPU-oracle sample")
     return p.parse_args()
 
@@ -75,14 +75,24 @@ def cpu_baseline(cfg, mode, n_slice, n_steps):
     modes = dict(ga=oracle.MODE_GA, ga_hinge=oracle.MODE_GA_HINGE, sa=oracle.MODE_SA, sa_step=oracle.MODE_SA_STEP,
                  asgd=oracle.MODE_ASGD)
     O = oracle.Master(n_slice, W, modes[mode], oracle.Hyper(cfg["eta"], cfg["gamma"]))
-    O.run_buffers(sched[:8], bufs, pick_by_worker=(cfg["pick"] == "worker"))       # touch the pages
+    by_worker = cfg["pick"] == "worker"
+    O.run_buffers(sched[:8], bufs, pick_by_worker=by_worker)       # touch the pages
+    n_one = min(64, (n_steps - 8) // 4)                            # a short single-thread leg first
+    cores = oracle.num_threads()
+    oracle.set_num_threads(1)
     t0 = time.perf_counter()
-    O.run_buffers(sched[8:], bufs, pick_by_worker=(cfg["pick"] == "worker"))
+    O.run_buffers(sched[8:8 + n_one], bufs, pick_by_worker=by_worker)
+    dt1 = time.perf_counter() - t0
+    oracle.set_num_threads(cores)
+    t0 = time.perf_counter()
+    O.run_buffers(sched[8 + n_one:], bufs, pick_by_worker=by_worker)
     dt = time.perf_counter() - t0
-    updates = float(n_slice) * (n_steps - 8)
-    return {"value": updates / dt / 1e9, "unit": "G param-updates/s", "cores": oracle.num_threads(), "kind": "oracle",
-            "sample": "contiguous slice of %d parameters, all %d workers, %d arrivals of the same schedule and "
-                      "gradient recipe (%.1f s)" % (n_slice, W, n_steps - 8, dt)}
+    n_all = n_steps - 8 - n_one
+    return {"value": float(n_slice) * n_all / dt / 1e9, "unit": "G param-updates/s", "cores": cores, "kind": "oracle",
+            "value_1_core": float(n_slice) * n_one / dt1 / 1e9,
+            "sample": "contiguous slice of %d parameters, all %d workers, the same schedule and gradient recipe: "
+                      "%d arrivals on %d threads (%.1f s) after %d arrivals on one thread (%.1f s)"
+                      % (n_slice, W, n_all, cores, dt, n_one, dt1)}
 
 
 def kernels_hash():
