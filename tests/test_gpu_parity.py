@@ -419,3 +419,45 @@ def test_per_arrival_step_sizes(mode, path):
     compare_masters(M, O, "warm-up %s %s" % (MODE_NAMES[mode], path))
     with pytest.raises(ga.GaError):
         ga.ga_run_schedule_lr(M.ctx, sched[:2], src, np.array([0.1, -1.0], np.float32))
+
+
+def test_many_workers_and_context_churn():
+    # 1000 workers on a short vector; contexts created and destroyed repeatedly; two masters interleaved on two streams
+    N, W, T, seed = 515, 1000, 3000, 2
+    a, ts = ga_inputs.curvatures(N, seed), ga_inputs.optimum(N, seed)
+    da = torch.zeros(516, dtype=torch.float32, device=DEV)[:N]
+    dts = torch.zeros(516, dtype=torch.float32, device=DEV)[:N]
+    da.copy_(dev(a))
+    dts.copy_(dev(ts))
+    sched = ga.ga_simulate_schedule(W, T, ga.GA_DIST_LOGNORMAL, 1.0, seed)
+    M = ga.Master(N, W, mode=ga.GA_MODE_GA)
+    M.run_schedule(sched, ga.quadratic_source(da, dts, seed))
+    O = oracle.Master(N, W, oracle.MODE_GA, oracle.Hyper())
+    O.run_quadratic(sched, a, ts, seed)
+    assert bits_equal(host(M.theta()), O.theta) == 0
+    assert np.array_equal(M.delays(), np.array(O.tau_log, np.uint64)) and M.delays().max() > W
+    for _ in range(200):
+        X = ga.Master(64, 2, mode=ga.GA_MODE_GA)
+        X.run_schedule(np.array([0, 1, 1], np.uint32), ga.quadratic_source(da[:64], dts[:64], 1))
+        X.close()
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    sched2 = ga.ga_simulate_schedule(4, 200, seed=5)
+    with torch.cuda.stream(s1):
+        A = ga.Master(N, 4, mode=ga.GA_MODE_GA, stream=s1)
+    with torch.cuda.stream(s2):
+        B = ga.Master(N, 4, mode=ga.GA_MODE_SA, stream=s2)
+    for lo in range(0, 200, 25):
+        with torch.cuda.stream(s1):
+            A.run_schedule(sched2[lo:lo + 25], ga.quadratic_source(da, dts, 3))
+        with torch.cuda.stream(s2):
+            B.run_schedule(sched2[lo:lo + 25], ga.quadratic_source(da, dts, 4))
+    with torch.cuda.stream(s1):
+        ta = A.theta()
+    with torch.cuda.stream(s2):
+        tb = B.theta()
+    torch.cuda.synchronize()
+    OA = oracle.Master(N, 4, oracle.MODE_GA, oracle.Hyper())
+    OA.run_quadratic(sched2, a, ts, 3)
+    OB = oracle.Master(N, 4, oracle.MODE_SA, oracle.Hyper())
+    OB.run_quadratic(sched2, a, ts, 4)
+    assert bits_equal(host(ta), OA.theta) == 0 and bits_equal(host(tb), OB.theta) == 0
