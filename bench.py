@@ -96,9 +96,12 @@ def cpu_baseline(cfg, mode, n_slice, n_steps):
 
 
 def kernels_hash():
+    """Hash of the sources of the fused-update kernel (its own file and the shared device header)."""
     import hashlib
-    path = os.path.join(ROOT, "paper_1909_10802_amd", "csrc", "ga_kernels.hip")
-    return hashlib.sha256(open(path, "rb").read()).hexdigest()[:16]
+    h = hashlib.sha256()
+    for name in ("ga_device.h", "ga_apply.hip"):
+        h.update(open(os.path.join(ROOT, "paper_1909_10802_amd", "csrc", name), "rb").read())
+    return h.hexdigest()[:16]
 
 
 def bench_fused(args, cfg, torch, ga, ga_inputs):

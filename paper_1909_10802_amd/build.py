@@ -1,12 +1,14 @@
 """Build libga.so (gfx950) in-tree with hipcc."""
 import os
 import subprocess
+import tempfile
+from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libga.so")
-SOURCES = ["ga_kernels.hip", "ga_host.cpp"]
+SOURCES = ["ga_apply.hip", "ga_persistent.hip", "ga_layerwise.hip", "ga_aux.hip", "ga_host.cpp"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
@@ -17,12 +19,7 @@ HIPCC_FLAGS = [
 ]
 
 
-def build(verbose=False):
-    """Compile every source for gfx950 and link the shared library. Always recompiles."""
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *HIPCC_FLAGS, "-shared", "-o", LIB]
-    for src in SOURCES:
-        cmd += ["-x", "hip", os.path.join(CSRC, src)]
+def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd))
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
@@ -31,6 +28,17 @@ def build(verbose=False):
         raise RuntimeError("hipcc failed:\n" + out)
     if verbose and out.strip():
         print(out)
+
+
+def build(verbose=False):
+    """Compile every source for gfx950 (in parallel) and link the shared library. Always recompiles."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    with tempfile.TemporaryDirectory(prefix="libga_build_") as tmp:
+        objs = [os.path.join(tmp, os.path.splitext(s)[0] + ".o") for s in SOURCES]
+        cmds = [[hipcc, *HIPCC_FLAGS, "-c", "-x", "hip", os.path.join(CSRC, s), "-o", o] for s, o in zip(SOURCES, objs)]
+        with ThreadPoolExecutor(max_workers=min(len(cmds), 8)) as pool:
+            list(pool.map(lambda c: _run(c, verbose), cmds))
+        _run([hipcc, "--offload-arch=gfx950", "-fPIC", "-shared", "-o", LIB, *objs], verbose)
     return LIB
 
 

@@ -1,0 +1,273 @@
+// libga, gfx950: fused update of one arrival.
+//   apply_kernel         MOMENTUM family (Alg. 2-5 + Alg. 14), gradient from HBM
+//   family_apply_kernel  DANA (Alg. 6-8) and Adam (Alg. 9-11) masters
+// The path is elementwise (Sec. 4.3: every parameter is penalised independently), bound by HBM
+// traffic; there is no contraction and therefore no MFMA.
+
+#include "ga_device.h"
+
+namespace ga {
+namespace {
+
+// ---------------------------------------------------------------------------
+// Fused update of one arrival.  Each thread owns U groups of four consecutive
+// parameters, 256 groups apart, so that every wavefront issues 1 KiB
+// contiguous 128-bit loads and stores per array.  All loads of a thread are
+// issued before the first dependent operation.
+// ---------------------------------------------------------------------------
+template <int MODE, int DT, bool KEEP_M, bool SNAP, bool ALIGNED, bool STREAM_V, int U>
+__global__ __launch_bounds__(kBlock) void apply_kernel(float* __restrict__ theta, float* __restrict__ v,
+                                                       float* __restrict__ m, float* __restrict__ snap,
+                                                       const void* __restrict__ g, uint64_t N, StepConst c) {
+    constexpr bool GAP = is_gap(MODE);
+    const uint64_t n4 = N >> 2;
+    const uint64_t base = (uint64_t)blockIdx.x * (kBlock * U) + threadIdx.x;
+
+    f32x4 th[U], vv[U], mm[U], ss[U], gg[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const uint64_t q = base + (uint64_t)u * kBlock;
+        mm[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+        ss[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (q < n4) {
+            th[u] = load4<false>(theta, q);
+            vv[u] = load4<STREAM_V>(v, q);
+            if constexpr (KEEP_M) mm[u] = load4<true>(m, q);
+            if constexpr (GAP) ss[u] = load4<true>(snap, q);
+            gg[u] = load_g4<DT, ALIGNED>(g, q);
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const uint64_t q = base + (uint64_t)u * kBlock;
+        if (q < n4) {
+            update4<MODE, KEEP_M>(th[u], vv[u], mm[u], ss[u], gg[u], c);
+            store4<false>(theta, q, th[u]);
+            store4<STREAM_V>(v, q, vv[u]);
+            if constexpr (KEEP_M) store4<true>(m, q, mm[u]);
+            if constexpr (SNAP) store4<true>(snap, q, th[u]);
+        }
+    }
+
+    // ragged tail: the last N % 4 parameters, one per thread of block 0
+    if (blockIdx.x == 0 && threadIdx.x < (N & 3)) {
+        const uint64_t j = 4 * n4 + threadIdx.x;
+        float t1 = theta[j], v1 = v[j], m1 = 0.0f, s1 = 0.0f;
+        if constexpr (KEEP_M) m1 = m[j];
+        if constexpr (GAP) s1 = snap[j];
+        update_one<MODE, KEEP_M>(t1, v1, m1, s1, load_g1<DT>(g, j), c);
+        theta[j] = t1;
+        v[j] = v1;
+        if constexpr (KEEP_M) m[j] = m1;
+        if constexpr (SNAP) snap[j] = t1;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Fused update of one arrival for the DANA and ADAM families: the same launch
+// shape as apply_kernel with one more state array.  x: vsum | m1 (touched at
+// every arrival, kept in the memory-side cache when it fits); y: the arriving
+// worker's v_i (streamed) | v2.
+// ---------------------------------------------------------------------------
+template <int FAMILY, int MODE, int DT, bool KEEP_M, bool SNAP, bool ALIGNED, bool STREAM_X, int U>
+__global__ __launch_bounds__(kBlock) void family_apply_kernel(float* __restrict__ theta, float* __restrict__ x,
+                                                              float* __restrict__ y, float* __restrict__ m,
+                                                              float* __restrict__ snap,
+                                                              const void* __restrict__ g, uint64_t N, StepConst c) {
+    constexpr bool GAP = is_gap(MODE);
+    const uint64_t n4 = N >> 2;
+    const uint64_t base = (uint64_t)blockIdx.x * (kBlock * U) + threadIdx.x;
+
+    f32x4 th[U], xx[U], yy[U], mm[U], ss[U], gg[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const uint64_t q = base + (uint64_t)u * kBlock;
+        mm[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+        ss[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (q < n4) {
+            th[u] = load4<false>(theta, q);
+            xx[u] = load4<STREAM_X>(x, q);
+            yy[u] = load4<true>(y, q);
+            if constexpr (KEEP_M) mm[u] = load4<true>(m, q);
+            if constexpr (GAP) ss[u] = load4<true>(snap, q);
+            gg[u] = load_g4<DT, ALIGNED>(g, q);
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const uint64_t q = base + (uint64_t)u * kBlock;
+        if (q < n4) {
+            f32x4 out;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                float t1 = th[u][e], x1 = xx[u][e], y1 = yy[u][e], m1 = mm[u][e];
+                if constexpr (FAMILY == GA_FAMILY_DANA) out[e] = dana_one<MODE, KEEP_M>(t1, x1, y1, m1, ss[u][e], gg[u][e], c);
+                else out[e] = adam_one<MODE, KEEP_M>(t1, x1, y1, m1, ss[u][e], gg[u][e], c);
+                th[u][e] = t1; xx[u][e] = x1; yy[u][e] = y1; mm[u][e] = m1;
+            }
+            store4<false>(theta, q, th[u]);
+            store4<STREAM_X>(x, q, xx[u]);
+            store4<true>(y, q, yy[u]);
+            if constexpr (KEEP_M) store4<true>(m, q, mm[u]);
+            if constexpr (SNAP) store4<true>(snap, q, out);
+        }
+    }
+
+    if (blockIdx.x == 0 && threadIdx.x < (N & 3)) {
+        const uint64_t j = 4 * n4 + threadIdx.x;
+        float t1 = theta[j], x1 = x[j], y1 = y[j], m1 = 0.0f, s1 = 0.0f, out;
+        if constexpr (KEEP_M) m1 = m[j];
+        if constexpr (GAP) s1 = snap[j];
+        if constexpr (FAMILY == GA_FAMILY_DANA) out = dana_one<MODE, KEEP_M>(t1, x1, y1, m1, s1, load_g1<DT>(g, j), c);
+        else out = adam_one<MODE, KEEP_M>(t1, x1, y1, m1, s1, load_g1<DT>(g, j), c);
+        theta[j] = t1;
+        x[j] = x1;
+        y[j] = y1;
+        if constexpr (KEEP_M) m[j] = m1;
+        if constexpr (SNAP) snap[j] = out;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Dispatch of the apply kernel over (mode, dtype, keep_m, aligned).
+// ---------------------------------------------------------------------------
+constexpr int kApplyU = 2;
+
+
+template <int MODE, int DT, bool KEEP_M, bool SNAP, bool ALIGNED>
+hipError_t launch_apply_t(const StatePtrs& st, float* snap, const void* g, uint64_t N, const StepConst& c,
+                          hipStream_t stream) {
+    const uint64_t n4 = N >> 2;
+    const uint64_t per_block = (uint64_t)kBlock * kApplyU;
+    const uint64_t blocks = (n4 + per_block - 1) / per_block;
+    if (blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    const dim3 grid(blocks == 0 ? 1u : (uint32_t)blocks), block(kBlock);
+    if (N <= kKeepVMaxN)
+        hipLaunchKernelGGL((apply_kernel<MODE, DT, KEEP_M, SNAP, ALIGNED, false, kApplyU>), grid, block, 0, stream,
+                           st.theta, st.v, st.m, snap, g, N, c);
+    else
+        hipLaunchKernelGGL((apply_kernel<MODE, DT, KEEP_M, SNAP, ALIGNED, true, kApplyU>), grid, block, 0, stream,
+                           st.theta, st.v, st.m, snap, g, N, c);
+    return hipGetLastError();
+}
+
+template <int MODE, bool KEEP_M, bool SNAP>
+hipError_t launch_apply_m(const StatePtrs& st, float* snap, const void* g, int dt, uint64_t N, const StepConst& c,
+                          hipStream_t stream) {
+    const uintptr_t addr = reinterpret_cast<uintptr_t>(g);
+    if (dt == GA_F32) {
+        if ((addr & 15u) == 0) return launch_apply_t<MODE, GA_F32, KEEP_M, SNAP, true>(st, snap, g, N, c, stream);
+        return launch_apply_t<MODE, GA_F32, KEEP_M, SNAP, false>(st, snap, g, N, c, stream);
+    }
+    if ((addr & 7u) == 0) return launch_apply_t<MODE, GA_BF16, KEEP_M, SNAP, true>(st, snap, g, N, c, stream);
+    return launch_apply_t<MODE, GA_BF16, KEEP_M, SNAP, false>(st, snap, g, N, c, stream);
+}
+
+// non-GA modes: m and the snapshot are optional
+template <int MODE>
+hipError_t launch_apply_opt(const StatePtrs& st, float* snap, const void* g, int dt, uint64_t N, const StepConst& c,
+                            bool keep_m, bool write_snap, hipStream_t stream) {
+    if (keep_m) {
+        return write_snap ? launch_apply_m<MODE, true, true>(st, snap, g, dt, N, c, stream)
+                          : launch_apply_m<MODE, true, false>(st, snap, g, dt, N, c, stream);
+    }
+    return write_snap ? launch_apply_m<MODE, false, true>(st, snap, g, dt, N, c, stream)
+                      : launch_apply_m<MODE, false, false>(st, snap, g, dt, N, c, stream);
+}
+
+// ---------------------------------------------------------------------------
+// Dispatch of the DANA / ADAM kernel.
+// ---------------------------------------------------------------------------
+constexpr int kFamilyU = 1;
+
+template <int FAMILY, int MODE, int DT, bool KEEP_M, bool SNAP, bool ALIGNED>
+hipError_t launch_family_t(float* theta, float* x, float* y, float* m, float* snap, const void* g, uint64_t N,
+                           const StepConst& c, hipStream_t stream) {
+    const uint64_t n4 = N >> 2;
+    const uint64_t per_block = (uint64_t)kBlock * kFamilyU;
+    const uint64_t blocks = (n4 + per_block - 1) / per_block;
+    if (blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    const dim3 grid(blocks == 0 ? 1u : (uint32_t)blocks), block(kBlock);
+    if (N <= kKeepVMaxN)
+        hipLaunchKernelGGL((family_apply_kernel<FAMILY, MODE, DT, KEEP_M, SNAP, ALIGNED, false, kFamilyU>), grid, block,
+                           0, stream, theta, x, y, m, snap, g, N, c);
+    else
+        hipLaunchKernelGGL((family_apply_kernel<FAMILY, MODE, DT, KEEP_M, SNAP, ALIGNED, true, kFamilyU>), grid, block,
+                           0, stream, theta, x, y, m, snap, g, N, c);
+    return hipGetLastError();
+}
+
+template <int FAMILY, int MODE, bool KEEP_M, bool SNAP>
+hipError_t launch_family_m(float* theta, float* x, float* y, float* m, float* snap, const void* g, int dt,
+                           uint64_t N, const StepConst& c, hipStream_t stream) {
+    const uintptr_t addr = reinterpret_cast<uintptr_t>(g);
+    if (dt == GA_F32) {
+        if ((addr & 15u) == 0)
+            return launch_family_t<FAMILY, MODE, GA_F32, KEEP_M, SNAP, true>(theta, x, y, m, snap, g, N, c, stream);
+        return launch_family_t<FAMILY, MODE, GA_F32, KEEP_M, SNAP, false>(theta, x, y, m, snap, g, N, c, stream);
+    }
+    if ((addr & 7u) == 0)
+        return launch_family_t<FAMILY, MODE, GA_BF16, KEEP_M, SNAP, true>(theta, x, y, m, snap, g, N, c, stream);
+    return launch_family_t<FAMILY, MODE, GA_BF16, KEEP_M, SNAP, false>(theta, x, y, m, snap, g, N, c, stream);
+}
+
+template <int FAMILY>
+hipError_t launch_family(float* theta, float* x, float* y, float* m, float* snap, const void* g, int dt, uint64_t N,
+                         int mode, bool keep_m, bool write_snap, const StepConst& c, hipStream_t stream) {
+#define GA_FAM(MODE, KEEP, SNAP) launch_family_m<FAMILY, MODE, KEEP, SNAP>(theta, x, y, m, snap, g, dt, N, c, stream)
+    switch (mode) {
+        case GA_MODE_GA: return GA_FAM(GA_MODE_GA, true, true);
+        case GA_MODE_GA_HINGE: return GA_FAM(GA_MODE_GA_HINGE, true, true);
+        case GA_MODE_SA:
+            if (keep_m) return write_snap ? GA_FAM(GA_MODE_SA, true, true) : GA_FAM(GA_MODE_SA, true, false);
+            return write_snap ? GA_FAM(GA_MODE_SA, false, true) : GA_FAM(GA_MODE_SA, false, false);
+        case GA_MODE_ASGD:
+            if (keep_m) return write_snap ? GA_FAM(GA_MODE_ASGD, true, true) : GA_FAM(GA_MODE_ASGD, true, false);
+            return write_snap ? GA_FAM(GA_MODE_ASGD, false, true) : GA_FAM(GA_MODE_ASGD, false, false);
+        default: return hipErrorInvalidValue;
+    }
+#undef GA_FAM
+}
+
+}  // namespace
+
+hipError_t launch_apply_dana(const StatePtrs& st, uint64_t N, uint32_t worker, const void* g, int grad_dtype, int mode,
+                             bool keep_m, bool write_snap, const StepConst& c, hipStream_t stream) {
+    return launch_family<GA_FAMILY_DANA>(st.theta, st.v, st.worker_v + (uint64_t)worker * st.stride, st.m,
+                                         st.snaps + (uint64_t)worker * st.stride, g, grad_dtype, N, mode, keep_m,
+                                         write_snap, c, stream);
+}
+
+hipError_t launch_apply_adam(const StatePtrs& st, uint64_t N, uint32_t worker, const void* g, int grad_dtype, int mode,
+                             bool keep_m, bool write_snap, const StepConst& c, hipStream_t stream) {
+    return launch_family<GA_FAMILY_ADAM>(st.theta, st.v, st.v2, st.m, st.snaps + (uint64_t)worker * st.stride, g,
+                                         grad_dtype, N, mode, keep_m, write_snap, c, stream);
+}
+
+hipError_t launch_apply(const StatePtrs& st, uint64_t N, uint32_t worker, const void* g, int grad_dtype, int mode,
+                        bool nesterov, bool keep_m, bool write_snap, const StepConst& c, hipStream_t stream) {
+    float* snap = st.snaps + (uint64_t)worker * st.stride;
+    if (mode == GA_MODE_SA_STEP) mode = GA_MODE_ASGD;   // the step-size penalty is already folded into c.lr
+    switch (mode | (nesterov ? kNesterov : 0)) {
+        case GA_MODE_GA:
+            return launch_apply_m<GA_MODE_GA, true, true>(st, snap, g, grad_dtype, N, c, stream);
+        case GA_MODE_GA_HINGE:
+            return launch_apply_m<GA_MODE_GA_HINGE, true, true>(st, snap, g, grad_dtype, N, c, stream);
+        case GA_MODE_SA:
+            return launch_apply_opt<GA_MODE_SA>(st, snap, g, grad_dtype, N, c, keep_m, write_snap, stream);
+        case GA_MODE_ASGD:
+            return launch_apply_opt<GA_MODE_ASGD>(st, snap, g, grad_dtype, N, c, keep_m, write_snap, stream);
+        case GA_MODE_GA | kNesterov:
+            return launch_apply_m<GA_MODE_GA | kNesterov, true, true>(st, snap, g, grad_dtype, N, c, stream);
+        case GA_MODE_GA_HINGE | kNesterov:
+            return launch_apply_m<GA_MODE_GA_HINGE | kNesterov, true, true>(st, snap, g, grad_dtype, N, c, stream);
+        case GA_MODE_SA | kNesterov:
+            return launch_apply_opt<GA_MODE_SA | kNesterov>(st, snap, g, grad_dtype, N, c, keep_m, write_snap, stream);
+        case GA_MODE_ASGD | kNesterov:
+            return launch_apply_opt<GA_MODE_ASGD | kNesterov>(st, snap, g, grad_dtype, N, c, keep_m, write_snap, stream);
+        default:
+            return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace ga

@@ -1,0 +1,224 @@
+// libga, gfx950: the gradient source alone (quadratic_gradient_kernel, noise_fill_kernel,
+// box_muller_raw_kernel), Gap statistics (diag_kernel + diag_final_kernel, App. C.8) and fills.
+
+#include "ga_device.h"
+
+namespace ga {
+namespace {
+
+__global__ __launch_bounds__(kBlock) void noise_fill_kernel(uint32_t seed_lo, uint32_t seed_hi, uint64_t k,
+                                                            uint64_t j0, uint64_t n, float* __restrict__ out) {
+    const uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (i >= n) return;
+    const uint64_t j = j0 + i;
+    const f32x4 z = noise4(seed_lo, seed_hi, j >> 2, k);
+    const uint32_t lane = (uint32_t)(j & 3);
+    out[i] = lane == 0 ? z.x : lane == 1 ? z.y : lane == 2 ? z.z : z.w;
+}
+
+__global__ __launch_bounds__(kBlock) void box_muller_raw_kernel(const uint32_t* __restrict__ xa,
+                                                                const uint32_t* __restrict__ xb, uint64_t n,
+                                                                float* __restrict__ zc, float* __restrict__ zs) {
+    const uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (i >= n) return;
+    float c, s;
+    box_muller_pair(xa[i], xb[i], c, s);
+    zc[i] = c;
+    zs[i] = s;
+}
+
+__global__ __launch_bounds__(kBlock) void quadratic_gradient_kernel(const float* __restrict__ snap,
+                                                                    const float* __restrict__ a,
+                                                                    const float* __restrict__ ts, uint64_t N,
+                                                                    uint64_t k, RunConst rc,
+                                                                    float* __restrict__ g_out) {
+    const uint64_t q = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+    const uint64_t j0 = 4 * q;
+    if (j0 >= N) return;
+    const f32x4 z = noise4(rc.seed_lo, rc.seed_hi, q, k);
+    if (j0 + 3 < N) {
+        const f32x4 s = reinterpret_cast<const f32x4*>(snap)[q];
+        const f32x4 a4 = reinterpret_cast<const f32x4*>(a)[q];
+        const f32x4 t4 = reinterpret_cast<const f32x4*>(ts)[q];
+        f32x4 g;
+        g.x = quadratic_g(s.x, a4.x, t4.x, rc.sigma, z.x);
+        g.y = quadratic_g(s.y, a4.y, t4.y, rc.sigma, z.y);
+        g.z = quadratic_g(s.z, a4.z, t4.z, rc.sigma, z.z);
+        g.w = quadratic_g(s.w, a4.w, t4.w, rc.sigma, z.w);
+        reinterpret_cast<f32x4*>(g_out)[q] = g;
+    } else {
+        const float zz[4] = {z.x, z.y, z.z, z.w};
+        for (int e = 0; e < 4 && j0 + e < N; ++e)
+            g_out[j0 + e] = quadratic_g(snap[j0 + e], a[j0 + e], ts[j0 + e], rc.sigma, zz[e]);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Gap statistics: per-thread accumulation, wavefront (64 lanes) butterfly,
+// one partial per block, then a single block adds the partials in a fixed
+// order so that the result does not depend on scheduling.
+// ---------------------------------------------------------------------------
+struct DiagAcc {
+    double sum;
+    uint32_t gt1, gt0, bad;
+};
+
+__device__ __forceinline__ void diag_one(DiagAcc& acc, float th, float s, float m, float inv_bc, float eta_max,
+                                         float eps) {
+    const float diff = th - s;
+    const float delta = fabsf(diff);
+    const float mhat = m * inv_bc;
+    const float root = sqrtf(mhat);
+    const float sum = root + eps;
+    const float C = eta_max * sum;
+    const float graw = delta / C;
+    if (!isfinite(graw)) {
+        acc.bad += 1;
+    } else {
+        acc.sum += (double)graw;
+        acc.gt1 += (graw > 1.0f);
+        acc.gt0 += (graw > 0.0f);
+    }
+}
+
+__device__ __forceinline__ DiagPartial block_reduce(double sum, unsigned long long gt1, unsigned long long gt0,
+                                                    unsigned long long bad) {
+    __shared__ DiagPartial wave_part[kBlock / 64];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        sum += __shfl_xor(sum, off, 64);
+        gt1 += __shfl_xor(gt1, off, 64);
+        gt0 += __shfl_xor(gt0, off, 64);
+        bad += __shfl_xor(bad, off, 64);
+    }
+    const int wave = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0) {
+        wave_part[wave].sum_graw = sum;
+        wave_part[wave].n_gt1 = gt1;
+        wave_part[wave].n_gt0 = gt0;
+        wave_part[wave].n_bad = bad;
+    }
+    __syncthreads();
+    DiagPartial r = wave_part[0];
+#pragma unroll
+    for (int w = 1; w < kBlock / 64; ++w) {
+        r.sum_graw += wave_part[w].sum_graw;
+        r.n_gt1 += wave_part[w].n_gt1;
+        r.n_gt0 += wave_part[w].n_gt0;
+        r.n_bad += wave_part[w].n_bad;
+    }
+    return r;
+}
+
+__global__ __launch_bounds__(kBlock) void diag_kernel(const float* __restrict__ theta, const float* __restrict__ m,
+                                                      const float* __restrict__ snap, uint64_t N, float inv_bc,
+                                                      float eta_max, float eps,
+                                                      DiagPartial* __restrict__ partials) {
+    const uint64_t n4 = N >> 2;
+    DiagAcc acc = {0.0, 0u, 0u, 0u};
+    for (uint64_t q = (uint64_t)blockIdx.x * kBlock + threadIdx.x; q < n4; q += (uint64_t)gridDim.x * kBlock) {
+        const f32x4 th = reinterpret_cast<const f32x4*>(theta)[q];
+        const f32x4 s = reinterpret_cast<const f32x4*>(snap)[q];
+        const f32x4 mm = reinterpret_cast<const f32x4*>(m)[q];
+        diag_one(acc, th.x, s.x, mm.x, inv_bc, eta_max, eps);
+        diag_one(acc, th.y, s.y, mm.y, inv_bc, eta_max, eps);
+        diag_one(acc, th.z, s.z, mm.z, inv_bc, eta_max, eps);
+        diag_one(acc, th.w, s.w, mm.w, inv_bc, eta_max, eps);
+    }
+    if (blockIdx.x == 0 && threadIdx.x < (N & 3)) {
+        const uint64_t j = 4 * n4 + threadIdx.x;
+        diag_one(acc, theta[j], snap[j], m[j], inv_bc, eta_max, eps);
+    }
+    const DiagPartial r = block_reduce(acc.sum, acc.gt1, acc.gt0, acc.bad);
+    if (threadIdx.x == 0) partials[blockIdx.x] = r;
+}
+
+__global__ __launch_bounds__(kBlock) void diag_final_kernel(const DiagPartial* __restrict__ partials,
+                                                            uint32_t n_partials, DiagPartial* __restrict__ total) {
+    double sum = 0.0;
+    unsigned long long gt1 = 0, gt0 = 0, bad = 0;
+    for (uint32_t i = threadIdx.x; i < n_partials; i += kBlock) {
+        sum += partials[i].sum_graw;
+        gt1 += partials[i].n_gt1;
+        gt0 += partials[i].n_gt0;
+        bad += partials[i].n_bad;
+    }
+    const DiagPartial r = block_reduce(sum, gt1, gt0, bad);
+    if (threadIdx.x == 0) *total = r;
+}
+
+// ---------------------------------------------------------------------------
+// Fills.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kBlock) void fill_kernel(float* __restrict__ dst, uint64_t n, float value) {
+    for (uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += (uint64_t)gridDim.x * kBlock)
+        dst[i] = value;
+}
+
+__global__ __launch_bounds__(kBlock) void broadcast_rows_kernel(float* __restrict__ dst, uint64_t stride,
+                                                                uint32_t rows, const float* __restrict__ src,
+                                                                uint64_t n) {
+    for (uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += (uint64_t)gridDim.x * kBlock) {
+        const float x = src[i];
+        for (uint32_t r = 0; r < rows; ++r) dst[(uint64_t)r * stride + i] = x;
+    }
+}
+
+}  // namespace
+
+hipError_t launch_quadratic_gradient(const StatePtrs& st, uint64_t N, uint32_t worker, const float* a,
+                                     const float* theta_star, uint64_t k, const RunConst& rc, float* g_out,
+                                     hipStream_t stream) {
+    const uint64_t groups = (N + 3) >> 2;
+    const uint64_t blocks = (groups + kBlock - 1) / kBlock;
+    if (blocks == 0 || blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(quadratic_gradient_kernel, dim3((uint32_t)blocks), dim3(kBlock), 0, stream,
+                       st.snaps + (uint64_t)worker * st.stride, a, theta_star, N, k, rc, g_out);
+    return hipGetLastError();
+}
+
+hipError_t launch_diagnostics(const StatePtrs& st, uint64_t N, uint32_t worker, float inv_bc, float eta_max,
+                              float eps, DiagPartial* dev_partials, hipStream_t stream) {
+    const uint32_t grid = blocks_for(N >> 2, (uint64_t)kBlock * 4, kDiagMaxBlocks);
+    hipLaunchKernelGGL(diag_kernel, dim3(grid), dim3(kBlock), 0, stream, st.theta, st.m,
+                       st.snaps + (uint64_t)worker * st.stride, N, inv_bc, eta_max, eps, dev_partials);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(diag_final_kernel, dim3(1), dim3(kBlock), 0, stream, dev_partials, grid,
+                       dev_partials + kDiagMaxBlocks);
+    return hipGetLastError();
+}
+
+hipError_t launch_box_muller_raw(const uint32_t* xa, const uint32_t* xb, uint64_t n, float* zc, float* zs,
+                                 hipStream_t stream) {
+    if (n == 0) return hipSuccess;
+    const uint64_t blocks = (n + kBlock - 1) / kBlock;
+    if (blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(box_muller_raw_kernel, dim3((uint32_t)blocks), dim3(kBlock), 0, stream, xa, xb, n, zc, zs);
+    return hipGetLastError();
+}
+
+hipError_t launch_noise_fill(uint64_t seed, uint64_t k, uint64_t j0, uint64_t n, float* out, hipStream_t stream) {
+    if (n == 0) return hipSuccess;
+    const uint64_t blocks = (n + kBlock - 1) / kBlock;
+    if (blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(noise_fill_kernel, dim3((uint32_t)blocks), dim3(kBlock), 0, stream, (uint32_t)seed,
+                       (uint32_t)(seed >> 32), k, j0, n, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_fill(float* dst, uint64_t n, float value, hipStream_t stream) {
+    if (n == 0) return hipSuccess;
+    hipLaunchKernelGGL(fill_kernel, dim3(blocks_for(n, kBlock * 8, 65536)), dim3(kBlock), 0, stream, dst, n, value);
+    return hipGetLastError();
+}
+
+hipError_t launch_broadcast_rows(float* dst, uint64_t stride, uint32_t rows, const float* src, uint64_t n,
+                                 hipStream_t stream) {
+    if (n == 0 || rows == 0) return hipSuccess;
+    hipLaunchKernelGGL(broadcast_rows_kernel, dim3(blocks_for(n, kBlock * 4, 65536)), dim3(kBlock), 0, stream, dst,
+                       stride, rows, src, n);
+    return hipGetLastError();
+}
+
+}  // namespace ga

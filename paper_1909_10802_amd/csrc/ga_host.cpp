@@ -1,7 +1,7 @@
 // Host side of libga: the C ABI of include/ga.h, the integer bookkeeping of
 // the master (step counter, iter[], delays: Alg. 3 / Alg. 5), the per-arrival
 // scalars (step size, Alg. 14 bias correction) and the arrival-schedule
-// simulator.  Device work is delegated to the launchers in ga_kernels.hip.
+// simulator.  Device work is delegated to the launchers in the .hip files.
 
 #include <hip/hip_runtime_api.h>
 

@@ -1,5 +1,5 @@
 // Internal interface between the host bookkeeping (ga_host.cpp) and the
-// gfx950 kernels (ga_kernels.hip).  Not part of the public ABI.
+// gfx950 kernels (ga_apply.hip, ga_persistent.hip, ga_layerwise.hip, ga_aux.hip).  Not part of the public ABI.
 #ifndef GA_INTERNAL_H
 #define GA_INTERNAL_H
 

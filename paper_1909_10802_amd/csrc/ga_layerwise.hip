@@ -1,0 +1,232 @@
+// libga, gfx950: layer-wise and global Gap (Eq. 4, Def. 1): reduce, per-layer Gap, update.
+
+#include "ga_device.h"
+
+namespace ga {
+namespace {
+
+// ---------------------------------------------------------------------------
+// Layer-wise and global Gap (Eq. 4, Def. 1).  Three launches per arrival:
+//   layer_partial_kernel   one block per chunk of a layer: sum (theta-snap)^2 and sum m in double
+//   layer_gap_kernel       one block per layer adds its chunk partials in a fixed order and forms G_p
+//   layer_apply_kernel     one block per chunk: the momentum update with ghat = g / G_p
+// A chunk never crosses a layer boundary; boundaries are arbitrary, so a chunk has a scalar
+// head and tail around its 16-byte aligned body.  Every sum has a fixed order.
+// ---------------------------------------------------------------------------
+constexpr int kLayerU = 4;   // 128-bit groups in flight per thread in the chunk kernels
+
+struct ChunkRange {
+    uint64_t start, end;   // parameters [start, end)
+    uint64_t a0, a1;       // aligned body [a0, a1), multiples of 4
+};
+
+__device__ __forceinline__ ChunkRange chunk_range(const LayerChunk& ch) {
+    ChunkRange r;
+    r.start = ch.start;
+    r.end = ch.start + ch.len;
+    r.a0 = (r.start + 3) & ~(uint64_t)3;
+    if (r.a0 > r.end) r.a0 = r.end;
+    r.a1 = r.end & ~(uint64_t)3;
+    if (r.a1 < r.a0) r.a1 = r.a0;
+    return r;
+}
+
+__global__ __launch_bounds__(kBlock) void layer_partial_kernel(const float* __restrict__ theta,
+                                                               const float* __restrict__ m,
+                                                               const float* __restrict__ snap,
+                                                               const LayerChunk* __restrict__ chunks,
+                                                               LayerPartial* __restrict__ partials) {
+    const ChunkRange r = chunk_range(chunks[blockIdx.x]);
+    double d2 = 0.0, ms = 0.0;
+    auto one = [&](float th, float s, float mm) {
+        const float diff = th - s;
+        d2 += (double)diff * (double)diff;
+        ms += (double)mm;
+    };
+    for (uint64_t j = r.start + threadIdx.x; j < r.a0; j += kBlock) one(theta[j], snap[j], m[j]);
+    const uint64_t q_end = r.a1 >> 2;
+    for (uint64_t q0 = (r.a0 >> 2) + threadIdx.x; q0 < q_end; q0 += (uint64_t)kLayerU * kBlock) {
+        f32x4 th[kLayerU], sv[kLayerU], mm[kLayerU];
+#pragma unroll
+        for (int u = 0; u < kLayerU; ++u) {
+            const uint64_t q = q0 + (uint64_t)u * kBlock;
+            if (q < q_end) {
+                th[u] = load4<false>(theta, q);
+                sv[u] = load4<true>(snap, q);
+                mm[u] = load4<true>(m, q);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kLayerU; ++u) {
+            if (q0 + (uint64_t)u * kBlock < q_end) {
+                one(th[u].x, sv[u].x, mm[u].x); one(th[u].y, sv[u].y, mm[u].y);
+                one(th[u].z, sv[u].z, mm[u].z); one(th[u].w, sv[u].w, mm[u].w);
+            }
+        }
+    }
+    for (uint64_t j = r.a1 + threadIdx.x; j < r.end; j += kBlock) one(theta[j], snap[j], m[j]);
+
+    __shared__ double part[2][kBlock / 64];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        d2 += __shfl_xor(d2, off, 64);
+        ms += __shfl_xor(ms, off, 64);
+    }
+    if ((threadIdx.x & 63) == 0) {
+        part[0][threadIdx.x >> 6] = d2;
+        part[1][threadIdx.x >> 6] = ms;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        LayerPartial out = {part[0][0], part[1][0]};
+#pragma unroll
+        for (int w = 1; w < kBlock / 64; ++w) {
+            out.dist2 += part[0][w];
+            out.msum += part[1][w];
+        }
+        partials[blockIdx.x] = out;
+    }
+}
+
+template <bool HINGE>
+__global__ __launch_bounds__(kBlock) void layer_gap_kernel(const LayerPartial* __restrict__ partials,
+                                                           const LayerSpan* __restrict__ spans, float inv_bc_prev,
+                                                           float eta_max, float eps, float* __restrict__ gaps) {
+    // one block per layer: strided partial sums, 64-lane butterfly, then the waves in order
+    const LayerSpan sp = spans[blockIdx.x];
+    double d2 = 0.0, ms = 0.0;
+    for (uint32_t i = threadIdx.x; i < sp.n_chunks; i += kBlock) {
+        d2 += partials[sp.first_chunk + i].dist2;
+        ms += partials[sp.first_chunk + i].msum;
+    }
+    __shared__ double part[2][kBlock / 64];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        d2 += __shfl_xor(d2, off, 64);
+        ms += __shfl_xor(ms, off, 64);
+    }
+    if ((threadIdx.x & 63) == 0) {
+        part[0][threadIdx.x >> 6] = d2;
+        part[1][threadIdx.x >> 6] = ms;
+    }
+    __syncthreads();
+    if (threadIdx.x != 0) return;
+    d2 = part[0][0];
+    ms = part[1][0];
+#pragma unroll
+    for (int w = 1; w < kBlock / 64; ++w) {
+        d2 += part[0][w];
+        ms += part[1][w];
+    }
+    const float delta = (float)sqrt(d2);
+    const float mhat = (float)ms * inv_bc_prev;
+    const float root = sqrtf(mhat);
+    const float sum = root + eps;
+    const float C = eta_max * sum;
+    const float graw = delta / C;
+    gaps[blockIdx.x] = HINGE ? fmaxf(1.0f, graw) : 1.0f + graw;
+}
+
+template <bool NAG>
+__device__ __forceinline__ void layer_update_one(float& th, float& v, float& m, float g, float G, const StepConst& c) {
+    const float ghat = g / G;
+    const float gv = c.gamma * v;
+    const float vn = gv + ghat;
+    float dir = vn;
+    if constexpr (NAG) {
+        const float look = c.gamma * vn;
+        dir = ghat + look;
+    }
+    const float step = c.lr * dir;
+    th = th - step;
+    v = vn;
+    m = second_moment(m, dir, c);
+}
+
+template <int DT, bool ALIGNED, bool STREAM_V, bool NAG>
+__global__ __launch_bounds__(kBlock) void layer_apply_kernel(float* __restrict__ theta, float* __restrict__ v,
+                                                             float* __restrict__ m, float* __restrict__ snap,
+                                                             const void* __restrict__ g,
+                                                             const LayerChunk* __restrict__ chunks,
+                                                             const float* __restrict__ gaps, StepConst c) {
+    const LayerChunk ch = chunks[blockIdx.x];
+    const ChunkRange r = chunk_range(ch);
+    const float G = gaps[ch.layer];
+    auto scalar = [&](uint64_t j) {
+        float t1 = theta[j], v1 = v[j], m1 = m[j];
+        layer_update_one<NAG>(t1, v1, m1, load_g1<DT>(g, j), G, c);
+        theta[j] = t1; v[j] = v1; m[j] = m1; snap[j] = t1;
+    };
+    for (uint64_t j = r.start + threadIdx.x; j < r.a0; j += kBlock) scalar(j);
+    constexpr int U = 2;
+    const uint64_t q_end = r.a1 >> 2;
+    for (uint64_t q0 = (r.a0 >> 2) + threadIdx.x; q0 < q_end; q0 += (uint64_t)U * kBlock) {
+        f32x4 th[U], vv[U], mm[U], gg[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint64_t q = q0 + (uint64_t)u * kBlock;
+            if (q < q_end) {
+                th[u] = load4<false>(theta, q);
+                vv[u] = load4<STREAM_V>(v, q);
+                mm[u] = load4<true>(m, q);
+                gg[u] = load_g4<DT, ALIGNED>(g, q);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint64_t q = q0 + (uint64_t)u * kBlock;
+            if (q < q_end) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    float t1 = th[u][e], v1 = vv[u][e], m1 = mm[u][e];
+                    layer_update_one<NAG>(t1, v1, m1, gg[u][e], G, c);
+                    th[u][e] = t1; vv[u][e] = v1; mm[u][e] = m1;
+                }
+                store4<false>(theta, q, th[u]);
+                store4<STREAM_V>(v, q, vv[u]);
+                store4<true>(m, q, mm[u]);
+                store4<true>(snap, q, th[u]);
+            }
+        }
+    }
+    for (uint64_t j = r.a1 + threadIdx.x; j < r.end; j += kBlock) scalar(j);
+}
+
+}  // namespace
+
+hipError_t launch_apply_layerwise(const StatePtrs& st, uint64_t N, uint32_t worker, const void* g, int grad_dtype,
+                                  int mode, bool nesterov, const LayerTables& lt, const StepConst& c,
+                                  hipStream_t stream) {
+    if (lt.n_chunks == 0 || lt.n_layers == 0) return hipErrorInvalidValue;
+    float* snap = st.snaps + (uint64_t)worker * st.stride;
+    const dim3 block(kBlock), grid(lt.n_chunks), lgrid(lt.n_layers);
+    hipLaunchKernelGGL(layer_partial_kernel, grid, block, 0, stream, st.theta, st.m, snap, lt.chunks, lt.partials);
+    if (mode == GA_MODE_GA_HINGE)
+        hipLaunchKernelGGL(layer_gap_kernel<true>, lgrid, block, 0, stream, lt.partials, lt.spans, c.inv_bc_prev,
+                           c.eta_max, c.eps, lt.gaps);
+    else
+        hipLaunchKernelGGL(layer_gap_kernel<false>, lgrid, block, 0, stream, lt.partials, lt.spans, c.inv_bc_prev,
+                           c.eta_max, c.eps, lt.gaps);
+    const uintptr_t addr = reinterpret_cast<uintptr_t>(g);
+    const bool stream_v = N > kKeepVMaxN;
+#define GA_LAYER_APPLY(DT, AL, SV)                                                                                  \
+    do {                                                                                                            \
+        if (nesterov)                                                                                               \
+            hipLaunchKernelGGL((layer_apply_kernel<DT, AL, SV, true>), grid, block, 0, stream, st.theta, st.v, st.m, \
+                               snap, g, lt.chunks, lt.gaps, c);                                                     \
+        else                                                                                                        \
+            hipLaunchKernelGGL((layer_apply_kernel<DT, AL, SV, false>), grid, block, 0, stream, st.theta, st.v,     \
+                               st.m, snap, g, lt.chunks, lt.gaps, c);                                               \
+    } while (0)
+    if (grad_dtype == GA_F32) {
+        if ((addr & 15u) == 0) { if (stream_v) GA_LAYER_APPLY(GA_F32, true, true); else GA_LAYER_APPLY(GA_F32, true, false); }
+        else { if (stream_v) GA_LAYER_APPLY(GA_F32, false, true); else GA_LAYER_APPLY(GA_F32, false, false); }
+    } else {
+        if ((addr & 7u) == 0) { if (stream_v) GA_LAYER_APPLY(GA_BF16, true, true); else GA_LAYER_APPLY(GA_BF16, true, false); }
+        else { if (stream_v) GA_LAYER_APPLY(GA_BF16, false, true); else GA_LAYER_APPLY(GA_BF16, false, false); }
+    }
+#undef GA_LAYER_APPLY
+    return hipGetLastError();
+}
+
+}  // namespace ga
