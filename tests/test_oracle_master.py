@@ -352,3 +352,30 @@ def test_bf16_widening():
     assert np.all(np.abs(w - x) <= np.abs(x) * 2.0 ** -8)
     assert np.array_equal(ga_inputs.f32_to_bf16_bits(w), b)        # widening is exact
     assert oracle.bf16_to_f32(np.array([0x3F80, 0xC000, 0x0000], np.uint16)).tolist() == [1.0, -2.0, 0.0]
+
+
+# ---------------------------------------------------------------- behaviour the paper reports
+def test_gap_stays_below_delay_and_penalties_stabilise_momentum():
+    # Sec. 4.3 / App. C.8: measured over a run, the mean parameter-wise Gap stays well below the
+    # mean delay.  Sec. 2 / 5: with momentum and several workers plain ASGD blows up at a step size
+    # where the penalised masters keep descending.  Checked on the synthetic quadratic, W = 8.
+    N, W, T, chunk = 4096, 8, 1600, 40
+    a, ts = quad_inputs(N, 1, np.float32)
+    sched = oracle.simulate_schedule(W, T + 1, seed=1)
+    f = lambda th: 0.5 * float(np.sum(a.astype(np.float64) * (th.astype(np.float64) - ts) ** 2))
+    f0 = f(np.zeros(N, np.float32))
+    loss = {}
+    for mode in (MODE_ASGD, MODE_SA, MODE_GA):
+        M = Master(N, W, mode, Hyper(), np.float32)
+        gaps, taus = [], []
+        with np.errstate(all="ignore"):
+            for s in range(0, T, chunk):
+                taus.append(M.run_quadratic(sched[s:s + chunk], a, ts, seed=1))
+                gaps.append(1.0 + M.gap_statistics(int(sched[s + chunk]))["mean_graw"])
+        loss[mode] = f(M.theta)
+        if mode == MODE_GA:
+            mean_tau = float(np.concatenate(taus)[W:].mean())
+            assert abs(mean_tau - W) < 0.05                       # steady state: tau averages W
+            assert 1.0 < np.mean(gaps) < 0.5 * mean_tau, (np.mean(gaps), mean_tau)
+    assert not loss[MODE_ASGD] < f0                               # diverged (or overflowed)
+    assert loss[MODE_SA] < 1e-2 * f0 and loss[MODE_GA] < 1e-2 * f0, loss
