@@ -150,8 +150,10 @@ def bench_fused(args, cfg, torch, ga, ga_inputs):
     if args.family != "momentum":
         bpu += 8                                                    # one more state array read and written
     if args.gap_scope != "parameter":
-        bpu += 8                                                    # reduction pass re-reads theta, snapshot, m (12 B),
-                                                                    # the update pass no longer reads the snapshot (-4 B)
+        # inside one run_schedule call the update pass reads the next worker's snapshot instead of this
+        # worker's and prepares the next norms: 36 B as for the parameter-wise Gap; only the first arrival
+        # of a call needs the separate reduction pass over theta, snapshot and m (12 B)
+        bpu += 12.0 * len(events) / K
     achieved = bpu * N / (kernel_ms * 1e-3) / 1e9
     theta = M.theta()
     finite = bool(torch.isfinite(theta).all().item())
@@ -164,9 +166,9 @@ def bench_fused(args, cfg, torch, ga, ga_inputs):
     traffic = t["bytes"] if t and t["kernels_sha256"] == kernels_hash() and args.gap_scope == "parameter" else None
     roof = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
             "traffic": traffic if args.family == "momentum" else None,
-            "kernel": ("layer_partial_kernel + layer_gap_kernel + layer_apply_kernel" if args.gap_scope != "parameter"
+            "kernel": ("layer_gap_kernel + layer_apply_kernel (+ layer_partial_kernel on the first arrival of a call)" if args.gap_scope != "parameter"
                        else "apply_kernel" if args.family == "momentum" else "family_apply_kernel"), "bytes_per_update": bpu, "avg_launch_ms": kernel_ms,
-            "algorithmic_bytes_per_launch": bpu * N}
+            "algorithmic_bytes_per_launch": int(round(bpu * N))}
     desc = ("%s: N=%d float parameters, %d workers, %s iteration times, %d %s gradient buffers picked by %s, one "
             "fused-update launch per arrival, family %s, mode %s" % (args.workload, N, W, cfg["dist"], cfg["n_bufs"],
                                                                      cfg["grad_dtype"], cfg["pick"], args.family,

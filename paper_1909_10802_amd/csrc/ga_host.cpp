@@ -40,6 +40,10 @@ struct ga_ctx {
     hipEvent_t staged = nullptr;
     bool staged_pending = false;
     int gap_scope = GA_GAP_PARAMETER;
+    // layer-wise / global Gap: the chunk sums on the device are those of the next arrival of this worker
+    // (valid only between two arrivals of one ga_run_schedule call)
+    bool layer_sums_ready = false;
+    uint32_t layer_sums_worker = 0;
     ga::LayerTables layers{};
     std::vector<ga::LayerChunk> host_chunks;   // uploaded at create; kept for the lifetime of the context
     std::vector<ga::LayerSpan> host_spans;
@@ -326,15 +330,25 @@ int check_quadratic_source(ga_ctx* ctx, const ga_grad_source* src) {
 }
 
 // One arrival through the fused kernel; the bookkeeping is committed only if the launch succeeded.
-int apply_one(ga_ctx* ctx, uint32_t worker, const void* dev_grad, int dtype, bool write_snap, float eta_k) {
+// next_worker (layer-wise and global Gap only): the worker of the arrival that follows in the same
+// schedule, or -1; the update pass then prepares that arrival's norms (see launch_apply_layerwise).
+int apply_one(ga_ctx* ctx, uint32_t worker, const void* dev_grad, int dtype, bool write_snap, float eta_k,
+              int64_t next_worker = -1) {
     const uint64_t k = ctx->k + 1;
     const uint64_t tau = k - ctx->iter[worker];
     const ga_arrival row = make_row(worker, k, tau, ctx->mode, eta_k, ctx->beta);
     const ga::StepConst sc = step_const(ctx, row, k);
     hipError_t e;
-    if (ctx->gap_scope != GA_GAP_PARAMETER)
-        e = ga::launch_apply_layerwise(ctx->st, ctx->N, worker, dev_grad, dtype, ctx->mode, ctx->nesterov, ctx->layers, sc, ctx->stream);
-    else if (ctx->family == GA_FAMILY_DANA)
+    if (ctx->gap_scope != GA_GAP_PARAMETER) {
+        const bool ready = ctx->layer_sums_ready && ctx->layer_sums_worker == worker;
+        ctx->layer_sums_ready = false;
+        e = ga::launch_apply_layerwise(ctx->st, ctx->N, worker, dev_grad, dtype, ctx->mode, ctx->nesterov, ctx->layers, sc,
+                                       ready, next_worker, ctx->stream);
+        if (e == hipSuccess && next_worker >= 0) {
+            ctx->layer_sums_ready = true;
+            ctx->layer_sums_worker = (uint32_t)next_worker;
+        }
+    } else if (ctx->family == GA_FAMILY_DANA)
         e = ga::launch_apply_dana(ctx->st, ctx->N, worker, dev_grad, dtype, ctx->mode, keeps_m(ctx), write_snap, sc, ctx->stream);
     else if (ctx->family == GA_FAMILY_ADAM)
         e = ga::launch_apply_adam(ctx->st, ctx->N, worker, dev_grad, dtype, ctx->mode, keeps_m(ctx), write_snap, sc, ctx->stream);
@@ -678,9 +692,19 @@ int ga_run_schedule(ga_ctx* ctx, const uint32_t* host_schedule, uint64_t T, cons
     return ga_run_schedule_lr(ctx, host_schedule, T, src, nullptr);
 }
 
+static int run_schedule_checked(ga_ctx* ctx, const uint32_t* host_schedule, uint64_t T, const ga_grad_source* src,
+                                const float* host_eta);
+
 int ga_run_schedule_lr(ga_ctx* ctx, const uint32_t* host_schedule, uint64_t T, const ga_grad_source* src,
                        const float* host_eta) {
     if (!ctx) return GA_ERR_ARG;
+    const int rc = run_schedule_checked(ctx, host_schedule, T, src, host_eta);
+    ctx->layer_sums_ready = false;   // nothing prepared on the device outlives the call
+    return rc;
+}
+
+static int run_schedule_checked(ga_ctx* ctx, const uint32_t* host_schedule, uint64_t T, const ga_grad_source* src,
+                                const float* host_eta) {
     if (!src || (T > 0 && !host_schedule)) return fail(ctx, GA_ERR_ARG, "run_schedule: null argument");
     if (host_eta)
         for (uint64_t a = 0; a < T; ++a)
@@ -702,7 +726,8 @@ int ga_run_schedule_lr(ga_ctx* ctx, const uint32_t* host_schedule, uint64_t T, c
         for (uint64_t a = 0; a < T; ++a) {
             const uint32_t w = host_schedule[a];
             const uint64_t b = (src->pick == GA_PICK_BY_WORKER) ? w % src->n_bufs : ctx->k % src->n_bufs;
-            const int rc = apply_one(ctx, w, src->host_dev_bufs[b], src->dtype, write_snap, host_eta ? host_eta[a] : ctx->lr);
+            const int64_t next = (a + 1 < T) ? (int64_t)host_schedule[a + 1] : -1;
+            const int rc = apply_one(ctx, w, src->host_dev_bufs[b], src->dtype, write_snap, host_eta ? host_eta[a] : ctx->lr, next);
             if (rc != GA_OK) return rc;
         }
         return GA_OK;
@@ -726,7 +751,8 @@ int ga_run_schedule_lr(ga_ctx* ctx, const uint32_t* host_schedule, uint64_t T, c
             const hipError_t e = ga::launch_quadratic_gradient(ctx->st, ctx->N, w, src->dev_a, src->dev_theta_star,
                                                                ctx->k + 1, rcst, src->dev_scratch_g, ctx->stream);
             if (e != hipSuccess) return hip_fail(ctx, e, "gradient launch");
-            rc = apply_one(ctx, w, src->dev_scratch_g, GA_F32, true, host_eta ? host_eta[a] : ctx->lr);
+            const int64_t next = (a + 1 < T) ? (int64_t)host_schedule[a + 1] : -1;
+            rc = apply_one(ctx, w, src->dev_scratch_g, GA_F32, true, host_eta ? host_eta[a] : ctx->lr, next);
             if (rc != GA_OK) return rc;
         }
         return GA_OK;

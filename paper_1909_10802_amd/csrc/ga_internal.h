@@ -94,9 +94,12 @@ hipError_t launch_apply_adam(const StatePtrs& st, uint64_t N, uint32_t worker, c
                              bool keep_m, bool write_snap, const StepConst& c, hipStream_t stream);
 
 // Layer-wise / global Gap arrival: per-chunk reduction, per-layer Gap, update with one Gap per layer.
+// sums_ready: lt.partials already hold this arrival's chunk sums (left by the previous call), so the
+// reduction pass is skipped.  next_worker >= 0: the update pass also leaves the chunk sums of the
+// arrival that follows, which must be that worker's, with no change to the state in between.
 hipError_t launch_apply_layerwise(const StatePtrs& st, uint64_t N, uint32_t worker, const void* g, int grad_dtype,
                                   int mode, bool nesterov, const LayerTables& lt, const StepConst& c,
-                                  hipStream_t stream);
+                                  bool sums_ready, int64_t next_worker, hipStream_t stream);
 
 // T arrivals replayed inside one launch, gradients generated in the kernel.
 // table: device array of T rows; k0: master step before the first row.

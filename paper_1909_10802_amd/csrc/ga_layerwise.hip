@@ -12,8 +12,44 @@ namespace {
 //   layer_apply_kernel     one block per chunk: the momentum update with ghat = g / G_p
 // A chunk never crosses a layer boundary; boundaries are arbitrary, so a chunk has a scalar
 // head and tail around its 16-byte aligned body.  Every sum has a fixed order.
+//
+// When the caller already knows which worker arrives next, layer_apply_kernel<LOOK = true> also
+// forms that arrival's chunk sums from the values it holds (the new theta and m) and the next
+// worker's snapshot, so the separate reduction pass is not launched for it.  Both kernels give a
+// thread the same elements in the same order and reduce the block the same way: the sums are
+// the same bits either way.
 // ---------------------------------------------------------------------------
 constexpr int kLayerU = 4;   // 128-bit groups in flight per thread in the chunk kernels
+
+__device__ __forceinline__ void gap_terms(double& d2, double& ms, float th, float s, float mm) {
+    const float diff = th - s;
+    d2 += (double)diff * (double)diff;
+    ms += (double)mm;
+}
+
+// Wave butterfly, then the waves of the block in order; thread 0 stores the chunk's sums.
+__device__ __forceinline__ void store_chunk_partial(double d2, double ms, LayerPartial* __restrict__ out) {
+    __shared__ double part[2][kBlock / 64];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        d2 += __shfl_xor(d2, off, 64);
+        ms += __shfl_xor(ms, off, 64);
+    }
+    if ((threadIdx.x & 63) == 0) {
+        part[0][threadIdx.x >> 6] = d2;
+        part[1][threadIdx.x >> 6] = ms;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        LayerPartial p = {part[0][0], part[1][0]};
+#pragma unroll
+        for (int w = 1; w < kBlock / 64; ++w) {
+            p.dist2 += part[0][w];
+            p.msum += part[1][w];
+        }
+        *out = p;
+    }
+}
 
 struct ChunkRange {
     uint64_t start, end;   // parameters [start, end)
@@ -38,11 +74,7 @@ __global__ __launch_bounds__(kBlock) void layer_partial_kernel(const float* __re
                                                                LayerPartial* __restrict__ partials) {
     const ChunkRange r = chunk_range(chunks[blockIdx.x]);
     double d2 = 0.0, ms = 0.0;
-    auto one = [&](float th, float s, float mm) {
-        const float diff = th - s;
-        d2 += (double)diff * (double)diff;
-        ms += (double)mm;
-    };
+    auto one = [&](float th, float s, float mm) { gap_terms(d2, ms, th, s, mm); };
     for (uint64_t j = r.start + threadIdx.x; j < r.a0; j += kBlock) one(theta[j], snap[j], m[j]);
     const uint64_t q_end = r.a1 >> 2;
     for (uint64_t q0 = (r.a0 >> 2) + threadIdx.x; q0 < q_end; q0 += (uint64_t)kLayerU * kBlock) {
@@ -65,27 +97,7 @@ __global__ __launch_bounds__(kBlock) void layer_partial_kernel(const float* __re
         }
     }
     for (uint64_t j = r.a1 + threadIdx.x; j < r.end; j += kBlock) one(theta[j], snap[j], m[j]);
-
-    __shared__ double part[2][kBlock / 64];
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) {
-        d2 += __shfl_xor(d2, off, 64);
-        ms += __shfl_xor(ms, off, 64);
-    }
-    if ((threadIdx.x & 63) == 0) {
-        part[0][threadIdx.x >> 6] = d2;
-        part[1][threadIdx.x >> 6] = ms;
-    }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        LayerPartial out = {part[0][0], part[1][0]};
-#pragma unroll
-        for (int w = 1; w < kBlock / 64; ++w) {
-            out.dist2 += part[0][w];
-            out.msum += part[1][w];
-        }
-        partials[blockIdx.x] = out;
-    }
+    store_chunk_partial(d2, ms, partials + blockIdx.x);
 }
 
 template <bool HINGE>
@@ -143,25 +155,32 @@ __device__ __forceinline__ void layer_update_one(float& th, float& v, float& m, 
     m = second_moment(m, dir, c);
 }
 
-template <int DT, bool ALIGNED, bool STREAM_V, bool NAG>
+// LOOK: also leave the chunk sums of the arrival that follows.  next_snap is the next worker's
+// snapshot, or null when the same worker arrives again (its snapshot is the theta written here:
+// the distance is zero).
+template <int DT, bool ALIGNED, bool STREAM_V, bool NAG, bool LOOK>
 __global__ __launch_bounds__(kBlock) void layer_apply_kernel(float* __restrict__ theta, float* __restrict__ v,
                                                              float* __restrict__ m, float* __restrict__ snap,
                                                              const void* __restrict__ g,
                                                              const LayerChunk* __restrict__ chunks,
-                                                             const float* __restrict__ gaps, StepConst c) {
+                                                             const float* __restrict__ gaps, StepConst c,
+                                                             const float* __restrict__ next_snap,
+                                                             LayerPartial* __restrict__ partials) {
     const LayerChunk ch = chunks[blockIdx.x];
     const ChunkRange r = chunk_range(ch);
     const float G = gaps[ch.layer];
+    double d2 = 0.0, ms = 0.0;
     auto scalar = [&](uint64_t j) {
         float t1 = theta[j], v1 = v[j], m1 = m[j];
         layer_update_one<NAG>(t1, v1, m1, load_g1<DT>(g, j), G, c);
+        if constexpr (LOOK) gap_terms(d2, ms, t1, next_snap ? next_snap[j] : t1, m1);
         theta[j] = t1; v[j] = v1; m[j] = m1; snap[j] = t1;
     };
     for (uint64_t j = r.start + threadIdx.x; j < r.a0; j += kBlock) scalar(j);
     constexpr int U = 2;
     const uint64_t q_end = r.a1 >> 2;
     for (uint64_t q0 = (r.a0 >> 2) + threadIdx.x; q0 < q_end; q0 += (uint64_t)U * kBlock) {
-        f32x4 th[U], vv[U], mm[U], gg[U];
+        f32x4 th[U], vv[U], mm[U], gg[U], nx[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const uint64_t q = q0 + (uint64_t)u * kBlock;
@@ -170,6 +189,8 @@ __global__ __launch_bounds__(kBlock) void layer_apply_kernel(float* __restrict__
                 vv[u] = load4<STREAM_V>(v, q);
                 mm[u] = load4<true>(m, q);
                 gg[u] = load_g4<DT, ALIGNED>(g, q);
+                if constexpr (LOOK)
+                    if (next_snap) nx[u] = load4<true>(next_snap, q);
             }
         }
 #pragma unroll
@@ -180,6 +201,7 @@ __global__ __launch_bounds__(kBlock) void layer_apply_kernel(float* __restrict__
                 for (int e = 0; e < 4; ++e) {
                     float t1 = th[u][e], v1 = vv[u][e], m1 = mm[u][e];
                     layer_update_one<NAG>(t1, v1, m1, gg[u][e], G, c);
+                    if constexpr (LOOK) gap_terms(d2, ms, t1, next_snap ? nx[u][e] : t1, m1);
                     th[u][e] = t1; vv[u][e] = v1; mm[u][e] = m1;
                 }
                 store4<false>(theta, q, th[u]);
@@ -190,17 +212,19 @@ __global__ __launch_bounds__(kBlock) void layer_apply_kernel(float* __restrict__
         }
     }
     for (uint64_t j = r.a1 + threadIdx.x; j < r.end; j += kBlock) scalar(j);
+    if constexpr (LOOK) store_chunk_partial(d2, ms, partials + blockIdx.x);
 }
 
 }  // namespace
 
 hipError_t launch_apply_layerwise(const StatePtrs& st, uint64_t N, uint32_t worker, const void* g, int grad_dtype,
                                   int mode, bool nesterov, const LayerTables& lt, const StepConst& c,
-                                  hipStream_t stream) {
+                                  bool sums_ready, int64_t next_worker, hipStream_t stream) {
     if (lt.n_chunks == 0 || lt.n_layers == 0) return hipErrorInvalidValue;
     float* snap = st.snaps + (uint64_t)worker * st.stride;
     const dim3 block(kBlock), grid(lt.n_chunks), lgrid(lt.n_layers);
-    hipLaunchKernelGGL(layer_partial_kernel, grid, block, 0, stream, st.theta, st.m, snap, lt.chunks, lt.partials);
+    if (!sums_ready)
+        hipLaunchKernelGGL(layer_partial_kernel, grid, block, 0, stream, st.theta, st.m, snap, lt.chunks, lt.partials);
     if (mode == GA_MODE_GA_HINGE)
         hipLaunchKernelGGL(layer_gap_kernel<true>, lgrid, block, 0, stream, lt.partials, lt.spans, c.inv_bc_prev,
                            c.eta_max, c.eps, lt.gaps);
@@ -209,14 +233,16 @@ hipError_t launch_apply_layerwise(const StatePtrs& st, uint64_t N, uint32_t work
                            c.eta_max, c.eps, lt.gaps);
     const uintptr_t addr = reinterpret_cast<uintptr_t>(g);
     const bool stream_v = N > kKeepVMaxN;
+    const bool look = next_worker >= 0;
+    const float* next_snap =
+        (look && (uint32_t)next_worker != worker) ? st.snaps + (uint64_t)next_worker * st.stride : nullptr;
+#define GA_LAYER_APPLY3(DT, AL, SV, NG, LK)                                                                         \
+    hipLaunchKernelGGL((layer_apply_kernel<DT, AL, SV, NG, LK>), grid, block, 0, stream, st.theta, st.v, st.m, snap, \
+                       g, lt.chunks, lt.gaps, c, next_snap, lt.partials)
 #define GA_LAYER_APPLY(DT, AL, SV)                                                                                  \
     do {                                                                                                            \
-        if (nesterov)                                                                                               \
-            hipLaunchKernelGGL((layer_apply_kernel<DT, AL, SV, true>), grid, block, 0, stream, st.theta, st.v, st.m, \
-                               snap, g, lt.chunks, lt.gaps, c);                                                     \
-        else                                                                                                        \
-            hipLaunchKernelGGL((layer_apply_kernel<DT, AL, SV, false>), grid, block, 0, stream, st.theta, st.v,     \
-                               st.m, snap, g, lt.chunks, lt.gaps, c);                                               \
+        if (nesterov) { if (look) GA_LAYER_APPLY3(DT, AL, SV, true, true); else GA_LAYER_APPLY3(DT, AL, SV, true, false); } \
+        else { if (look) GA_LAYER_APPLY3(DT, AL, SV, false, true); else GA_LAYER_APPLY3(DT, AL, SV, false, false); } \
     } while (0)
     if (grad_dtype == GA_F32) {
         if ((addr & 15u) == 0) { if (stream_v) GA_LAYER_APPLY(GA_F32, true, true); else GA_LAYER_APPLY(GA_F32, true, false); }
@@ -226,6 +252,7 @@ hipError_t launch_apply_layerwise(const StatePtrs& st, uint64_t N, uint32_t work
         else { if (stream_v) GA_LAYER_APPLY(GA_BF16, false, true); else GA_LAYER_APPLY(GA_BF16, false, false); }
     }
 #undef GA_LAYER_APPLY
+#undef GA_LAYER_APPLY3
     return hipGetLastError();
 }
 

@@ -129,3 +129,53 @@ def test_resnet50_size_161_layers():
     del M, bufs
     gc.collect()
     torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("scope", ["layer", "global"])
+@pytest.mark.parametrize("nesterov", [False, True], ids=["heavy_ball", "nag"])
+def test_sums_prepared_by_the_previous_update_equal_the_separate_pass(scope, nesterov):
+    # Inside one ga_run_schedule call the update pass of an arrival also forms the norms of the next
+    # one (the next worker is known); arrival by arrival, a separate reduction pass forms them.  Both
+    # must give the same bits, also when a worker arrives twice in a row, and both must match the oracle.
+    N, W, seed = sum(LAYERS), 4, 13
+    kw = dict(layer_sizes=LAYERS) if scope == "layer" else dict(gap_scope=ga.GA_GAP_GLOBAL)
+    bufs = ga_inputs.gradient_buffers(W, N + 1, seed=seed, std=0.3)
+    dbufs = [dev(b)[1:] for b in bufs]                                  # 4-byte aligned only
+    sched = np.array([0, 1, 1, 1, 2, 0, 0, 3, 2, 2, 1, 3, 3, 0, 2, 1, 1, 0], dtype=np.uint32)
+    src = ga.buffer_source(dbufs, ga.GA_PICK_BY_WORKER)
+    A = ga.Master(N, W, mode=ga.GA_MODE_GA, nesterov=nesterov, **kw)
+    A.run_schedule(sched[:11], src)                                     # two calls: nothing is carried across
+    A.run_schedule(sched[11:], src)
+    B = ga.Master(N, W, mode=ga.GA_MODE_GA, nesterov=nesterov, **kw)
+    for w in sched:
+        B.apply(int(w), dbufs[int(w)])
+    O = oracle.LayerwiseMaster(N, W, oracle.MODE_GA, oracle.Hyper(), LAYERS if scope == "layer" else None,
+                               nesterov=nesterov)
+    O.run_buffers(sched, np.ascontiguousarray(bufs[:, 1:]))
+    sa, sb = gpu_state(A), gpu_state(B)
+    for x, y, name in zip(sa, sb, ("theta", "v", "m", "snapshots")):
+        assert bits_equal(x, y) == 0, name
+    assert bits_equal(A.layer_gaps(), B.layer_gaps()) == 0
+    check(A, O, "%s look-ahead" % scope)
+
+
+def test_state_written_between_calls_is_seen_by_the_next_arrival():
+    # the norms prepared for a following arrival never outlive a call: putting a new m or theta
+    # between two calls changes the next Gap exactly as the oracle says
+    N, W, seed = sum(LAYERS), 3, 17
+    bufs = ga_inputs.gradient_buffers(W, N, seed=seed, std=0.3)
+    dbufs = [dev(b) for b in bufs]
+    src = ga.buffer_source(dbufs, ga.GA_PICK_BY_WORKER)
+    M = ga.Master(N, W, mode=ga.GA_MODE_GA, layer_sizes=LAYERS)
+    O = oracle.LayerwiseMaster(N, W, oracle.MODE_GA, oracle.Hyper(), LAYERS)
+    first, second = np.array([0, 1, 2, 0], np.uint32), np.array([1, 1, 2], np.uint32)
+    M.run_schedule(first, src)
+    O.run_buffers(first, bufs)
+    new_m = (4.0 * O.m + 1e-3).astype(np.float32)
+    new_theta = (O.theta + 0.25).astype(np.float32)
+    O.m[:], O.theta[:] = new_m, new_theta
+    ga.ga_put_m(M.ctx, dev(new_m))
+    ga.ga_put_theta(M.ctx, dev(new_theta))
+    M.run_schedule(second, src)
+    O.run_buffers(second, bufs)
+    assert check(M, O, "after put") == 0
