@@ -86,13 +86,16 @@ bool build_layer_tables(uint64_t N, uint32_t n_layers, const uint64_t* sizes, st
     for (uint32_t p = 0; p < n_layers; ++p) {
         const uint64_t len = sizes ? sizes[p] : N;
         if (len == 0 || len > N - start) return false;
-        const uint64_t c = (len + ga::kLayerChunk - 1) / ga::kLayerChunk;
+        // cuts inside a layer fall on 256-byte boundaries of the arrays, so only the first and the last
+        // chunk of a layer have an unaligned edge
+        const uint64_t base = start & ~(uint64_t)63, end = start + len;
+        const uint64_t c = (end - base + ga::kLayerChunk - 1) / ga::kLayerChunk;
         if (spans) spans->push_back(ga::LayerSpan{(uint32_t)n_chunks, (uint32_t)c});
         if (chunks)
             for (uint64_t i = 0; i < c; ++i) {
-                const uint64_t off = i * ga::kLayerChunk;
-                const uint64_t l = len - off < ga::kLayerChunk ? len - off : ga::kLayerChunk;
-                chunks->push_back(ga::LayerChunk{start + off, (uint32_t)l, p});
+                const uint64_t lo = i == 0 ? start : base + i * ga::kLayerChunk;
+                const uint64_t hi = base + (i + 1) * ga::kLayerChunk < end ? base + (i + 1) * ga::kLayerChunk : end;
+                chunks->push_back(ga::LayerChunk{lo, (uint32_t)(hi - lo), p});
             }
         n_chunks += c;
         start += len;

@@ -47,7 +47,10 @@ struct DiagPartial {
 };
 
 // Layer-wise Gap: layers are cut into chunks of at most kLayerChunk parameters; one block per chunk.
-constexpr uint32_t kLayerChunk = 8192;
+#ifndef GA_LAYER_CHUNK
+#define GA_LAYER_CHUNK 4096
+#endif
+constexpr uint32_t kLayerChunk = GA_LAYER_CHUNK;   // a multiple of 64
 struct LayerChunk {
     uint64_t start;   // first parameter
     uint32_t len;     // parameters in the chunk

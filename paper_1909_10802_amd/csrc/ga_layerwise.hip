@@ -107,9 +107,21 @@ __global__ __launch_bounds__(kBlock) void layer_gap_kernel(const LayerPartial* _
     // one block per layer: strided partial sums, 64-lane butterfly, then the waves in order
     const LayerSpan sp = spans[blockIdx.x];
     double d2 = 0.0, ms = 0.0;
-    for (uint32_t i = threadIdx.x; i < sp.n_chunks; i += kBlock) {
-        d2 += partials[sp.first_chunk + i].dist2;
-        ms += partials[sp.first_chunk + i].msum;
+    constexpr int B = 8;   // loads in flight per thread; the additions keep their order
+    for (uint32_t i0 = threadIdx.x; i0 < sp.n_chunks; i0 += B * kBlock) {
+        LayerPartial p[B];
+#pragma unroll
+        for (int b = 0; b < B; ++b) {
+            const uint32_t i = i0 + b * kBlock;
+            p[b] = i < sp.n_chunks ? partials[sp.first_chunk + i] : LayerPartial{0.0, 0.0};
+        }
+#pragma unroll
+        for (int b = 0; b < B; ++b) {
+            if (i0 + b * kBlock < sp.n_chunks) {
+                d2 += p[b].dist2;
+                ms += p[b].msum;
+            }
+        }
     }
     __shared__ double part[2][kBlock / 64];
 #pragma unroll
