@@ -56,7 +56,7 @@ def parse():
                    help="after the timed region run three plain device copies of N floats (known size: 4N bytes read, "
                         "4N written) so that a counter profile of this command can be scaled")
     p.add_argument("--cpu-slice", type=int, default=1 << 23, help="parameters in the CPU-oracle sample")
-    p.add_argument("--cpu-steps", type=int, default=2000, help="arrivals in the CPU-oracle sample")
+    p.add_argument("--cpu-steps", type=int, default=6000, help="arrivals in the CPU-oracle sample")
     return p.parse_args()
 
 
@@ -77,7 +77,7 @@ def cpu_baseline(cfg, mode, n_slice, n_steps):
     O = oracle.Master(n_slice, W, modes[mode], oracle.Hyper(cfg["eta"], cfg["gamma"]))
     by_worker = cfg["pick"] == "worker"
     O.run_buffers(sched[:8], bufs, pick_by_worker=by_worker)       # touch the pages
-    n_one = min(64, (n_steps - 8) // 4)                            # a short single-thread leg first
+    n_one = min(128, (n_steps - 8) // 4)                            # a short single-thread leg first
     cores = oracle.num_threads()
     oracle.set_num_threads(1)
     t0 = time.perf_counter()
