@@ -51,6 +51,9 @@ def parse():
                    help="parameter-wise Gap (Eq. 5), layer-wise (Eq. 4, the workload's tensor table) or global (Def. 1)")
     p.add_argument("--mode", default="ga", choices=["ga", "ga_hinge", "sa", "sa_step", "asgd"])
     p.add_argument("--diag-every", type=int, default=250, help="Gap statistics every this many arrivals (0: never)")
+    p.add_argument("--queue", type=int, default=0,
+                   help="buffer workloads: apply the arrivals as queues of this many per launch (the persistent kernel "
+                        "fed from the gradient buffers) instead of one launch per arrival")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--calibration-copy", action="store_true",
                    help="after the timed region run three plain device copies of N floats (known size: 4N bytes read, "
@@ -178,6 +181,50 @@ def bench_fused(args, cfg, torch, ga, ga_inputs):
     return wall, roof, desc, extra
 
 
+def bench_queue(args, cfg, torch, ga, ga_inputs):
+    """Buffer workloads with the arrivals applied as queues of --queue per launch (results identical to one
+    launch per arrival; theta, v, m are read and written once per queue instead of once per arrival)."""
+    N, W, seed = cfg["N"], cfg["W"], cfg["seed"]
+    dev = "cuda:0"
+    K, Wm, Q = args.steps, args.warmup, args.queue
+    bufs = ga_inputs.device_gradient_buffers(cfg["n_bufs"], N, seed, cfg["grad_std"], cfg["grad_dtype"], dev)
+    src = ga.buffer_source(bufs, ga.GA_PICK_BY_WORKER if cfg["pick"] == "worker" else ga.GA_PICK_BY_ARRIVAL,
+                           persistent=True)
+    sched = ga.ga_simulate_schedule(W, K + Wm + 1, ga_inputs.DIST_CODES[cfg["dist"]], cfg["sigma"], seed)
+    eta = 0.01 if args.family == "adam" else cfg["eta"]
+    track = args.mode in ("ga", "ga_hinge")
+    M = ga.Master(N, W, eta=eta, gamma=cfg["gamma"], mode=args.mode, device=dev, family=args.family)
+    M.run_schedule(sched[:Wm], src)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    n_launch = 0
+    for done in range(0, K, Q):
+        M.run_schedule(sched[Wm + done:Wm + min(done + Q, K)], src)
+        n_launch += 1
+    e1.record()
+    last_diag = M.diagnostics(int(sched[Wm + K])) if track else None
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    kernel_s = e0.elapsed_time(e1) * 1e-3
+    g_bytes = 4 if cfg["grad_dtype"] == "f32" else 2
+    per_arrival = g_bytes + (8 if track else 0) + (8 if args.family == "dana" else 0)
+    per_launch = 4 * 2 * ((3 if track else 2) + (1 if args.family == "adam" else 0))
+    bpu = per_arrival + per_launch * n_launch / K
+    ach = bpu * N * K / kernel_s / 1e9
+    roof = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
+            "traffic": None, "kernel": "persistent_kernel (gradient buffers)", "bytes_per_update": bpu,
+            "avg_launch_ms": kernel_s * 1e3 / n_launch, "arrivals_per_launch": Q,
+            "algorithmic_bytes_per_launch": int(round(bpu * N * K / n_launch))}
+    desc = ("%s: N=%d float parameters, %d workers, %s iteration times, %d %s gradient buffers picked by %s, queues of "
+            "%d arrivals per launch, family %s, mode %s" % (args.workload, N, W, cfg["dist"], cfg["n_bufs"],
+                                                            cfg["grad_dtype"], cfg["pick"], Q, args.family, args.mode))
+    extra = {"theta_finite": bool(torch.isfinite(M.theta()).all().item()),
+             "mean_gap_last": None if last_diag is None else last_diag["mean_graw"] + 1.0}
+    return wall, roof, desc, extra
+
+
 def bench_persistent(args, cfg, torch, ga, ga_inputs):
     """Workloads with the in-kernel quadratic-plus-noise source: the persistent multi-arrival kernel."""
     N, W, seed = cfg["N"], cfg["W"], cfg["seed"]
@@ -261,7 +308,10 @@ def main():
     fused = cfg["source"] == "buffers"
     if not fused and args.gap_scope != "parameter":
         sys.exit("bench.py: the persistent-kernel workloads use the parameter-wise Gap")
-    wall, roof, desc, extra = (bench_fused if fused else bench_persistent)(args, cfg, torch, ga, ga_inputs)
+    if args.queue and (not fused or args.gap_scope != "parameter"):
+        sys.exit("bench.py: --queue is for the gradient-buffer workloads with the parameter-wise Gap")
+    run = bench_queue if (fused and args.queue) else bench_fused if fused else bench_persistent
+    wall, roof, desc, extra = run(args, cfg, torch, ga, ga_inputs)
     N, K = cfg["N"], args.steps
     out = {
         "metric": "G param-updates/s and achieved HBM GB/s (% of peak), GA fused update",

@@ -153,7 +153,15 @@ enum ga_pick { GA_PICK_BY_WORKER = 0, GA_PICK_BY_ARRIVAL = 1 };
  * GA_SRC_BUFFERS: precomputed gradients.  host_dev_bufs is a HOST array of
  *   n_bufs DEVICE pointers, each to N values of `dtype`.  Arrival k of worker i
  *   uses buffer (i mod n_bufs) for GA_PICK_BY_WORKER, ((k-1) mod n_bufs) for
- *   GA_PICK_BY_ARRIVAL.  One update launch per arrival.
+ *   GA_PICK_BY_ARRIVAL.  persistent == 0: one update launch per arrival.
+ *   persistent != 0 (parameter-wise Gap only; every buffer aligned to four
+ *   values: 16 bytes for GA_F32, 8 for GA_BF16, else GA_ERR_ALIGN): the
+ *   arrivals of the call are a queue whose gradients are all present, and
+ *   each chunk of up to 8192 of them is applied by one launch that keeps
+ *   theta, v and m in registers and touches only the gradient and the
+ *   snapshot of each arrival.  The arrivals are applied in schedule order
+ *   with the arithmetic of the per-arrival kernel: the results are the same
+ *   bits.  The buffers must not change before the stream has finished.
  */
 typedef struct ga_grad_source {
     int kind; /* ga_source_kind */

@@ -313,8 +313,9 @@ def quadratic_source(dev_a, dev_theta_star, seed, sigma=0.01, persistent=True, d
     return s
 
 
-def buffer_source(dev_bufs, pick=GA_PICK_BY_WORKER):
-    """dev_bufs: list of CUDA tensors (all float32 or all bfloat16), N values each."""
+def buffer_source(dev_bufs, pick=GA_PICK_BY_WORKER, persistent=False):
+    """dev_bufs: list of CUDA tensors (all float32 or all bfloat16), N values each.
+    persistent: apply the arrivals of a ga_run_schedule call as a queue, one launch per chunk of them."""
     import torch
     s = ga_grad_source()
     s.kind = GA_SRC_BUFFERS
@@ -324,6 +325,7 @@ def buffer_source(dev_bufs, pick=GA_PICK_BY_WORKER):
     s.dtype = GA_BF16 if dev_bufs[0].dtype == torch.bfloat16 else GA_F32
     assert all(b.dtype == dev_bufs[0].dtype for b in dev_bufs)
     s.pick = pick
+    s.persistent = 1 if persistent else 0
     s._keep = (ptrs, list(dev_bufs))
     return s
 

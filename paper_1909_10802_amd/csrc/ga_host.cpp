@@ -28,6 +28,7 @@ struct ga_ctx {
     ga::StatePtrs st{};
     ga_arrival* dev_table = nullptr;
     ga::AdamRow* dev_adam_table = nullptr;
+    const void** dev_grad_table = nullptr;   // one gradient-buffer pointer per row of the arrival table
     size_t state_bytes = 0;        // theta .. last state row, contiguous in the workspace
     ga::DiagPartial* dev_partials = nullptr;
     uint64_t k = 0;
@@ -37,6 +38,7 @@ struct ga_ctx {
     // the upload so that the next chunk does not overwrite rows that are still being copied
     ga_arrival* rows = nullptr;
     ga::AdamRow* adam_rows = nullptr;
+    const void** grad_rows = nullptr;
     hipEvent_t staged = nullptr;
     bool staged_pending = false;
     int gap_scope = GA_GAP_PARAMETER;
@@ -76,7 +78,7 @@ uint64_t round_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
 struct Layout {
     uint64_t Np, n_rows;
     size_t off_theta, off_v, off_m, off_snaps, off_worker_v, off_v2, off_table, off_partials, total;
-    size_t off_chunks, off_spans, off_layer_partials, off_gaps, off_adam_table;
+    size_t off_chunks, off_spans, off_layer_partials, off_gaps, off_adam_table, off_grad_table;
 };
 
 // Chunks of at most kLayerChunk parameters, never across a layer boundary.  sizes == nullptr: one layer of N.
@@ -104,7 +106,7 @@ bool build_layer_tables(uint64_t N, uint32_t n_layers, const uint64_t* sizes, st
     return start == N && n_chunks < 0x7FFFFFFFull;
 }
 
-// theta | v | m | W snapshots | [DANA: W worker momenta] | [ADAM: v2] | arrival table | reduction partials
+// theta | v | m | W snapshots | [DANA: W worker momenta] | [ADAM: v2] | arrival, Adam and gradient-pointer tables | reduction partials
 Layout layout_for(uint64_t N, uint32_t W, int family, uint64_t n_chunks = 0, uint32_t n_layers = 0) {
     Layout L;
     L.Np = round_up(N, 64);                  // every array starts 256-byte aligned
@@ -124,7 +126,8 @@ Layout layout_for(uint64_t N, uint32_t W, int family, uint64_t n_chunks = 0, uin
     }
     L.off_table = L.n_rows * row;
     L.off_adam_table = L.off_table + round_up((uint64_t)ga::kTableCap * sizeof(ga_arrival), 256);
-    L.off_partials = L.off_adam_table + round_up((uint64_t)ga::kTableCap * sizeof(ga::AdamRow), 256);
+    L.off_grad_table = L.off_adam_table + round_up((uint64_t)ga::kTableCap * sizeof(ga::AdamRow), 256);
+    L.off_partials = L.off_grad_table + round_up((uint64_t)ga::kTableCap * sizeof(void*), 256);
     L.total = L.off_partials + round_up((uint64_t)(ga::kDiagMaxBlocks + 1) * sizeof(ga::DiagPartial), 256);
     L.off_chunks = L.total;
     L.off_spans = L.off_chunks + round_up(n_chunks * sizeof(ga::LayerChunk), 256);
@@ -584,6 +587,7 @@ int ga_create_ex(ga_ctx** out, const ga_config* cfg, void* dev_workspace, size_t
     c->st.stride = L.Np;
     c->dev_table = reinterpret_cast<ga_arrival*>(base + L.off_table);
     c->dev_adam_table = reinterpret_cast<ga::AdamRow*>(base + L.off_adam_table);
+    c->dev_grad_table = reinterpret_cast<const void**>(base + L.off_grad_table);
     c->dev_partials = reinterpret_cast<ga::DiagPartial*>(base + L.off_partials);
     c->iter.assign(n_workers, 0);
 
@@ -609,6 +613,7 @@ int ga_create_ex(ga_ctx** out, const ga_config* cfg, void* dev_workspace, size_t
     }
     if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void**>(&c->rows), ga::kTableCap * sizeof(ga_arrival), hipHostMallocDefault);
     if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void**>(&c->adam_rows), ga::kTableCap * sizeof(ga::AdamRow), hipHostMallocDefault);
+    if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void**>(&c->grad_rows), ga::kTableCap * sizeof(void*), hipHostMallocDefault);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c->staged, hipEventDisableTiming);
     if (e != hipSuccess) {
         const int rc = hip_fail(nullptr, e, "create: initial fill or host staging");
@@ -637,6 +642,7 @@ void ga_destroy(ga_ctx* ctx) {
     if (ctx->staged) (void)hipEventDestroy(ctx->staged);
     if (ctx->rows) (void)hipHostFree(ctx->rows);
     if (ctx->adam_rows) (void)hipHostFree(ctx->adam_rows);
+    if (ctx->grad_rows) (void)hipHostFree(ctx->grad_rows);
     delete ctx;
 }
 
@@ -698,6 +704,62 @@ int ga_run_schedule(ga_ctx* ctx, const uint32_t* host_schedule, uint64_t T, cons
 static int run_schedule_checked(ga_ctx* ctx, const uint32_t* host_schedule, uint64_t T, const ga_grad_source* src,
                                 const float* host_eta);
 
+// Persistent path: the table of a chunk of the schedule is planned on the host, uploaded, and replayed by
+// one launch; with gradient buffers the table also names the buffer of every arrival.
+static int run_persistent(ga_ctx* ctx, const uint32_t* host_schedule, uint64_t T, const ga_grad_source* src,
+                          const float* host_eta) {
+    const bool buffers = src->kind == GA_SRC_BUFFERS;
+    const ga::RunConst rcst = run_const(ctx, src);
+    for (uint64_t done = 0; done < T;) {
+        const uint32_t n = (uint32_t)((T - done < ga::kTableCap) ? (T - done) : ga::kTableCap);
+        std::vector<uint64_t> iter_after = ctx->iter;
+        std::vector<uint64_t> taus(n);
+        hipError_t e = hipSuccess;
+        if (ctx->staged_pending) {               // the previous upload from the staging rows must have finished
+            e = hipEventSynchronize(ctx->staged);
+            if (e != hipSuccess) return hip_fail(ctx, e, "table staging");
+            ctx->staged_pending = false;
+        }
+        plan(n, host_schedule + done, ctx->k, iter_after.data(), ctx->mode, ctx->lr, ctx->beta, ctx->rows, taus.data(),
+             host_eta ? host_eta + done : nullptr);
+        e = hipMemcpyAsync(ctx->dev_table, ctx->rows, (size_t)n * sizeof(ga_arrival), hipMemcpyHostToDevice, ctx->stream);
+        if (e != hipSuccess) return hip_fail(ctx, e, "table upload");
+        if (ctx->family == GA_FAMILY_ADAM) {
+            for (uint32_t a = 0; a < n; ++a) {
+                ctx->adam_rows[a].inv_bc1 = inverse_bias_correction(ctx->beta1, ctx->k + a + 1);
+                ctx->adam_rows[a].inv_bc2 = inverse_bias_correction(ctx->beta2, ctx->k + a + 1);
+            }
+            e = hipMemcpyAsync(ctx->dev_adam_table, ctx->adam_rows, (size_t)n * sizeof(ga::AdamRow), hipMemcpyHostToDevice, ctx->stream);
+            if (e != hipSuccess) return hip_fail(ctx, e, "table upload");
+        }
+        if (buffers) {
+            for (uint32_t a = 0; a < n; ++a) {     // the arrival at master step k + a + 1
+                const uint32_t w = host_schedule[done + a];
+                const uint64_t b = (src->pick == GA_PICK_BY_WORKER) ? w % src->n_bufs : (ctx->k + a) % src->n_bufs;
+                ctx->grad_rows[a] = src->host_dev_bufs[b];
+            }
+            e = hipMemcpyAsync(ctx->dev_grad_table, ctx->grad_rows, (size_t)n * sizeof(void*), hipMemcpyHostToDevice, ctx->stream);
+            if (e != hipSuccess) return hip_fail(ctx, e, "table upload");
+        }
+        e = hipEventRecord(ctx->staged, ctx->stream);
+        if (e != hipSuccess) return hip_fail(ctx, e, "table staging");
+        ctx->staged_pending = true;
+        if (buffers)
+            e = ga::launch_batched(ctx->st, ctx->N, ctx->family, ctx->dev_table, ctx->dev_adam_table, n, ctx->k,
+                                   ctx->dev_grad_table, src->dtype, ctx->mode, ctx->nesterov, keeps_m(ctx), rcst, ctx->stream);
+        else
+            e = ga::launch_persistent(ctx->st, ctx->N, ctx->family, ctx->dev_table, ctx->dev_adam_table, n, ctx->k, src->dev_a,
+                                      src->dev_theta_star, ctx->mode, ctx->nesterov, keeps_m(ctx), rcst, ctx->stream);
+        if (e != hipSuccess) return hip_fail(ctx, e, "persistent launch");
+        ctx->delays.insert(ctx->delays.end(), taus.begin(), taus.end());
+        ctx->iter.swap(iter_after);
+        ctx->k += n;
+        done += n;
+    }
+    return GA_OK;
+}
+
+
 int ga_run_schedule_lr(ga_ctx* ctx, const uint32_t* host_schedule, uint64_t T, const ga_grad_source* src,
                        const float* host_eta) {
     if (!ctx) return GA_ERR_ARG;
@@ -725,6 +787,15 @@ static int run_schedule_checked(ga_ctx* ctx, const uint32_t* host_schedule, uint
         for (uint32_t b = 0; b < src->n_bufs; ++b)
             if (!src->host_dev_bufs[b] || ((uintptr_t)src->host_dev_bufs[b] & need))
                 return fail(ctx, GA_ERR_ARG, "run_schedule: gradient buffer %u is null or misaligned", b);
+        if (src->persistent) {
+            if (ctx->gap_scope != GA_GAP_PARAMETER)
+                return fail(ctx, GA_ERR_ARG, "run_schedule: the persistent kernel exists for the parameter-wise Gap only");
+            const uintptr_t vec = src->dtype == GA_F32 ? 15u : 7u;
+            for (uint32_t b = 0; b < src->n_bufs; ++b)
+                if ((uintptr_t)src->host_dev_bufs[b] & vec)
+                    return fail(ctx, GA_ERR_ALIGN, "run_schedule: with persistent set, gradient buffer %u must be aligned to four values", b);
+            return run_persistent(ctx, host_schedule, T, src, host_eta);
+        }
         const bool write_snap = is_gap_mode(ctx->mode) || ctx->track_gap;
         for (uint64_t a = 0; a < T; ++a) {
             const uint32_t w = host_schedule[a];
@@ -761,41 +832,7 @@ static int run_schedule_checked(ga_ctx* ctx, const uint32_t* host_schedule, uint
         return GA_OK;
     }
 
-    // persistent path: the table of a chunk is planned on the host, uploaded, and replayed by one launch
-    for (uint64_t done = 0; done < T;) {
-        const uint32_t n = (uint32_t)((T - done < ga::kTableCap) ? (T - done) : ga::kTableCap);
-        std::vector<uint64_t> iter_after = ctx->iter;
-        std::vector<uint64_t> taus(n);
-        hipError_t e = hipSuccess;
-        if (ctx->staged_pending) {               // the previous upload from the staging rows must have finished
-            e = hipEventSynchronize(ctx->staged);
-            if (e != hipSuccess) return hip_fail(ctx, e, "table staging");
-            ctx->staged_pending = false;
-        }
-        plan(n, host_schedule + done, ctx->k, iter_after.data(), ctx->mode, ctx->lr, ctx->beta, ctx->rows, taus.data(),
-             host_eta ? host_eta + done : nullptr);
-        e = hipMemcpyAsync(ctx->dev_table, ctx->rows, (size_t)n * sizeof(ga_arrival), hipMemcpyHostToDevice, ctx->stream);
-        if (e != hipSuccess) return hip_fail(ctx, e, "table upload");
-        if (ctx->family == GA_FAMILY_ADAM) {
-            for (uint32_t a = 0; a < n; ++a) {
-                ctx->adam_rows[a].inv_bc1 = inverse_bias_correction(ctx->beta1, ctx->k + a + 1);
-                ctx->adam_rows[a].inv_bc2 = inverse_bias_correction(ctx->beta2, ctx->k + a + 1);
-            }
-            e = hipMemcpyAsync(ctx->dev_adam_table, ctx->adam_rows, (size_t)n * sizeof(ga::AdamRow), hipMemcpyHostToDevice, ctx->stream);
-            if (e != hipSuccess) return hip_fail(ctx, e, "table upload");
-        }
-        e = hipEventRecord(ctx->staged, ctx->stream);
-        if (e != hipSuccess) return hip_fail(ctx, e, "table staging");
-        ctx->staged_pending = true;
-        e = ga::launch_persistent(ctx->st, ctx->N, ctx->family, ctx->dev_table, ctx->dev_adam_table, n, ctx->k, src->dev_a,
-                                  src->dev_theta_star, ctx->mode, ctx->nesterov, keeps_m(ctx), rcst, ctx->stream);
-        if (e != hipSuccess) return hip_fail(ctx, e, "persistent launch");
-        ctx->delays.insert(ctx->delays.end(), taus.begin(), taus.end());
-        ctx->iter.swap(iter_after);
-        ctx->k += n;
-        done += n;
-    }
-    return GA_OK;
+    return run_persistent(ctx, host_schedule, T, src, host_eta);
 }
 
 int ga_quadratic_gradient(ga_ctx* ctx, uint32_t worker_id, const ga_grad_source* src, float* dev_g_out) {

@@ -111,6 +111,13 @@ hipError_t launch_persistent(const StatePtrs& st, uint64_t N, int family, const 
                              const float* theta_star, int mode, bool nesterov, bool keep_m, const RunConst& rc,
                              hipStream_t stream);
 
+// The same with the gradient of row t read from the buffer dev_grads[t] (N values of grad_dtype,
+// each buffer aligned to four values); dev_grads is a device array of T pointers.
+hipError_t launch_batched(const StatePtrs& st, uint64_t N, int family, const ga_arrival* dev_table,
+                          const AdamRow* dev_adam_table, uint32_t T, uint64_t k0, const void* const* dev_grads,
+                          int grad_dtype, int mode, bool nesterov, bool keep_m, const RunConst& rc,
+                          hipStream_t stream);
+
 // g_out = a * (snap_w - theta_star) + sigma * z(seed, k, j)
 hipError_t launch_quadratic_gradient(const StatePtrs& st, uint64_t N, uint32_t worker, const float* a,
                                      const float* theta_star, uint64_t k, const RunConst& rc, float* g_out,
