@@ -328,6 +328,25 @@ int ga_set_theta(ga_ctx* ctx, const float* dev_theta0);
  * parameter. */
 int ga_apply(ga_ctx* ctx, uint32_t worker_id, const void* dev_grad, int grad_dtype);
 
+/* A queue of n arrivals whose gradients are all in device memory, applied in
+ * order (Alg. 4 / 5 / 3 per arrival, as ga_apply would) by one launch per
+ * chunk of up to 8192 arrivals: theta, v and m stay in registers over the
+ * chunk and only the gradient and the arriving worker's snapshot move per
+ * arrival.  Same results, bit for bit, as n calls of ga_apply.
+ *   host_workers   HOST array of n worker ids (a worker may appear more than once)
+ *   host_dev_grads HOST array of n DEVICE pointers, each to N values of
+ *                  grad_dtype, aligned to four values (16 bytes for GA_F32,
+ *                  8 for GA_BF16); read, never written, not owned; they must
+ *                  stay unchanged until the stream has finished
+ * Parameter-wise Gap only.  Any family and penalty; the context's step size
+ * is used for every arrival.  Asynchronous on the context's stream.
+ * Errors (nothing is launched and no bookkeeping changes): GA_ERR_ARG (null
+ * pointer, unknown dtype, layer-wise or global Gap), GA_ERR_WORKER,
+ * GA_ERR_ALIGN; GA_ERR_HIP from a failed upload or launch leaves the arrivals
+ * of the chunks already launched applied. */
+int ga_apply_queue(ga_ctx* ctx, uint64_t n, const uint32_t* host_workers, const void* const* host_dev_grads,
+                   int grad_dtype);
+
 /* T arrivals in the order of host_schedule (worker ids), gradients from src.
  * All arguments are checked before the first arrival (then nothing has
  * changed on error); if a HIP call fails later (GA_ERR_HIP), the arrivals

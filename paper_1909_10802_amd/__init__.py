@@ -91,6 +91,7 @@ SIGNATURES = {
     "ga_set_track_gap": (_i, [_p, _i]),
     "ga_set_theta": (_i, [_p, _p]),
     "ga_apply": (_i, [_p, _u32, _p, _i]),
+    "ga_apply_queue": (_i, [_p, _u64, _p, _p, _i]),
     "ga_run_schedule": (_i, [_p, _p, _u64, C.POINTER(ga_grad_source)]),
     "ga_run_schedule_lr": (_i, [_p, _p, _u64, C.POINTER(ga_grad_source), _p]),
     "ga_warmup_lr": (_i, [_f, _u32, _u64, _u64, _u64, _p]),
@@ -299,6 +300,18 @@ def ga_apply(ctx, worker_id, dev_grad, grad_dtype=None):
     _check(lib().ga_apply(ctx, worker_id, _dev(dev_grad), grad_dtype), ctx)
 
 
+def ga_apply_queue(ctx, host_workers, dev_grads, grad_dtype=None):
+    """host_workers: worker ids; dev_grads: one CUDA tensor per arrival (all float32 or all bfloat16)."""
+    import torch
+    host_workers = np.ascontiguousarray(host_workers, dtype=np.uint32)
+    assert host_workers.size == len(dev_grads)
+    if grad_dtype is None:
+        grad_dtype = GA_BF16 if len(dev_grads) and dev_grads[0].dtype == torch.bfloat16 else GA_F32
+    want = {GA_BF16: torch.bfloat16, GA_F32: torch.float32}.get(grad_dtype)     # unknown codes: the library refuses
+    ptrs = (C.c_void_p * max(len(dev_grads), 1))(*[_dev(g, want) for g in dev_grads])
+    _check(lib().ga_apply_queue(ctx, host_workers.size, _np_ptr(host_workers), ptrs, grad_dtype), ctx)
+
+
 def quadratic_source(dev_a, dev_theta_star, seed, sigma=0.01, persistent=True, dev_scratch_g=None):
     import torch
     s = ga_grad_source()
@@ -492,6 +505,9 @@ class Master:
 
     def apply(self, worker_id, dev_grad):
         ga_apply(self.ctx, worker_id, dev_grad)
+
+    def apply_queue(self, workers, dev_grads):
+        ga_apply_queue(self.ctx, workers, dev_grads)
 
     def run_schedule(self, schedule, src):
         ga_run_schedule(self.ctx, schedule, src)

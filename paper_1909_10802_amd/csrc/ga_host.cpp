@@ -706,10 +706,13 @@ static int run_schedule_checked(ga_ctx* ctx, const uint32_t* host_schedule, uint
 
 // Persistent path: the table of a chunk of the schedule is planned on the host, uploaded, and replayed by
 // one launch; with gradient buffers the table also names the buffer of every arrival.
+// queue_grads != nullptr: one device buffer per arrival, given by the caller (src is then not used).
 static int run_persistent(ga_ctx* ctx, const uint32_t* host_schedule, uint64_t T, const ga_grad_source* src,
-                          const float* host_eta) {
-    const bool buffers = src->kind == GA_SRC_BUFFERS;
-    const ga::RunConst rcst = run_const(ctx, src);
+                          const float* host_eta, const void* const* queue_grads = nullptr, int queue_dtype = GA_F32) {
+    const bool buffers = queue_grads || src->kind == GA_SRC_BUFFERS;
+    const int grad_dtype = queue_grads ? queue_dtype : src->dtype;
+    ga_grad_source none{};
+    const ga::RunConst rcst = run_const(ctx, queue_grads ? &none : src);
     for (uint64_t done = 0; done < T;) {
         const uint32_t n = (uint32_t)((T - done < ga::kTableCap) ? (T - done) : ga::kTableCap);
         std::vector<uint64_t> iter_after = ctx->iter;
@@ -734,6 +737,10 @@ static int run_persistent(ga_ctx* ctx, const uint32_t* host_schedule, uint64_t T
         }
         if (buffers) {
             for (uint32_t a = 0; a < n; ++a) {     // the arrival at master step k + a + 1
+                if (queue_grads) {
+                    ctx->grad_rows[a] = queue_grads[done + a];
+                    continue;
+                }
                 const uint32_t w = host_schedule[done + a];
                 const uint64_t b = (src->pick == GA_PICK_BY_WORKER) ? w % src->n_bufs : (ctx->k + a) % src->n_bufs;
                 ctx->grad_rows[a] = src->host_dev_bufs[b];
@@ -746,7 +753,7 @@ static int run_persistent(ga_ctx* ctx, const uint32_t* host_schedule, uint64_t T
         ctx->staged_pending = true;
         if (buffers)
             e = ga::launch_batched(ctx->st, ctx->N, ctx->family, ctx->dev_table, ctx->dev_adam_table, n, ctx->k,
-                                   ctx->dev_grad_table, src->dtype, ctx->mode, ctx->nesterov, keeps_m(ctx), rcst, ctx->stream);
+                                   ctx->dev_grad_table, grad_dtype, ctx->mode, ctx->nesterov, keeps_m(ctx), rcst, ctx->stream);
         else
             e = ga::launch_persistent(ctx->st, ctx->N, ctx->family, ctx->dev_table, ctx->dev_adam_table, n, ctx->k, src->dev_a,
                                       src->dev_theta_star, ctx->mode, ctx->nesterov, keeps_m(ctx), rcst, ctx->stream);
@@ -833,6 +840,25 @@ static int run_schedule_checked(ga_ctx* ctx, const uint32_t* host_schedule, uint
     }
 
     return run_persistent(ctx, host_schedule, T, src, host_eta);
+}
+
+int ga_apply_queue(ga_ctx* ctx, uint64_t n, const uint32_t* host_workers, const void* const* host_dev_grads,
+                   int grad_dtype) {
+    if (!ctx) return GA_ERR_ARG;
+    if (n == 0) return GA_OK;
+    if (!host_workers || !host_dev_grads) return fail(ctx, GA_ERR_ARG, "apply_queue: null argument");
+    if (grad_dtype != GA_F32 && grad_dtype != GA_BF16) return fail(ctx, GA_ERR_ARG, "apply_queue: unknown gradient dtype");
+    if (ctx->gap_scope != GA_GAP_PARAMETER)
+        return fail(ctx, GA_ERR_ARG, "apply_queue: the persistent kernel exists for the parameter-wise Gap only");
+    const uintptr_t vec = grad_dtype == GA_F32 ? 15u : 7u;
+    for (uint64_t a = 0; a < n; ++a) {
+        if (host_workers[a] >= ctx->W)
+            return fail(ctx, GA_ERR_WORKER, "apply_queue: workers[%llu] = %u >= n_workers %u", (unsigned long long)a, host_workers[a], ctx->W);
+        if (!host_dev_grads[a]) return fail(ctx, GA_ERR_ARG, "apply_queue: gradient %llu is null", (unsigned long long)a);
+        if ((uintptr_t)host_dev_grads[a] & vec)
+            return fail(ctx, GA_ERR_ALIGN, "apply_queue: gradient %llu must be aligned to four values", (unsigned long long)a);
+    }
+    return run_persistent(ctx, host_workers, n, nullptr, nullptr, host_dev_grads, grad_dtype);
 }
 
 int ga_quadratic_gradient(ga_ctx* ctx, uint32_t worker_id, const ga_grad_source* src, float* dev_g_out) {

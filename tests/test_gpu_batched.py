@@ -117,3 +117,44 @@ def test_queue_argument_errors():
     with pytest.raises(ga.GaError) as e:
         L.run_schedule(np.zeros(3, np.uint32), ga.buffer_source([buf[:N]], persistent=True))
     assert e.value.status == ga.GA_ERR_ARG and L.k == 0
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_apply_queue_equals_apply_one_by_one(dtype):
+    # a queue given as (worker, gradient) pairs, longer than one table, against ga_apply per arrival and the oracle
+    N, W, T = 4_099, 6, 300
+    ref, dbufs = make_bufs(7, N, 31, dtype)
+    rng = np.random.default_rng(8)
+    workers = rng.integers(0, W, T).astype(np.uint32)
+    which = rng.integers(0, 7, T)
+    A = ga.Master(N, W, mode=ga.GA_MODE_GA, eta=0.05)
+    A.apply_queue(workers[:100], [dbufs[b] for b in which[:100]])
+    A.apply_queue(workers[100:], [dbufs[b] for b in which[100:]])
+    A.apply_queue(workers[:0], [])                                     # an empty queue is a no-op
+    B = ga.Master(N, W, mode=ga.GA_MODE_GA, eta=0.05)
+    O = oracle.Master(N, W, oracle.MODE_GA, oracle.Hyper(0.05, 0.9))
+    for w, b in zip(workers, which):
+        B.apply(int(w), dbufs[b])
+        O.apply(int(w), ref[b])
+    for x, y, name in zip(gpu_state(A), gpu_state(B), ("theta", "v", "m", "snapshots")):
+        assert bits_equal(x, y) == 0, name
+    compare_masters(A, O, "apply_queue %s" % dtype)
+
+
+def test_apply_queue_errors_change_nothing():
+    N, W = 1000, 2
+    buf = torch.zeros(N + 4, dtype=torch.float32, device=DEV)
+    M = ga.Master(N, W)
+    for workers, grads, status in [([0, 2], [buf[:N], buf[:N]], ga.GA_ERR_WORKER),
+                                   ([0, 1], [buf[:N], buf[1:N + 1]], ga.GA_ERR_ALIGN)]:
+        with pytest.raises(ga.GaError) as e:
+            M.apply_queue(workers, grads)
+        assert e.value.status == status and M.k == 0
+    with pytest.raises(ga.GaError) as e:
+        ga.ga_apply_queue(M.ctx, [0], [buf[:N]], grad_dtype=7)
+    assert e.value.status == ga.GA_ERR_ARG
+    L = ga.Master(N, W, layer_sizes=[400, 600])
+    with pytest.raises(ga.GaError) as e:
+        L.apply_queue([0], [buf[:N]])
+    assert e.value.status == ga.GA_ERR_ARG and L.k == 0
+    assert float(M.theta().abs().sum()) == 0.0
