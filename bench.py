@@ -107,6 +107,23 @@ def kernels_hash():
     return h.hexdigest()[:16]
 
 
+def measured_copy_rate(torch, src):
+    """GB/s (bytes read + bytes written) of a plain device copy of the parameter vector: median of 20 timed copies
+    after 3 untimed ones.  A reference point for the part's streaming rate, beside the published HBM peak."""
+    dst = torch.empty_like(src)
+    times = []
+    for i in range(23):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        dst.copy_(src)
+        e1.record()
+        e1.synchronize()
+        if i >= 3:
+            times.append(e0.elapsed_time(e1))
+    times.sort()
+    return 2.0 * src.numel() * src.element_size() / (times[len(times) // 2] * 1e-3) / 1e9
+
+
 def bench_fused(args, cfg, torch, ga, ga_inputs):
     """Workloads with precomputed gradient buffers: one fused-update launch per arrival."""
     N, W, seed = cfg["N"], cfg["W"], cfg["seed"]
@@ -160,6 +177,7 @@ def bench_fused(args, cfg, torch, ga, ga_inputs):
     achieved = bpu * N / (kernel_ms * 1e-3) / 1e9
     theta = M.theta()
     finite = bool(torch.isfinite(theta).all().item())
+    copy_gbs = measured_copy_rate(torch, theta)
     if args.calibration_copy:
         dst = torch.empty(N, dtype=torch.float32, device=dev)
         for _ in range(3):
@@ -171,7 +189,8 @@ def bench_fused(args, cfg, torch, ga, ga_inputs):
             "traffic": traffic if args.family == "momentum" else None,
             "kernel": ("layer_gap_kernel + layer_apply_kernel (+ layer_partial_kernel on the first arrival of a call)" if args.gap_scope != "parameter"
                        else "apply_kernel" if args.family == "momentum" else "family_apply_kernel"), "bytes_per_update": bpu, "avg_launch_ms": kernel_ms,
-            "algorithmic_bytes_per_launch": int(round(bpu * N))}
+            "algorithmic_bytes_per_launch": int(round(bpu * N)),
+            "copy_GBs": copy_gbs, "frac_of_copy": achieved / copy_gbs}
     desc = ("%s: N=%d float parameters, %d workers, %s iteration times, %d %s gradient buffers picked by %s, one "
             "fused-update launch per arrival, family %s, mode %s" % (args.workload, N, W, cfg["dist"], cfg["n_bufs"],
                                                                      cfg["grad_dtype"], cfg["pick"], args.family,
