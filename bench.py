@@ -63,6 +63,17 @@ def parse():
     return p.parse_args()
 
 
+def cpu_model():
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
 def cpu_baseline(cfg, mode, n_slice, n_steps):
     """Time the oracle, as it stands, on a contiguous slice of the workload."""
     import numpy as np
@@ -92,7 +103,7 @@ def cpu_baseline(cfg, mode, n_slice, n_steps):
     dt = time.perf_counter() - t0
     n_all = n_steps - 8 - n_one
     return {"value": float(n_slice) * n_all / dt / 1e9, "unit": "G param-updates/s", "cores": cores, "kind": "oracle",
-            "value_1_core": float(n_slice) * n_one / dt1 / 1e9,
+            "value_1_core": float(n_slice) * n_one / dt1 / 1e9, "cpu": cpu_model(),
             "sample": "contiguous slice of %d parameters, all %d workers, the same schedule and gradient recipe: "
                       "%d arrivals on %d threads (%.1f s) after %d arrivals on one thread (%.1f s)"
                       % (n_slice, W, n_all, cores, dt, n_one, dt1)}
@@ -303,7 +314,7 @@ def cpu_baseline_quadratic(cfg, mode, n_slice, n_steps):
     O.run_quadratic(sched[8:], a, ts, seed)
     dt = time.perf_counter() - t0
     return {"value": float(n_slice) * (n_steps - 8) / dt / 1e9, "unit": "G param-updates/s",
-            "cores": oracle.num_threads(), "kind": "oracle",
+            "cores": oracle.num_threads(), "kind": "oracle", "cpu": cpu_model(),
             "sample": "first %d parameters, all %d workers, %d arrivals of the same schedule (%.1f s)"
                       % (n_slice, W, n_steps - 8, dt)}
 
