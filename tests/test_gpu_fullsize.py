@@ -70,7 +70,8 @@ def run_quadratic_workload(name, modes, n_random):
         free_gpu()
 
 
-def run_buffer_workload(name, modes, n_random):
+def run_buffer_workload(name, modes, n_random, queue=0):
+    """queue > 0: the arrivals are applied as queues of that many per launch (the buffer-fed persistent kernel)."""
     cfg = ga_inputs.WORKLOADS[name]
     N, W, T, seed = cfg["N"], cfg["W"], cfg["T"], cfg["seed"]
     bounds = np.cumsum(ga_inputs.tensor_sizes(N, cfg["n_tensors"], seed))[:-1] if "n_tensors" in cfg else ()
@@ -82,10 +83,11 @@ def run_buffer_workload(name, modes, n_random):
     dist = ga_inputs.DIST_CODES[cfg["dist"]]
     sched = ga.ga_simulate_schedule(W, T, dist, cfg["sigma"], seed)
     assert np.array_equal(sched, oracle.simulate_schedule(W, T, dist, cfg["sigma"], seed))
-    src = ga.buffer_source(bufs, ga.GA_PICK_BY_WORKER if by_worker else ga.GA_PICK_BY_ARRIVAL)
+    src = ga.buffer_source(bufs, ga.GA_PICK_BY_WORKER if by_worker else ga.GA_PICK_BY_ARRIVAL, persistent=queue > 0)
     for mode in modes:
         M = ga.Master(N, W, eta=cfg["eta"], gamma=cfg["gamma"], mode=mode)
-        M.run_schedule(sched, src)
+        for done in range(0, T, queue if queue else T):
+            M.run_schedule(sched[done:done + (queue if queue else T)], src)
         O = oracle.Master(idx.size, W, ORACLE_MODE[mode], oracle.Hyper(cfg["eta"], cfg["gamma"]))
         O.run_buffers(sched, bufs_s, pick_by_worker=by_worker)
         check_sample(M, O, idx_dev, "%s mode %d" % (name, mode))
@@ -136,6 +138,10 @@ def test_cfg2_sampled():
 
 def test_cfg3_sampled():
     run_buffer_workload("cfg3", [ga.GA_MODE_GA, ga.GA_MODE_GA_HINGE], n_random=20000)
+
+
+def test_cfg3_queues_sampled():
+    run_buffer_workload("cfg3", [ga.GA_MODE_GA], n_random=20000, queue=250)
 
 
 def test_cfg4_sampled():
