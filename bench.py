@@ -250,7 +250,13 @@ def bench_queue(args, cfg, torch, ga, ga_inputs):
     desc = ("%s: N=%d float parameters, %d workers, %s iteration times, %d %s gradient buffers picked by %s, queues of "
             "%d arrivals per launch, family %s, mode %s" % (args.workload, N, W, cfg["dist"], cfg["n_bufs"],
                                                             cfg["grad_dtype"], cfg["pick"], Q, args.family, args.mode))
-    extra = {"theta_finite": bool(torch.isfinite(M.theta()).all().item()),
+    theta = M.theta()
+    if args.calibration_copy:
+        dst = torch.empty(N, dtype=torch.float32, device=dev)
+        for _ in range(3):
+            dst.copy_(theta)
+        torch.cuda.synchronize()
+    extra = {"theta_finite": bool(torch.isfinite(theta).all().item()),
              "mean_gap_last": None if last_diag is None else last_diag["mean_graw"] + 1.0}
     return wall, roof, desc, extra
 
