@@ -116,14 +116,28 @@ __global__ __launch_bounds__(kBlock) void diag_kernel(const float* __restrict__ 
                                                       DiagPartial* __restrict__ partials) {
     const uint64_t n4 = N >> 2;
     DiagAcc acc = {0.0, 0u, 0u, 0u};
-    for (uint64_t q = (uint64_t)blockIdx.x * kBlock + threadIdx.x; q < n4; q += (uint64_t)gridDim.x * kBlock) {
-        const f32x4 th = reinterpret_cast<const f32x4*>(theta)[q];
-        const f32x4 s = reinterpret_cast<const f32x4*>(snap)[q];
-        const f32x4 mm = reinterpret_cast<const f32x4*>(m)[q];
-        diag_one(acc, th.x, s.x, mm.x, inv_bc, eta_max, eps);
-        diag_one(acc, th.y, s.y, mm.y, inv_bc, eta_max, eps);
-        diag_one(acc, th.z, s.z, mm.z, inv_bc, eta_max, eps);
-        diag_one(acc, th.w, s.w, mm.w, inv_bc, eta_max, eps);
+    constexpr int U = 4;   // groups in flight per thread; the accumulation keeps its order
+    const uint64_t stride = (uint64_t)gridDim.x * kBlock;
+    for (uint64_t q0 = (uint64_t)blockIdx.x * kBlock + threadIdx.x; q0 < n4; q0 += U * stride) {
+        f32x4 th[U], s[U], mm[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint64_t q = q0 + u * stride;
+            if (q < n4) {
+                th[u] = load4<false>(theta, q);
+                s[u] = load4<true>(snap, q);
+                mm[u] = load4<true>(m, q);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (q0 + u * stride < n4) {
+                diag_one(acc, th[u].x, s[u].x, mm[u].x, inv_bc, eta_max, eps);
+                diag_one(acc, th[u].y, s[u].y, mm[u].y, inv_bc, eta_max, eps);
+                diag_one(acc, th[u].z, s[u].z, mm[u].z, inv_bc, eta_max, eps);
+                diag_one(acc, th[u].w, s[u].w, mm[u].w, inv_bc, eta_max, eps);
+            }
+        }
     }
     if (blockIdx.x == 0 && threadIdx.x < (N & 3)) {
         const uint64_t j = 4 * n4 + threadIdx.x;
