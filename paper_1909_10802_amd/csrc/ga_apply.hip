@@ -15,6 +15,11 @@ namespace {
 // contiguous 128-bit loads and stores per array.  All loads of a thread are
 // issued before the first dependent operation.
 // ---------------------------------------------------------------------------
+// Beyond the size where theta and v stay in the memory-side cache every array is streamed: theta takes the
+// non-temporal hint too (measured on 350 M parameters: 5.91 -> 6.05 TB/s together with one group per thread).
+#ifndef GA_STREAM_THETA
+#define GA_STREAM_THETA 1
+#endif
 template <int MODE, int DT, bool KEEP_M, bool SNAP, bool ALIGNED, bool STREAM_V, int U>
 __global__ __launch_bounds__(kBlock) void apply_kernel(float* __restrict__ theta, float* __restrict__ v,
                                                        float* __restrict__ m, float* __restrict__ snap,
@@ -30,7 +35,7 @@ __global__ __launch_bounds__(kBlock) void apply_kernel(float* __restrict__ theta
         mm[u] = f32x4{0.f, 0.f, 0.f, 0.f};
         ss[u] = f32x4{0.f, 0.f, 0.f, 0.f};
         if (q < n4) {
-            th[u] = load4<false>(theta, q);
+            th[u] = load4<STREAM_V && GA_STREAM_THETA>(theta, q);
             vv[u] = load4<STREAM_V>(v, q);
             if constexpr (KEEP_M) mm[u] = load4<true>(m, q);
             if constexpr (GAP) ss[u] = load4<true>(snap, q);
@@ -42,7 +47,7 @@ __global__ __launch_bounds__(kBlock) void apply_kernel(float* __restrict__ theta
         const uint64_t q = base + (uint64_t)u * kBlock;
         if (q < n4) {
             update4<MODE, KEEP_M>(th[u], vv[u], mm[u], ss[u], gg[u], c);
-            store4<false>(theta, q, th[u]);
+            store4<STREAM_V && GA_STREAM_THETA>(theta, q, th[u]);
             store4<STREAM_V>(v, q, vv[u]);
             if constexpr (KEEP_M) store4<true>(m, q, mm[u]);
             if constexpr (SNAP) store4<true>(snap, q, th[u]);
@@ -132,21 +137,26 @@ __global__ __launch_bounds__(kBlock) void family_apply_kernel(float* __restrict_
 // Dispatch of the apply kernel over (mode, dtype, keep_m, aligned).
 // ---------------------------------------------------------------------------
 constexpr int kApplyU = 2;
+#ifndef GA_APPLY_U_STREAM
+#define GA_APPLY_U_STREAM 1
+#endif
+constexpr int kApplyUStream = GA_APPLY_U_STREAM;   // groups per thread when nothing stays in the memory-side cache
 
 
 template <int MODE, int DT, bool KEEP_M, bool SNAP, bool ALIGNED>
 hipError_t launch_apply_t(const StatePtrs& st, float* snap, const void* g, uint64_t N, const StepConst& c,
                           hipStream_t stream) {
     const uint64_t n4 = N >> 2;
-    const uint64_t per_block = (uint64_t)kBlock * kApplyU;
+    const bool stream_v = N > kKeepVMaxN;
+    const uint64_t per_block = (uint64_t)kBlock * (stream_v ? kApplyUStream : kApplyU);
     const uint64_t blocks = (n4 + per_block - 1) / per_block;
     if (blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
     const dim3 grid(blocks == 0 ? 1u : (uint32_t)blocks), block(kBlock);
-    if (N <= kKeepVMaxN)
+    if (!stream_v)
         hipLaunchKernelGGL((apply_kernel<MODE, DT, KEEP_M, SNAP, ALIGNED, false, kApplyU>), grid, block, 0, stream,
                            st.theta, st.v, st.m, snap, g, N, c);
     else
-        hipLaunchKernelGGL((apply_kernel<MODE, DT, KEEP_M, SNAP, ALIGNED, true, kApplyU>), grid, block, 0, stream,
+        hipLaunchKernelGGL((apply_kernel<MODE, DT, KEEP_M, SNAP, ALIGNED, true, kApplyUStream>), grid, block, 0, stream,
                            st.theta, st.v, st.m, snap, g, N, c);
     return hipGetLastError();
 }
