@@ -30,7 +30,7 @@ VALU_PER_UPDATE = {"ga": 106.7, "ga_hinge": 106.7}
 # HBM-side bytes per fused-update launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE scaled by a copy of
 # known size; profiles/apply_kernel_cfg3.md), valid for the kernel source with this hash only
 TRAFFIC = {
-    ("cfg3", "ga"): {"bytes": 920017839, "read": 511097898, "written": 408919941, "kernels_sha256": "494176d27106a6e4"},
+    ("cfg3", "ga"): {"bytes": 920026388, "read": 511104880, "written": 408921508, "kernels_sha256": "720ea4dcbf4e9080"},
 }
 BYTES_PER_UPDATE = {           # algorithmic bytes per parameter per arrival, fused update
     ("ga", "f32"): 36, ("ga", "bf16"): 34, ("ga_hinge", "f32"): 36, ("ga_hinge", "bf16"): 34,

@@ -15,12 +15,9 @@ namespace {
 // contiguous 128-bit loads and stores per array.  All loads of a thread are
 // issued before the first dependent operation.
 // ---------------------------------------------------------------------------
-// Beyond the size where theta and v stay in the memory-side cache every array is streamed: theta takes the
-// non-temporal hint too (measured on 350 M parameters: 5.91 -> 6.05 TB/s together with one group per thread).
-#ifndef GA_STREAM_THETA
-#define GA_STREAM_THETA 1
-#endif
-template <int MODE, int DT, bool KEEP_M, bool SNAP, bool ALIGNED, bool STREAM_V, int U>
+// STREAM: 0 theta and v stay in the memory-side cache; 1 only theta fits, v is streamed; 2 nothing fits, every array
+// takes the non-temporal hint (measured on 350 M parameters: 5.91 -> 6.05 TB/s together with one group per thread).
+template <int MODE, int DT, bool KEEP_M, bool SNAP, bool ALIGNED, int STREAM, int U>
 __global__ __launch_bounds__(kBlock) void apply_kernel(float* __restrict__ theta, float* __restrict__ v,
                                                        float* __restrict__ m, float* __restrict__ snap,
                                                        const void* __restrict__ g, uint64_t N, StepConst c) {
@@ -35,8 +32,8 @@ __global__ __launch_bounds__(kBlock) void apply_kernel(float* __restrict__ theta
         mm[u] = f32x4{0.f, 0.f, 0.f, 0.f};
         ss[u] = f32x4{0.f, 0.f, 0.f, 0.f};
         if (q < n4) {
-            th[u] = load4<STREAM_V && GA_STREAM_THETA>(theta, q);
-            vv[u] = load4<STREAM_V>(v, q);
+            th[u] = load4<STREAM == 2>(theta, q);
+            vv[u] = load4<STREAM >= 1>(v, q);
             if constexpr (KEEP_M) mm[u] = load4<true>(m, q);
             if constexpr (GAP) ss[u] = load4<true>(snap, q);
             gg[u] = load_g4<DT, ALIGNED>(g, q);
@@ -47,8 +44,8 @@ __global__ __launch_bounds__(kBlock) void apply_kernel(float* __restrict__ theta
         const uint64_t q = base + (uint64_t)u * kBlock;
         if (q < n4) {
             update4<MODE, KEEP_M>(th[u], vv[u], mm[u], ss[u], gg[u], c);
-            store4<STREAM_V && GA_STREAM_THETA>(theta, q, th[u]);
-            store4<STREAM_V>(v, q, vv[u]);
+            store4<STREAM == 2>(theta, q, th[u]);
+            store4<STREAM >= 1>(v, q, vv[u]);
             if constexpr (KEEP_M) store4<true>(m, q, mm[u]);
             if constexpr (SNAP) store4<true>(snap, q, th[u]);
         }
@@ -147,16 +144,19 @@ template <int MODE, int DT, bool KEEP_M, bool SNAP, bool ALIGNED>
 hipError_t launch_apply_t(const StatePtrs& st, float* snap, const void* g, uint64_t N, const StepConst& c,
                           hipStream_t stream) {
     const uint64_t n4 = N >> 2;
-    const bool stream_v = N > kKeepVMaxN;
-    const uint64_t per_block = (uint64_t)kBlock * (stream_v ? kApplyUStream : kApplyU);
+    const int regime = N <= kKeepVMaxN ? 0 : N <= kKeepThetaMaxN ? 1 : 2;
+    const uint64_t per_block = (uint64_t)kBlock * (regime == 2 ? kApplyUStream : kApplyU);
     const uint64_t blocks = (n4 + per_block - 1) / per_block;
     if (blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
     const dim3 grid(blocks == 0 ? 1u : (uint32_t)blocks), block(kBlock);
-    if (!stream_v)
-        hipLaunchKernelGGL((apply_kernel<MODE, DT, KEEP_M, SNAP, ALIGNED, false, kApplyU>), grid, block, 0, stream,
+    if (regime == 0)
+        hipLaunchKernelGGL((apply_kernel<MODE, DT, KEEP_M, SNAP, ALIGNED, 0, kApplyU>), grid, block, 0, stream,
+                           st.theta, st.v, st.m, snap, g, N, c);
+    else if (regime == 1)
+        hipLaunchKernelGGL((apply_kernel<MODE, DT, KEEP_M, SNAP, ALIGNED, 1, kApplyU>), grid, block, 0, stream,
                            st.theta, st.v, st.m, snap, g, N, c);
     else
-        hipLaunchKernelGGL((apply_kernel<MODE, DT, KEEP_M, SNAP, ALIGNED, true, kApplyUStream>), grid, block, 0, stream,
+        hipLaunchKernelGGL((apply_kernel<MODE, DT, KEEP_M, SNAP, ALIGNED, 2, kApplyUStream>), grid, block, 0, stream,
                            st.theta, st.v, st.m, snap, g, N, c);
     return hipGetLastError();
 }

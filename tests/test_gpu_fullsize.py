@@ -144,6 +144,28 @@ def test_cfg3_queues_sampled():
     run_buffer_workload("cfg3", [ga.GA_MODE_GA], n_random=20000, queue=250)
 
 
+@pytest.mark.parametrize("N", [33_000_003, 70_000_001], ids=["33M", "70M"])
+def test_sizes_where_only_theta_stays_cached(N):
+    # between the size where theta and v both fit the memory-side cache and the size where nothing does,
+    # the fused update keeps theta cached and streams v: same arithmetic, another instantiation
+    W, T, seed, n_bufs = 4, 14, 12, 2
+    idx = ga_inputs.sample_indices(N, 8000, seed)
+    idx_dev = torch.from_numpy(idx.astype(np.int64)).to(DEV)
+    bufs = ga_inputs.device_gradient_buffers(n_bufs, N, seed, 0.3, "f32", DEV)
+    bufs_s = np.stack([host(b[idx_dev]) for b in bufs])
+    sched = ga.ga_simulate_schedule(W, T, ga.GA_DIST_EXP, 1.0, seed)
+    for mode in (ga.GA_MODE_GA, ga.GA_MODE_SA):
+        M = ga.Master(N, W, mode=mode, track_gap=True)
+        M.run_schedule(sched, ga.buffer_source(bufs, ga.GA_PICK_BY_WORKER))
+        O = oracle.Master(idx.size, W, ORACLE_MODE[mode], oracle.Hyper(), track_gap=True)
+        O.run_buffers(sched, bufs_s, pick_by_worker=True)
+        check_sample(M, O, idx_dev, "N=%d mode %d" % (N, mode))
+        del M
+        free_gpu()
+    del bufs
+    free_gpu()
+
+
 def test_cfg4_sampled():
     run_quadratic_workload("cfg4", [ga.GA_MODE_GA, ga.GA_MODE_GA_HINGE], n_random=8000)
 
