@@ -238,3 +238,31 @@ def test_export_import_state_resumes_bit_identically(family):
     assert e.value.status == ga.GA_ERR_ARG
     with pytest.raises(ga.GaError):
         ga.ga_import_state(C2.ctx, ckpt, 3, np.full(W, 9, np.uint64))
+
+
+@pytest.mark.parametrize("family", FAMILIES, ids=["dana", "adam"])
+def test_beyond_the_cache_resident_size_sampled(family):
+    # past 30 M parameters the second state array is streamed (another instantiation of the fused kernel)
+    N, W, T, seed = 33_000_003, 3, 12, 14
+    eta = 0.1 if family == ga.GA_FAMILY_DANA else 0.01
+    idx = ga_inputs.sample_indices(N, 8000, seed)
+    idx_dev = torch.from_numpy(idx.astype(np.int64)).to(DEV)
+    bufs = ga_inputs.device_gradient_buffers(2, N, seed, 0.3, "f32", DEV)
+    bufs_s = np.stack([host(b[idx_dev]) for b in bufs])
+    sched = ga.ga_simulate_schedule(W, T, ga.GA_DIST_EXP, 1.0, seed)
+    M = ga.Master(N, W, eta=eta, gamma=0.9, mode=ga.GA_MODE_GA, family=family)
+    M.run_schedule(sched, ga.buffer_source(bufs, ga.GA_PICK_BY_WORKER))
+    if family == ga.GA_FAMILY_DANA:
+        O = oracle.DanaMaster(idx.size, W, oracle.MODE_GA, oracle.Hyper(eta, 0.9))
+    else:
+        O = oracle.AdamMaster(idx.size, W, oracle.MODE_GA, oracle.Hyper(eta, 0.0))
+    O.run_buffers(sched, bufs_s, pick_by_worker=True)
+    theta = host(M.theta()[idx_dev])
+    assert bits_equal(theta, O.theta) == 0
+    assert_step_close(host(M.v()[idx_dev]), O.vsum if family == ga.GA_FAMILY_DANA else O.m1, "x")
+    assert_step_close(host(M.m()[idx_dev]), O.m, "m")
+    for w in range(W):
+        assert_step_close(host(M.snapshot(w)[idx_dev]), O.snaps[w], "snapshot %d" % w)
+    del M, bufs
+    gc.collect()
+    torch.cuda.empty_cache()

@@ -179,3 +179,30 @@ def test_state_written_between_calls_is_seen_by_the_next_arrival():
     M.run_schedule(second, src)
     O.run_buffers(second, bufs)
     assert check(M, O, "after put") == 0
+
+
+@pytest.mark.parametrize("scope", ["layer", "global"])
+def test_beyond_the_cache_resident_size(scope):
+    # past 30 M parameters v is streamed in the update pass (another instantiation); whole vector against the oracle
+    N, W, T, seed = 33_000_003, 3, 7, 15
+    sizes = ga_inputs.tensor_sizes(N, 40, seed)
+    bufs = ga_inputs.device_gradient_buffers(2, N, seed, 0.3, "f32", DEV)
+    ref = np.stack([host(b) for b in bufs])
+    sched = np.array([0, 1, 1, 2, 0, 2, 1], dtype=np.uint32)
+    if scope == "layer":
+        M = ga.Master(N, W, mode=ga.GA_MODE_GA, layer_sizes=sizes)
+        O = oracle.LayerwiseMaster(N, W, oracle.MODE_GA, oracle.Hyper(), sizes)
+    else:
+        M = ga.Master(N, W, mode=ga.GA_MODE_GA, gap_scope=ga.GA_GAP_GLOBAL)
+        O = oracle.LayerwiseMaster(N, W, oracle.MODE_GA, oracle.Hyper(), None)
+    M.run_schedule(sched, ga.buffer_source(bufs, ga.GA_PICK_BY_WORKER))
+    O.run_buffers(sched, ref)
+    theta = host(M.theta())
+    assert rel_l2(theta, O.theta) <= RTOL_TRAJ_L2
+    assert_step_close(theta, O.theta, "theta")
+    assert_step_close(host(M.v()), O.v, "v")
+    assert_step_close(host(M.m()), O.m, "m")
+    assert_step_close(M.layer_gaps(), O.last_gaps, "layer gaps")
+    del M, bufs
+    gc.collect()
+    torch.cuda.empty_cache()
