@@ -48,8 +48,9 @@ def test_queue_equals_oracle_and_per_arrival_kernel(mode, dtype, N):
 @pytest.mark.parametrize("family", [ga.GA_FAMILY_DANA, ga.GA_FAMILY_ADAM], ids=["dana", "adam"])
 @pytest.mark.parametrize("mode", [ga.GA_MODE_ASGD, ga.GA_MODE_SA, ga.GA_MODE_GA, ga.GA_MODE_GA_HINGE], ids=["none", "sa", "ga", "ga_hinge"])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-def test_queue_families(family, mode, dtype):
-    N, W, T, n_bufs = 15_003, 5, 120, 3
+@pytest.mark.parametrize("N", [15_003, 2_100_003], ids=["two_per_thread", "four_per_thread"])
+def test_queue_families(family, mode, dtype, N):
+    W, T, n_bufs = 5, 120 if N < 10**6 else 16, 3
     eta = 0.1 if family == ga.GA_FAMILY_DANA else 0.01
     ref, dbufs = make_bufs(n_bufs, N, 9, dtype)
     sched = ga.ga_simulate_schedule(W, T, seed=9)
