@@ -12,6 +12,11 @@ Prints ONE JSON line: whole-job throughput in G parameter-updates/s, the
 roofline of the fused-update kernel (algorithmic bytes per launch / average
 launch duration measured with events on the kernel's stream) and the CPU
 oracle timed on a bounded sample of the same workload.
+
+At 25.6 M parameters most of theta, v and m (306 MB) is served by the 256 MiB
+memory-side cache, so the default run adds a second, shorter leg of the same
+kernel where the state is far larger than that cache (`roofline_streaming`:
+N = 151,000,000 float parameters, float gradients, GA), timed the same way.
 """
 import argparse
 import json
@@ -24,11 +29,14 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+RESIDENT_BYTES = 240 << 20     # part of theta, v, m the fused update keeps in the memory-side cache (kResidentBytes, csrc/ga_device.h)
+STREAMING_LEG = dict(N=151_000_000, W=8, n_bufs=8, steps=300, warmup=24)   # Transformer-XL-base size (Sec. 6)
 ALU_PEAK_TLOPS = 78.65         # fp32 vector 157.3 TFLOP/s / 2 flop per lane-operation
 # VALU lane-operations per parameter-update of the persistent kernel (SQ_INSTS_VALU * 64 / updates, profiles/)
 VALU_PER_UPDATE = {"ga": 106.7, "ga_hinge": 106.7}
-# HBM-side bytes per fused-update launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE scaled by a copy of
-# known size; profiles/apply_kernel_cfg3.md), valid for the kernel source with this hash only
+# Bytes per fused-update launch between the L2 and the fabric, measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE
+# scaled by a copy of known size; profiles/apply_kernel_cfg3.md).  The counters sit in front of the memory-side
+# cache, so hits in that cache are included.  Valid for the kernel source with this hash only.
 TRAFFIC = {
     ("cfg3", "ga"): {"bytes": 920026388, "read": 511104880, "written": 408921508, "kernels_sha256": "720ea4dcbf4e9080"},
 }
@@ -45,6 +53,11 @@ def parse():
     p.add_argument("--steps", type=int, default=None, help="arrivals to time (default: the workload's own count)")
     p.add_argument("--warmup", type=int, default=100)
     p.add_argument("--workload", default="cfg3", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+    p.add_argument("--n", type=int, default=None, help="override the workload's number of parameters")
+    p.add_argument("--workers", type=int, default=None, help="override the workload's number of workers")
+    p.add_argument("--bufs", type=int, default=None, help="buffer workloads: override the number of gradient buffers")
+    p.add_argument("--no-streaming-leg", action="store_true",
+                   help="default workload only: skip the second leg at N = 151,000,000")
     p.add_argument("--family", default="momentum", choices=["momentum", "dana", "adam"],
                    help="master algorithm family: Alg. 2-5, Alg. 6-8 or Alg. 9-11")
     p.add_argument("--gap-scope", default="parameter", choices=["parameter", "layer", "global"],
@@ -196,8 +209,16 @@ def bench_fused(args, cfg, torch, ga, ga_inputs):
         torch.cuda.synchronize()
     t = TRAFFIC.get((args.workload, args.mode))
     traffic = t["bytes"] if t and t["kernels_sha256"] == kernels_hash() and args.gap_scope == "parameter" else None
+    # of the algorithmic bytes, the part that HBM itself has to serve: the kernel keeps a leading part of theta, v, m
+    # (RESIDENT_BYTES in all; each kept float saves one read and one write per arrival) in the memory-side cache
+    n_hot = {"momentum": 3 if (args.mode in ("ga", "ga_hinge") or args.diag_every > 0) else 2}.get(args.family, 2)
+    kept = min(RESIDENT_BYTES, 4 * N * n_hot)
+    hbm_only_bpu = bpu - 2.0 * kept / N
     roof = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
             "traffic": traffic if args.family == "momentum" else None,
+            "hbm_only_bytes_per_update": hbm_only_bpu, "hbm_only_GBs": hbm_only_bpu * N / (kernel_ms * 1e-3) / 1e9,
+            "hbm_only_frac": hbm_only_bpu * N / (kernel_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "cache_resident_bytes": kept,
             "kernel": ("layer_gap_kernel + layer_apply_kernel (+ layer_partial_kernel on the first arrival of a call)" if args.gap_scope != "parameter"
                        else "apply_kernel" if args.family == "momentum" else "family_apply_kernel"), "bytes_per_update": bpu, "avg_launch_ms": kernel_ms,
             "algorithmic_bytes_per_launch": int(round(bpu * N)),
@@ -208,7 +229,27 @@ def bench_fused(args, cfg, torch, ga, ga_inputs):
                                                                      args.mode))
     extra = {"hbm_pct_of_peak": 100.0 * achieved / HBM_PEAK_GBS, "theta_finite": finite,
              "mean_gap_last": None if last_diag is None else last_diag["mean_graw"] + 1.0}
+    M.close()
+    del M, bufs, src, theta
+    torch.cuda.empty_cache()
     return wall, roof, desc, extra
+
+
+def streaming_leg(args, cfg, torch, ga, ga_inputs):
+    """The fused update where the state is far larger than the memory-side cache: the same kernel, gradient recipe
+    and timing as the main leg at N = 151,000,000 (float gradients, a few workers so that it allocates fast)."""
+    leg = dict(STREAMING_LEG)
+    c2 = dict(cfg, N=leg["N"], W=leg["W"], n_bufs=leg["n_bufs"])
+    a2 = argparse.Namespace(**vars(args))
+    a2.steps, a2.warmup, a2.diag_every, a2.calibration_copy = leg["steps"], leg["warmup"], 0, False
+    wall, roof, desc, _ = bench_fused(a2, c2, torch, ga, ga_inputs)
+    keys = ("achieved", "peak", "unit", "frac", "kernel", "bytes_per_update", "avg_launch_ms",
+            "algorithmic_bytes_per_launch", "hbm_only_bytes_per_update", "hbm_only_GBs", "hbm_only_frac",
+            "cache_resident_bytes", "copy_GBs", "frac_of_copy")
+    out = {"N": leg["N"], "n_workers": leg["W"], "steps": leg["steps"], "warmup": leg["warmup"], "workload": desc,
+           "G_param_updates_per_s": leg["N"] * leg["steps"] / wall / 1e9}
+    out.update({k: roof[k] for k in keys})
+    return out
 
 
 def bench_queue(args, cfg, torch, ga, ga_inputs):
@@ -338,6 +379,14 @@ def main():
     import paper_1909_10802_amd as ga
 
     cfg = dict(ga_inputs.WORKLOADS[args.workload])
+    if args.n is not None:
+        cfg["N"] = args.n
+    if args.workers is not None:
+        cfg["W"] = args.workers
+    if args.bufs is not None:
+        if cfg["source"] != "buffers":
+            sys.exit("bench.py: --bufs is for the gradient-buffer workloads")
+        cfg["n_bufs"] = args.bufs
     if args.steps is None:
         args.steps = cfg["T"]
     torch.cuda.set_device(0)
@@ -363,6 +412,10 @@ def main():
         "roofline": roof,
     }
     out.update(extra)
+    default_leg = (run is bench_fused and args.workload == "cfg3" and args.family == "momentum" and args.mode == "ga"
+                   and args.gap_scope == "parameter" and args.n is None)
+    if default_leg and not args.no_streaming_leg:
+        out["roofline_streaming"] = streaming_leg(args, cfg, torch, ga, ga_inputs)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = (cpu_baseline if fused else cpu_baseline_quadratic)(cfg, args.mode, args.cpu_slice,
                                                                                   args.cpu_steps)

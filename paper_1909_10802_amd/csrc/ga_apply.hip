@@ -14,17 +14,16 @@ namespace {
 // parameters, 256 groups apart, so that every wavefront issues 1 KiB
 // contiguous 128-bit loads and stores per array.  All loads of a thread are
 // issued before the first dependent operation.
+//
+// The gradient, the snapshot and, by default, every other array are accessed with the non-temporal
+// hint.  The leading blocks of the grid (thresholds in `keep`) access theta, v and m without it, so that
+// this part of the state is served by the memory-side cache at the next arrival (ga_device.h).
 // ---------------------------------------------------------------------------
-// STREAM: 0 theta and v stay in the memory-side cache; 1 only theta fits, v is streamed; 2 nothing fits, every array
-// takes the non-temporal hint (measured on 350 M parameters: 5.91 -> 6.05 TB/s together with one group per thread).
-template <int MODE, int DT, bool KEEP_M, bool SNAP, bool ALIGNED, int STREAM, int U>
-__global__ __launch_bounds__(kBlock) void apply_kernel(float* __restrict__ theta, float* __restrict__ v,
-                                                       float* __restrict__ m, float* __restrict__ snap,
-                                                       const void* __restrict__ g, uint64_t N, StepConst c) {
+template <int MODE, int DT, bool KEEP_M, bool SNAP, bool ALIGNED, int U, bool NT_TH, bool NT_V, bool NT_M>
+__device__ __forceinline__ void apply_tile(float* __restrict__ theta, float* __restrict__ v, float* __restrict__ m,
+                                           float* __restrict__ snap, const void* __restrict__ g, uint64_t n4,
+                                           uint64_t base, const StepConst& c) {
     constexpr bool GAP = is_gap(MODE);
-    const uint64_t n4 = N >> 2;
-    const uint64_t base = (uint64_t)blockIdx.x * (kBlock * U) + threadIdx.x;
-
     f32x4 th[U], vv[U], mm[U], ss[U], gg[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -32,9 +31,9 @@ __global__ __launch_bounds__(kBlock) void apply_kernel(float* __restrict__ theta
         mm[u] = f32x4{0.f, 0.f, 0.f, 0.f};
         ss[u] = f32x4{0.f, 0.f, 0.f, 0.f};
         if (q < n4) {
-            th[u] = load4<STREAM == 2>(theta, q);
-            vv[u] = load4<STREAM >= 1>(v, q);
-            if constexpr (KEEP_M) mm[u] = load4<true>(m, q);
+            th[u] = load4<NT_TH>(theta, q);
+            vv[u] = load4<NT_V>(v, q);
+            if constexpr (KEEP_M) mm[u] = load4<NT_M>(m, q);
             if constexpr (GAP) ss[u] = load4<true>(snap, q);
             gg[u] = load_g4<DT, ALIGNED>(g, q);
         }
@@ -44,15 +43,33 @@ __global__ __launch_bounds__(kBlock) void apply_kernel(float* __restrict__ theta
         const uint64_t q = base + (uint64_t)u * kBlock;
         if (q < n4) {
             update4<MODE, KEEP_M>(th[u], vv[u], mm[u], ss[u], gg[u], c);
-            store4<STREAM == 2>(theta, q, th[u]);
-            store4<STREAM >= 1>(v, q, vv[u]);
-            if constexpr (KEEP_M) store4<true>(m, q, mm[u]);
+            store4<NT_TH>(theta, q, th[u]);
+            store4<NT_V>(v, q, vv[u]);
+            if constexpr (KEEP_M) store4<NT_M>(m, q, mm[u]);
             if constexpr (SNAP) store4<true>(snap, q, th[u]);
         }
     }
+}
+
+template <int MODE, int DT, bool KEEP_M, bool SNAP, bool ALIGNED, int U>
+__global__ __launch_bounds__(kBlock) void apply_kernel(float* __restrict__ theta, float* __restrict__ v,
+                                                       float* __restrict__ m, float* __restrict__ snap,
+                                                       const void* __restrict__ g, uint64_t N, StepConst c,
+                                                       Residency keep) {
+    constexpr bool GAP = is_gap(MODE);
+    const uint64_t n4 = N >> 2;
+    const uint32_t b = blockIdx.x;
+    const uint64_t base = (uint64_t)b * (kBlock * U) + threadIdx.x;
+#define GA_APPLY_TILE(NT_TH, NT_V, NT_M) \
+    apply_tile<MODE, DT, KEEP_M, SNAP, ALIGNED, U, NT_TH, NT_V, NT_M>(theta, v, m, snap, g, n4, base, c)
+    if (b >= keep.theta) GA_HINT_PATH("all streamed", GA_APPLY_TILE(true, true, true));
+    else if (b >= keep.v) GA_HINT_PATH("theta kept", GA_APPLY_TILE(false, true, true));
+    else if (!KEEP_M || b >= keep.m) GA_HINT_PATH("theta and v kept", GA_APPLY_TILE(false, false, true));
+    else GA_HINT_PATH("theta, v and m kept", GA_APPLY_TILE(false, false, false));
+#undef GA_APPLY_TILE
 
     // ragged tail: the last N % 4 parameters, one per thread of block 0
-    if (blockIdx.x == 0 && threadIdx.x < (N & 3)) {
+    if (b == 0 && threadIdx.x < (N & 3)) {
         const uint64_t j = 4 * n4 + threadIdx.x;
         float t1 = theta[j], v1 = v[j], m1 = 0.0f, s1 = 0.0f;
         if constexpr (KEEP_M) m1 = m[j];
@@ -68,18 +85,15 @@ __global__ __launch_bounds__(kBlock) void apply_kernel(float* __restrict__ theta
 // ---------------------------------------------------------------------------
 // Fused update of one arrival for the DANA and ADAM families: the same launch
 // shape as apply_kernel with one more state array.  x: vsum | m1 (touched at
-// every arrival, kept in the memory-side cache when it fits); y: the arriving
-// worker's v_i (streamed) | v2.
+// every arrival); y: the arriving worker's v_i (always streamed) | v2.  The
+// leading blocks keep theta, then x, in the memory-side cache.
 // ---------------------------------------------------------------------------
-template <int FAMILY, int MODE, int DT, bool KEEP_M, bool SNAP, bool ALIGNED, bool STREAM_X, int U>
-__global__ __launch_bounds__(kBlock) void family_apply_kernel(float* __restrict__ theta, float* __restrict__ x,
-                                                              float* __restrict__ y, float* __restrict__ m,
-                                                              float* __restrict__ snap,
-                                                              const void* __restrict__ g, uint64_t N, StepConst c) {
+template <int FAMILY, int MODE, int DT, bool KEEP_M, bool SNAP, bool ALIGNED, int U, bool NT_TH, bool NT_X>
+__device__ __forceinline__ void family_tile(float* __restrict__ theta, float* __restrict__ x, float* __restrict__ y,
+                                            float* __restrict__ m, float* __restrict__ snap,
+                                            const void* __restrict__ g, uint64_t n4, uint64_t base,
+                                            const StepConst& c) {
     constexpr bool GAP = is_gap(MODE);
-    const uint64_t n4 = N >> 2;
-    const uint64_t base = (uint64_t)blockIdx.x * (kBlock * U) + threadIdx.x;
-
     f32x4 th[U], xx[U], yy[U], mm[U], ss[U], gg[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -87,8 +101,8 @@ __global__ __launch_bounds__(kBlock) void family_apply_kernel(float* __restrict_
         mm[u] = f32x4{0.f, 0.f, 0.f, 0.f};
         ss[u] = f32x4{0.f, 0.f, 0.f, 0.f};
         if (q < n4) {
-            th[u] = load4<false>(theta, q);
-            xx[u] = load4<STREAM_X>(x, q);
+            th[u] = load4<NT_TH>(theta, q);
+            xx[u] = load4<NT_X>(x, q);
             yy[u] = load4<true>(y, q);
             if constexpr (KEEP_M) mm[u] = load4<true>(m, q);
             if constexpr (GAP) ss[u] = load4<true>(snap, q);
@@ -107,15 +121,33 @@ __global__ __launch_bounds__(kBlock) void family_apply_kernel(float* __restrict_
                 else out[e] = adam_one<MODE, KEEP_M>(t1, x1, y1, m1, ss[u][e], gg[u][e], c);
                 th[u][e] = t1; xx[u][e] = x1; yy[u][e] = y1; mm[u][e] = m1;
             }
-            store4<false>(theta, q, th[u]);
-            store4<STREAM_X>(x, q, xx[u]);
+            store4<NT_TH>(theta, q, th[u]);
+            store4<NT_X>(x, q, xx[u]);
             store4<true>(y, q, yy[u]);
             if constexpr (KEEP_M) store4<true>(m, q, mm[u]);
             if constexpr (SNAP) store4<true>(snap, q, out);
         }
     }
+}
 
-    if (blockIdx.x == 0 && threadIdx.x < (N & 3)) {
+template <int FAMILY, int MODE, int DT, bool KEEP_M, bool SNAP, bool ALIGNED, int U>
+__global__ __launch_bounds__(kBlock) void family_apply_kernel(float* __restrict__ theta, float* __restrict__ x,
+                                                              float* __restrict__ y, float* __restrict__ m,
+                                                              float* __restrict__ snap,
+                                                              const void* __restrict__ g, uint64_t N, StepConst c,
+                                                              Residency keep) {
+    constexpr bool GAP = is_gap(MODE);
+    const uint64_t n4 = N >> 2;
+    const uint32_t b = blockIdx.x;
+    const uint64_t base = (uint64_t)b * (kBlock * U) + threadIdx.x;
+#define GA_FAMILY_TILE(NT_TH, NT_X) \
+    family_tile<FAMILY, MODE, DT, KEEP_M, SNAP, ALIGNED, U, NT_TH, NT_X>(theta, x, y, m, snap, g, n4, base, c)
+    if (b >= keep.theta) GA_HINT_PATH("all streamed", GA_FAMILY_TILE(true, true));
+    else if (b >= keep.v) GA_HINT_PATH("theta kept", GA_FAMILY_TILE(false, true));
+    else GA_HINT_PATH("theta and x kept", GA_FAMILY_TILE(false, false));
+#undef GA_FAMILY_TILE
+
+    if (b == 0 && threadIdx.x < (N & 3)) {
         const uint64_t j = 4 * n4 + threadIdx.x;
         float t1 = theta[j], x1 = x[j], y1 = y[j], m1 = 0.0f, s1 = 0.0f, out;
         if constexpr (KEEP_M) m1 = m[j];
@@ -133,32 +165,29 @@ __global__ __launch_bounds__(kBlock) void family_apply_kernel(float* __restrict_
 // ---------------------------------------------------------------------------
 // Dispatch of the apply kernel over (mode, dtype, keep_m, aligned).
 // ---------------------------------------------------------------------------
-constexpr int kApplyU = 2;
-#ifndef GA_APPLY_U_STREAM
-#define GA_APPLY_U_STREAM 1
-#endif
-constexpr int kApplyUStream = GA_APPLY_U_STREAM;   // groups per thread when nothing stays in the memory-side cache
+// Two groups per thread up to this many parameters, one beyond (measured with a 240 MiB resident part:
+// 80 M +1.8 %, 100 M +0.7 %, 151 M -0.3 %, 250 M -1.2 % of HBM peak for two against one).
+constexpr uint64_t kTwoGroupsMaxN = (uint64_t)128 << 20;
 
+template <int MODE, int DT, bool KEEP_M, bool SNAP, bool ALIGNED, int U>
+hipError_t launch_apply_u(const StatePtrs& st, float* snap, const void* g, uint64_t N, const StepConst& c,
+                          hipStream_t stream) {
+    const uint64_t n4 = N >> 2;
+    const uint64_t per_block = (uint64_t)kBlock * U;
+    const uint64_t blocks = (n4 + per_block - 1) / per_block;
+    if (blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    const dim3 grid(blocks == 0 ? 1u : (uint32_t)blocks), block(kBlock);
+    const Residency keep = residency_for(grid.x, per_block * sizeof(f32x4), true, KEEP_M);
+    hipLaunchKernelGGL((apply_kernel<MODE, DT, KEEP_M, SNAP, ALIGNED, U>), grid, block, 0, stream, st.theta, st.v,
+                       st.m, snap, g, N, c, keep);
+    return hipGetLastError();
+}
 
 template <int MODE, int DT, bool KEEP_M, bool SNAP, bool ALIGNED>
 hipError_t launch_apply_t(const StatePtrs& st, float* snap, const void* g, uint64_t N, const StepConst& c,
                           hipStream_t stream) {
-    const uint64_t n4 = N >> 2;
-    const int regime = N <= kKeepVMaxN ? 0 : N <= kKeepThetaMaxN ? 1 : 2;
-    const uint64_t per_block = (uint64_t)kBlock * (regime == 2 ? kApplyUStream : kApplyU);
-    const uint64_t blocks = (n4 + per_block - 1) / per_block;
-    if (blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
-    const dim3 grid(blocks == 0 ? 1u : (uint32_t)blocks), block(kBlock);
-    if (regime == 0)
-        hipLaunchKernelGGL((apply_kernel<MODE, DT, KEEP_M, SNAP, ALIGNED, 0, kApplyU>), grid, block, 0, stream,
-                           st.theta, st.v, st.m, snap, g, N, c);
-    else if (regime == 1)
-        hipLaunchKernelGGL((apply_kernel<MODE, DT, KEEP_M, SNAP, ALIGNED, 1, kApplyU>), grid, block, 0, stream,
-                           st.theta, st.v, st.m, snap, g, N, c);
-    else
-        hipLaunchKernelGGL((apply_kernel<MODE, DT, KEEP_M, SNAP, ALIGNED, 2, kApplyUStream>), grid, block, 0, stream,
-                           st.theta, st.v, st.m, snap, g, N, c);
-    return hipGetLastError();
+    if (N <= kTwoGroupsMaxN) return launch_apply_u<MODE, DT, KEEP_M, SNAP, ALIGNED, 2>(st, snap, g, N, c, stream);
+    return launch_apply_u<MODE, DT, KEEP_M, SNAP, ALIGNED, 1>(st, snap, g, N, c, stream);
 }
 
 template <int MODE, bool KEEP_M, bool SNAP>
@@ -198,12 +227,9 @@ hipError_t launch_family_t(float* theta, float* x, float* y, float* m, float* sn
     const uint64_t blocks = (n4 + per_block - 1) / per_block;
     if (blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
     const dim3 grid(blocks == 0 ? 1u : (uint32_t)blocks), block(kBlock);
-    if (N <= kKeepVMaxN)
-        hipLaunchKernelGGL((family_apply_kernel<FAMILY, MODE, DT, KEEP_M, SNAP, ALIGNED, false, kFamilyU>), grid, block,
-                           0, stream, theta, x, y, m, snap, g, N, c);
-    else
-        hipLaunchKernelGGL((family_apply_kernel<FAMILY, MODE, DT, KEEP_M, SNAP, ALIGNED, true, kFamilyU>), grid, block,
-                           0, stream, theta, x, y, m, snap, g, N, c);
+    const Residency keep = residency_for(grid.x, per_block * sizeof(f32x4), true, false);
+    hipLaunchKernelGGL((family_apply_kernel<FAMILY, MODE, DT, KEEP_M, SNAP, ALIGNED, kFamilyU>), grid, block, 0,
+                       stream, theta, x, y, m, snap, g, N, c, keep);
     return hipGetLastError();
 }
 

@@ -174,7 +174,10 @@ __device__ __forceinline__ f32x4 load_g4(const void* __restrict__ g, uint64_t q)
         if constexpr (ALIGNED) {
             r = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));
         } else {
-            r.x = p[0]; r.y = p[1]; r.z = p[2]; r.w = p[3];
+            r.x = __builtin_nontemporal_load(p);
+            r.y = __builtin_nontemporal_load(p + 1);
+            r.z = __builtin_nontemporal_load(p + 2);
+            r.w = __builtin_nontemporal_load(p + 3);
         }
     } else {
         const uint16_t* p = static_cast<const uint16_t*>(g) + 4 * q;
@@ -185,8 +188,10 @@ __device__ __forceinline__ f32x4 load_g4(const void* __restrict__ g, uint64_t q)
             r.z = bf16_bits_to_float(w.y & 0xFFFFu);
             r.w = bf16_bits_to_float(w.y >> 16);
         } else {
-            r.x = bf16_bits_to_float(p[0]); r.y = bf16_bits_to_float(p[1]);
-            r.z = bf16_bits_to_float(p[2]); r.w = bf16_bits_to_float(p[3]);
+            r.x = bf16_bits_to_float(__builtin_nontemporal_load(p));
+            r.y = bf16_bits_to_float(__builtin_nontemporal_load(p + 1));
+            r.z = bf16_bits_to_float(__builtin_nontemporal_load(p + 2));
+            r.w = bf16_bits_to_float(__builtin_nontemporal_load(p + 3));
         }
     }
     return r;
@@ -198,12 +203,40 @@ __device__ __forceinline__ float load_g1(const void* __restrict__ g, uint64_t j)
     else return bf16_bits_to_float(static_cast<const uint16_t*>(g)[j]);
 }
 
-// The memory-side cache holds 256 MB.  Up to kKeepVMaxN parameters theta and v (8 B per parameter) both stay
-// in it; up to kKeepThetaMaxN theta alone does, at least in part (measured with the fused update's access
-// pattern: theta and v kept 89 % of HBM peak at 30 M parameters, 76 % at 40 M; theta kept 88-89 % from 30 M
-// to 64 M, 80 % at 70 M, and no better than streaming everything, 71 %, from 80 M on).
-constexpr uint64_t kKeepVMaxN = (uint64_t)230 * 1024 * 1024 / 8;
-constexpr uint64_t kKeepThetaMaxN = (uint64_t)290 * 1024 * 1024 / 4;
+// The memory-side cache in front of HBM holds 256 MiB, and lines brought in by accesses with the non-temporal
+// hint do not displace lines brought in without it.  The arrays a kernel touches at every arrival (theta, v, m)
+// therefore keep a leading part in that cache from one arrival to the next: the blocks below a threshold access it
+// without the hint, all other accesses carry it.  Measured with the fused update on 70 M - 250 M parameters: the
+// time falls linearly with the kept bytes up to 256 MiB and is back at the all-streamed time from 288 MiB on (the
+// kept lines then evict each other), so the budget stays clear of that edge.  For the same bytes, keeping more
+// of theta beats keeping the same parameters' theta and v.
+constexpr uint64_t kResidentBytes = (uint64_t)240 << 20;
+
+// Leading blocks of a launch whose theta / v / m accesses go without the hint (theta >= v >= m).
+struct Residency {
+    uint32_t theta, v, m;
+};
+
+// blocks: grid size; block_bytes: bytes of ONE array that a block covers.  theta first, then v, then m.
+inline Residency residency_for(uint64_t blocks, uint64_t block_bytes, bool with_v, bool with_m) {
+    uint64_t budget = kResidentBytes / block_bytes;
+    Residency r = {0u, 0u, 0u};
+    r.theta = (uint32_t)(blocks < budget ? blocks : budget);
+    budget -= r.theta;
+    if (with_v) r.v = (uint32_t)(blocks < budget ? blocks : budget);
+    budget -= r.v;
+    if (with_m) r.m = (uint32_t)(blocks < budget ? blocks : budget);
+    return r;
+}
+
+// Two block-uniform paths that differ only in cache hints are one path to the optimiser, which merges them and
+// drops the hints.  An empty asm statement at both ends of each path keeps them apart.
+#define GA_HINT_PATH(name, ...)                          \
+    do {                                                 \
+        asm volatile("; " name " begin" ::: "memory");   \
+        __VA_ARGS__;                                     \
+        asm volatile("; " name " end" ::: "memory");     \
+    } while (0)
 
 inline uint32_t blocks_for(uint64_t items, uint64_t per_block, uint32_t cap) {
     const uint64_t b = (items + per_block - 1) / per_block;

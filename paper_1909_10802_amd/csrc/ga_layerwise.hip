@@ -244,7 +244,7 @@ hipError_t launch_apply_layerwise(const StatePtrs& st, uint64_t N, uint32_t work
         hipLaunchKernelGGL(layer_gap_kernel<false>, lgrid, block, 0, stream, lt.partials, lt.spans, c.inv_bc_prev,
                            c.eta_max, c.eps, lt.gaps);
     const uintptr_t addr = reinterpret_cast<uintptr_t>(g);
-    const bool stream_v = N > kKeepVMaxN;
+    const bool stream_v = 8 * N > kResidentBytes;   // theta and v both stay in the memory-side cache, or theta alone
     const bool look = next_worker >= 0;
     const float* next_snap =
         (look && (uint32_t)next_worker != worker) ? st.snaps + (uint64_t)next_worker * st.stride : nullptr;
