@@ -370,6 +370,14 @@ int ga_quadratic_gradient(ga_ctx* ctx, uint32_t worker_id, const ga_grad_source*
  * GA_ERR_STATE.  Waits for the stream; host_out is written on return. */
 int ga_diagnostics(ga_ctx* ctx, uint32_t worker_id, ga_diag* host_out);
 
+/* The same statistics without waiting: the kernels are enqueued on the
+ * context's stream and the finished report is written to dev_out (DEVICE
+ * memory, 8-byte aligned, owned by the caller) when they have run; the
+ * arrival stream is not stalled.  Same arguments checks and errors as
+ * ga_diagnostics, plus GA_ERR_ALIGN for a misaligned dev_out.  The values
+ * are those ga_diagnostics reports (same kernels, same summation order). */
+int ga_diagnostics_async(ga_ctx* ctx, uint32_t worker_id, ga_diag* dev_out);
+
 /* Copies of the state, N floats each, to 4-byte aligned device buffers. */
 int ga_get_theta(ga_ctx* ctx, float* dev_dst);
 int ga_get_v(ga_ctx* ctx, float* dev_dst);

@@ -97,6 +97,7 @@ SIGNATURES = {
     "ga_warmup_lr": (_i, [_f, _u32, _u64, _u64, _u64, _p]),
     "ga_quadratic_gradient": (_i, [_p, _u32, C.POINTER(ga_grad_source), _p]),
     "ga_diagnostics": (_i, [_p, _u32, C.POINTER(ga_diag)]),
+    "ga_diagnostics_async": (_i, [_p, _u32, _p]),
     "ga_get_theta": (_i, [_p, _p]),
     "ga_get_v": (_i, [_p, _p]),
     "ga_get_m": (_i, [_p, _p]),
@@ -374,6 +375,23 @@ def ga_diagnostics(ctx, worker_id):
     return dict(mean_graw=d.mean_graw, frac_gt1=d.frac_gt1, frac_gt0=d.frac_gt0, n_nonfinite=d.n_nonfinite)
 
 
+DIAG_BYTES = C.sizeof(ga_diag)
+
+
+def diag_from_device(dev_out):
+    """Read a device ga_diag (uint8 CUDA tensor of DIAG_BYTES) back as a dict; waits for the device."""
+    raw = dev_out.cpu().numpy().tobytes()
+    d = ga_diag.from_buffer_copy(raw)
+    return dict(mean_graw=d.mean_graw, frac_gt1=d.frac_gt1, frac_gt0=d.frac_gt0, n_nonfinite=d.n_nonfinite)
+
+
+def ga_diagnostics_async(ctx, worker_id, dev_out):
+    """dev_out: uint8 CUDA tensor of at least DIAG_BYTES; nothing waits."""
+    import torch
+    _check(lib().ga_diagnostics_async(ctx, worker_id, _dev(dev_out, torch.uint8, DIAG_BYTES)), ctx)
+    return dev_out
+
+
 def _getter(name):
     def get(ctx, dev_dst):
         import torch
@@ -514,6 +532,12 @@ class Master:
 
     def diagnostics(self, worker_id):
         return ga_diagnostics(self.ctx, worker_id)
+
+    def diagnostics_async(self, worker_id, dev_out=None):
+        import torch
+        if dev_out is None:
+            dev_out = torch.empty(DIAG_BYTES, dtype=torch.uint8, device=self.device)
+        return ga_diagnostics_async(self.ctx, worker_id, dev_out)
 
     def theta(self):
         return ga_get_theta(self.ctx, self._new())

@@ -147,8 +147,8 @@ __global__ __launch_bounds__(kBlock) void diag_kernel(const float* __restrict__ 
     if (threadIdx.x == 0) partials[blockIdx.x] = r;
 }
 
-__global__ __launch_bounds__(kBlock) void diag_final_kernel(const DiagPartial* __restrict__ partials,
-                                                            uint32_t n_partials, DiagPartial* __restrict__ total) {
+// All partials added by one block in a fixed order; every thread returns the total.
+__device__ __forceinline__ DiagPartial add_partials(const DiagPartial* __restrict__ partials, uint32_t n_partials) {
     double sum = 0.0;
     unsigned long long gt1 = 0, gt0 = 0, bad = 0;
     for (uint32_t i = threadIdx.x; i < n_partials; i += kBlock) {
@@ -157,8 +157,27 @@ __global__ __launch_bounds__(kBlock) void diag_final_kernel(const DiagPartial* _
         gt0 += partials[i].n_gt0;
         bad += partials[i].n_bad;
     }
-    const DiagPartial r = block_reduce(sum, gt1, gt0, bad);
+    return block_reduce(sum, gt1, gt0, bad);
+}
+
+__global__ __launch_bounds__(kBlock) void diag_final_kernel(const DiagPartial* __restrict__ partials,
+                                                            uint32_t n_partials, DiagPartial* __restrict__ total) {
+    const DiagPartial r = add_partials(partials, n_partials);
     if (threadIdx.x == 0) *total = r;
+}
+
+// The same total turned into the report on the device (the divisions are IEEE double divisions, as on the host).
+__global__ __launch_bounds__(kBlock) void diag_report_kernel(const DiagPartial* __restrict__ partials,
+                                                             uint32_t n_partials, uint64_t N,
+                                                             ga_diag* __restrict__ out) {
+    const DiagPartial r = add_partials(partials, n_partials);
+    if (threadIdx.x == 0) {
+        const double n = (double)N;
+        out->mean_graw = r.sum_graw / n;
+        out->frac_gt1 = (double)r.n_gt1 / n;
+        out->frac_gt0 = (double)r.n_gt0 / n;
+        out->n_nonfinite = r.n_bad;
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -192,14 +211,17 @@ hipError_t launch_quadratic_gradient(const StatePtrs& st, uint64_t N, uint32_t w
 }
 
 hipError_t launch_diagnostics(const StatePtrs& st, uint64_t N, uint32_t worker, float inv_bc, float eta_max,
-                              float eps, DiagPartial* dev_partials, hipStream_t stream) {
+                              float eps, DiagPartial* dev_partials, ga_diag* dev_report, hipStream_t stream) {
     const uint32_t grid = blocks_for(N >> 2, (uint64_t)kBlock * 4, kDiagMaxBlocks);
     hipLaunchKernelGGL(diag_kernel, dim3(grid), dim3(kBlock), 0, stream, st.theta, st.m,
                        st.snaps + (uint64_t)worker * st.stride, N, inv_bc, eta_max, eps, dev_partials);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(diag_final_kernel, dim3(1), dim3(kBlock), 0, stream, dev_partials, grid,
-                       dev_partials + kDiagMaxBlocks);
+    if (dev_report)
+        hipLaunchKernelGGL(diag_report_kernel, dim3(1), dim3(kBlock), 0, stream, dev_partials, grid, N, dev_report);
+    else
+        hipLaunchKernelGGL(diag_final_kernel, dim3(1), dim3(kBlock), 0, stream, dev_partials, grid,
+                           dev_partials + kDiagMaxBlocks);
     return hipGetLastError();
 }
 

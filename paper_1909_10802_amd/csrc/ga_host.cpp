@@ -873,13 +873,19 @@ int ga_quadratic_gradient(ga_ctx* ctx, uint32_t worker_id, const ga_grad_source*
     return e == hipSuccess ? GA_OK : hip_fail(ctx, e, "gradient launch");
 }
 
-int ga_diagnostics(ga_ctx* ctx, uint32_t worker_id, ga_diag* host_out) {
-    if (!ctx) return GA_ERR_ARG;
-    if (!host_out) return fail(ctx, GA_ERR_ARG, "diagnostics: output is null");
+static int check_diagnostics(ga_ctx* ctx, uint32_t worker_id, const void* out) {
+    if (!out) return fail(ctx, GA_ERR_ARG, "diagnostics: output is null");
     if (worker_id >= ctx->W) return fail(ctx, GA_ERR_WORKER, "diagnostics: worker %u >= n_workers %u", worker_id, ctx->W);
     if (!keeps_m(ctx)) return fail(ctx, GA_ERR_STATE, "diagnostics: m is not maintained in this mode (enable gap tracking)");
+    return GA_OK;
+}
+
+int ga_diagnostics(ga_ctx* ctx, uint32_t worker_id, ga_diag* host_out) {
+    if (!ctx) return GA_ERR_ARG;
+    const int rc = check_diagnostics(ctx, worker_id, host_out);
+    if (rc != GA_OK) return rc;
     hipError_t e = ga::launch_diagnostics(ctx->st, ctx->N, worker_id, inverse_bias_correction(ctx->beta, ctx->k),
-                                          ctx->eta_max, ctx->eps, ctx->dev_partials, ctx->stream);
+                                          ctx->eta_max, ctx->eps, ctx->dev_partials, nullptr, ctx->stream);
     if (e != hipSuccess) return hip_fail(ctx, e, "diagnostics launch");
     ga::DiagPartial total;
     e = hipMemcpyAsync(&total, ctx->dev_partials + ga::kDiagMaxBlocks, sizeof total, hipMemcpyDeviceToHost, ctx->stream);
@@ -891,6 +897,16 @@ int ga_diagnostics(ga_ctx* ctx, uint32_t worker_id, ga_diag* host_out) {
     host_out->frac_gt0 = (double)total.n_gt0 / n;
     host_out->n_nonfinite = total.n_bad;
     return GA_OK;
+}
+
+int ga_diagnostics_async(ga_ctx* ctx, uint32_t worker_id, ga_diag* dev_out) {
+    if (!ctx) return GA_ERR_ARG;
+    const int rc = check_diagnostics(ctx, worker_id, dev_out);
+    if (rc != GA_OK) return rc;
+    if ((uintptr_t)dev_out & 7u) return fail(ctx, GA_ERR_ALIGN, "diagnostics_async: output must be 8-byte aligned");
+    const hipError_t e = ga::launch_diagnostics(ctx->st, ctx->N, worker_id, inverse_bias_correction(ctx->beta, ctx->k),
+                                                ctx->eta_max, ctx->eps, ctx->dev_partials, dev_out, ctx->stream);
+    return e == hipSuccess ? GA_OK : hip_fail(ctx, e, "diagnostics launch");
 }
 
 int ga_get_theta(ga_ctx* ctx, float* dev_dst) { return copy_out(ctx, dev_dst, ctx ? ctx->st.theta : nullptr); }

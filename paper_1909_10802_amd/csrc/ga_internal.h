@@ -123,9 +123,10 @@ hipError_t launch_quadratic_gradient(const StatePtrs& st, uint64_t N, uint32_t w
                                      const float* theta_star, uint64_t k, const RunConst& rc, float* g_out,
                                      hipStream_t stream);
 
-// Gap statistics of one worker: per-block partials, then a fixed-order total in partials[kDiagMaxBlocks].
+// Gap statistics of one worker: per-block partials, then a fixed-order total, written as a DiagPartial to
+// dev_partials[kDiagMaxBlocks] (dev_report null) or as the finished report to dev_report.
 hipError_t launch_diagnostics(const StatePtrs& st, uint64_t N, uint32_t worker, float inv_bc, float eta_max,
-                              float eps, DiagPartial* dev_partials, hipStream_t stream);
+                              float eps, DiagPartial* dev_partials, ga_diag* dev_report, hipStream_t stream);
 
 hipError_t launch_box_muller_raw(const uint32_t* xa, const uint32_t* xb, uint64_t n, float* zc, float* zs,
                                  hipStream_t stream);

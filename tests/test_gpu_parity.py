@@ -236,6 +236,38 @@ def test_diagnostics_under_sa_with_tracking():
         assert round(d["frac_gt1"] * N) == r["n_gt1"]
 
 
+@pytest.mark.parametrize("N", [3, 4097, 2_500_001])
+def test_diagnostics_async_writes_the_report_on_the_device(N):
+    """ga_diagnostics_async: same statistics as the oracle (App. C.8), written to device memory with no wait; it
+    must not disturb the arrivals enqueued around it."""
+    W, seed = 3, 33
+    theta, v, m, snaps = ga_inputs.random_state(N, W, seed)
+    if N > 100:
+        snaps[1, 17] = np.inf
+        snaps[1, 40:50] = theta[40:50]
+    k = 60
+    M = ga.Master(N, W, mode=ga.GA_MODE_GA)
+    load_state(M, theta, v, m, snaps, k, np.array([60, 31, 2], np.uint64))
+    outs = [M.diagnostics_async(w) for w in (1, 2)]             # two reports in flight, none waited for
+    g = ga_inputs.gradient_buffers(1, N, seed)[0]
+    M.apply(0, dev(g))                                           # an arrival behind them on the same stream
+    for w, out in zip((1, 2), outs):
+        d = ga.diag_from_device(out)
+        r = oracle.gap_statistics(theta, m, snaps[w], k, oracle.Hyper())
+        assert d["n_nonfinite"] == r["n_nonfinite"]
+        assert round(d["frac_gt1"] * N) == r["n_gt1"] and round(d["frac_gt0"] * N) == r["n_gt0"]
+        assert abs(d["mean_graw"] - r["mean_graw"]) <= 1e-6 * abs(r["mean_graw"])
+    O = oracle.Master(N, W, oracle.MODE_GA, oracle.Hyper())
+    O.theta, O.v, O.m, O.snaps = theta.copy(), v.copy(), m.copy(), snaps.copy()
+    O.k, O.iter = k, np.array([60, 31, 2], np.uint64)
+    O.apply(0, g)
+    th, vv, mm, sn = gpu_state(M)
+    assert_step_close(th, O.theta, "theta after the arrival behind the reports")
+    assert_step_close(sn, O.snaps, "snapshots after the arrival behind the reports")
+    with pytest.raises(ga.GaError):
+        ga.Master(N, W, mode=ga.GA_MODE_SA).diagnostics_async(0)   # m is not maintained
+
+
 # ------------------------------------------------------------------ state handling
 def test_checkpoint_resume_is_bit_identical():
     N, W, T, seed = 40_000, 5, 160, 8
