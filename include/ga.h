@@ -378,6 +378,32 @@ int ga_diagnostics(ga_ctx* ctx, uint32_t worker_id, ga_diag* host_out);
  * are those ga_diagnostics reports (same kernels, same summation order). */
 int ga_diagnostics_async(ga_ctx* ctx, uint32_t worker_id, ga_diag* dev_out);
 
+/* For callers that cannot allocate (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): the Gap statistics of
+ * ga_diagnostics for caller-held arrays, with no context and no workspace.
+ * The reduction partials live in a static device array of the library
+ * (GA_STATIC_SCRATCH_BYTES per GPU, held until the process ends); this call
+ * allocates and frees nothing on host or device.
+ *   dev_theta, dev_snapshot, dev_m   DEVICE arrays of N floats, 16-byte
+ *                    aligned, read only, owned by the caller
+ *   N                1 .. GA_STATIC_MAX_N (GA_ERR_ARG beyond it)
+ *   k, beta          C is taken with the bias correction 1 / (1 - beta^k)
+ *                    (0 for k = 0), i.e. as the arrival after master step k
+ *                    would see it; eta_max, eps as in Alg. 14
+ *   dev_out          DEVICE ga_diag, 8-byte aligned, written when the two
+ *                    kernels have run on hip_stream (hipStream_t, may be null)
+ * Asynchronous.  Every call on one GPU uses that GPU's one array: calls that
+ * overlap in time on the same GPU (two streams, two threads) race and give
+ * wrong statistics; calls on one stream are ordered and safe.  Nothing in the
+ * array has to be cleared between calls (each call writes every partial it
+ * reads).  The first call on a GPU looks up the array's address; make that
+ * call outside stream capture.  Errors: GA_ERR_ARG, GA_ERR_ALIGN, GA_ERR_HIP;
+ * the message is read with ga_last_error(NULL). */
+#define GA_STATIC_SCRATCH_BYTES 65536u
+#define GA_STATIC_MAX_N (1ull << 40)
+int ga_gap_statistics_static(const float* dev_theta, const float* dev_snapshot, const float* dev_m, uint64_t N,
+                             uint64_t k, float beta, float eta_max, float eps, ga_diag* dev_out, void* hip_stream);
+
 /* Copies of the state, N floats each, to 4-byte aligned device buffers. */
 int ga_get_theta(ga_ctx* ctx, float* dev_dst);
 int ga_get_v(ga_ctx* ctx, float* dev_dst);

@@ -98,6 +98,7 @@ SIGNATURES = {
     "ga_quadratic_gradient": (_i, [_p, _u32, C.POINTER(ga_grad_source), _p]),
     "ga_diagnostics": (_i, [_p, _u32, C.POINTER(ga_diag)]),
     "ga_diagnostics_async": (_i, [_p, _u32, _p]),
+    "ga_gap_statistics_static": (_i, [_p, _p, _p, _u64, _u64, _f, _f, _f, _p, _p]),
     "ga_get_theta": (_i, [_p, _p]),
     "ga_get_v": (_i, [_p, _p]),
     "ga_get_m": (_i, [_p, _p]),
@@ -389,6 +390,14 @@ def ga_diagnostics_async(ctx, worker_id, dev_out):
     """dev_out: uint8 CUDA tensor of at least DIAG_BYTES; nothing waits."""
     import torch
     _check(lib().ga_diagnostics_async(ctx, worker_id, _dev(dev_out, torch.uint8, DIAG_BYTES)), ctx)
+    return dev_out
+
+
+def ga_gap_statistics_static(dev_theta, dev_snapshot, dev_m, N, k, beta, eta_max, eps, dev_out, stream=None):
+    import torch
+    _check(lib().ga_gap_statistics_static(_dev(dev_theta, torch.float32, N), _dev(dev_snapshot, torch.float32, N),
+                                          _dev(dev_m, torch.float32, N), N, k, beta, eta_max, eps,
+                                          _dev(dev_out, torch.uint8, DIAG_BYTES), _stream_ptr(stream)))
     return dev_out
 
 

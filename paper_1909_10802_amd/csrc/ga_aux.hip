@@ -1,6 +1,8 @@
 // libga, gfx950: the gradient source alone (quadratic_gradient_kernel, noise_fill_kernel,
 // box_muller_raw_kernel), Gap statistics (diag_kernel + diag_final_kernel, App. C.8) and fills.
 
+#include <mutex>
+
 #include "ga_device.h"
 
 namespace ga {
@@ -180,6 +182,16 @@ __global__ __launch_bounds__(kBlock) void diag_report_kernel(const DiagPartial* 
     }
 }
 
+// Reduction partials for callers that bring no workspace and cannot allocate one: one copy of this array per
+// GPU, held until the process ends, shared by every such call on that GPU.  In host code `scratch` is only a
+// handle for hipGetSymbolAddress, never a device address.
+static __device__ __align__(256) DiagPartial scratch[kDiagMaxBlocks];
+static_assert(sizeof(DiagPartial) * kDiagMaxBlocks == GA_STATIC_SCRATCH_BYTES, "documented size of the static scratch array");
+
+constexpr int kMaxDevices = 64;
+DiagPartial* scratch_of_device[kMaxDevices];   // device address of `scratch` on each GPU, resolved on first use
+std::mutex scratch_lock;
+
 // ---------------------------------------------------------------------------
 // Fills.
 // ---------------------------------------------------------------------------
@@ -222,6 +234,38 @@ hipError_t launch_diagnostics(const StatePtrs& st, uint64_t N, uint32_t worker, 
     else
         hipLaunchKernelGGL(diag_final_kernel, dim3(1), dim3(kBlock), 0, stream, dev_partials, grid,
                            dev_partials + kDiagMaxBlocks);
+    return hipGetLastError();
+}
+
+hipError_t static_scratch_address(DiagPartial** out) {
+    int device = -1;
+    hipError_t e = hipGetDevice(&device);
+    if (e != hipSuccess) return e;
+    if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> hold(scratch_lock);
+    if (!scratch_of_device[device]) {
+        DiagPartial* p = nullptr;
+        e = hipGetSymbolAddress(reinterpret_cast<void**>(&p), HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        scratch_of_device[device] = p;
+    }
+    *out = scratch_of_device[device];
+    return hipSuccess;
+}
+
+hipError_t launch_diagnostics_static(const float* theta, const float* snap, const float* m, uint64_t N, float inv_bc,
+                                     float eta_max, float eps, ga_diag* dev_report, hipStream_t stream) {
+    DiagPartial* partials = nullptr;
+    hipError_t e = static_scratch_address(&partials);
+    if (e != hipSuccess) return e;
+    // every partial that the report kernel reads is written by this launch first: nothing has to start at zero
+    const uint32_t grid = blocks_for(N >> 2, (uint64_t)kBlock * 4, kDiagMaxBlocks);
+    hipLaunchKernelGGL(diag_kernel, dim3(grid), dim3(kBlock), 0, stream, theta, m, snap, N, inv_bc, eta_max, eps,
+                       partials);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(diag_report_kernel, dim3(1), dim3(kBlock), 0, stream, partials, grid, N, dev_report);
     return hipGetLastError();
 }
 

@@ -909,6 +909,23 @@ int ga_diagnostics_async(ga_ctx* ctx, uint32_t worker_id, ga_diag* dev_out) {
     return e == hipSuccess ? GA_OK : hip_fail(ctx, e, "diagnostics launch");
 }
 
+int ga_gap_statistics_static(const float* dev_theta, const float* dev_snapshot, const float* dev_m, uint64_t N,
+                             uint64_t k, float beta, float eta_max, float eps, ga_diag* dev_out, void* hip_stream) {
+    if (!dev_theta || !dev_snapshot || !dev_m || !dev_out) return fail(nullptr, GA_ERR_ARG, "gap_statistics_static: null argument");
+    if (N == 0) return fail(nullptr, GA_ERR_ARG, "gap_statistics_static: N must be positive");
+    if (N > GA_STATIC_MAX_N)
+        return fail(nullptr, GA_ERR_ARG, "gap_statistics_static: N = %llu is beyond the maximum of %llu parameters",
+                    (unsigned long long)N, (unsigned long long)GA_STATIC_MAX_N);
+    if (!(beta >= 0.f && beta < 1.f) || !(eps > 0.f) || !std::isfinite(eps) || !(eta_max > 0.f) || !std::isfinite(eta_max))
+        return fail(nullptr, GA_ERR_ARG, "gap_statistics_static: beta must be in [0,1), eps and eta_max finite and > 0");
+    if (((uintptr_t)dev_theta | (uintptr_t)dev_snapshot | (uintptr_t)dev_m) & 15u)
+        return fail(nullptr, GA_ERR_ALIGN, "gap_statistics_static: the arrays must be 16-byte aligned");
+    if ((uintptr_t)dev_out & 7u) return fail(nullptr, GA_ERR_ALIGN, "gap_statistics_static: output must be 8-byte aligned");
+    const hipError_t e = ga::launch_diagnostics_static(dev_theta, dev_snapshot, dev_m, N, inverse_bias_correction(beta, k),
+                                                       eta_max, eps, dev_out, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? GA_OK : hip_fail(nullptr, e, "gap_statistics_static");
+}
+
 int ga_get_theta(ga_ctx* ctx, float* dev_dst) { return copy_out(ctx, dev_dst, ctx ? ctx->st.theta : nullptr); }
 int ga_get_v(ga_ctx* ctx, float* dev_dst) { return copy_out(ctx, dev_dst, ctx ? ctx->st.v : nullptr); }
 int ga_get_m(ga_ctx* ctx, float* dev_dst) { return copy_out(ctx, dev_dst, ctx ? ctx->st.m : nullptr); }

@@ -128,6 +128,13 @@ hipError_t launch_quadratic_gradient(const StatePtrs& st, uint64_t N, uint32_t w
 hipError_t launch_diagnostics(const StatePtrs& st, uint64_t N, uint32_t worker, float inv_bc, float eta_max,
                               float eps, DiagPartial* dev_partials, ga_diag* dev_report, hipStream_t stream);
 
+// The same statistics of (theta, snap, m) with the partials in the library's static device array.
+hipError_t launch_diagnostics_static(const float* theta, const float* snap, const float* m, uint64_t N, float inv_bc,
+                                     float eta_max, float eps, ga_diag* dev_report, hipStream_t stream);
+
+// Device address of that array on the current GPU (resolved once per GPU).
+hipError_t static_scratch_address(DiagPartial** out);
+
 hipError_t launch_box_muller_raw(const uint32_t* xa, const uint32_t* xb, uint64_t n, float* zc, float* zs,
                                  hipStream_t stream);
 hipError_t launch_noise_fill(uint64_t seed, uint64_t k, uint64_t j0, uint64_t n, float* out, hipStream_t stream);
