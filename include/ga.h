@@ -25,9 +25,15 @@
  *     (with a few hundred KB of pinned host memory for staging the arrival table).
  *   - Every call that touches the device enqueues on the HIP stream given to
  *     ga_create and returns without waiting, unless stated otherwise.
- *   - Every function returning int returns a ga_status.  On any error nothing
- *     has been enqueued and no state has changed; ga_last_error(ctx) describes
- *     the failure.  No exception crosses this boundary.
+ *   - Every function returning int returns a ga_status; ga_last_error(ctx)
+ *     describes the failure.  No exception crosses this boundary.  Arguments
+ *     are checked before anything is enqueued: after GA_ERR_ARG,
+ *     GA_ERR_WORKER, GA_ERR_ALIGN or GA_ERR_STATE nothing has been enqueued
+ *     and no state has changed.  GA_ERR_HIP (a HIP runtime call failed) can
+ *     come in the middle of a call that enqueues several operations: what was
+ *     enqueued before it stays enqueued, the host bookkeeping covers exactly
+ *     the arrivals whose launch succeeded (ga_step tells how many), and a
+ *     failed ga_create_ex may have enqueued the fill of the workspace.
  *   - A context is not thread safe: one master, one caller at a time.
  *
  * Arithmetic of one arrival (worker i, gradient g, master step k >= 1,
@@ -426,11 +432,22 @@ int ga_put_array(ga_ctx* ctx, int which, uint32_t worker_id, const float* dev_sr
  * GA_ERR_STATE for a parameter-wise context or before the first arrival. */
 int ga_get_layer_gaps(ga_ctx* ctx, float* host_out, uint32_t max_n);
 
-/* Host bookkeeping: current step k; iter[W]; the delays of all arrivals so far
- * (at most max_n are written, the total count goes to n_out). */
+/* Host bookkeeping: current step k; iter[W]; the delays tau_k of the most
+ * recent arrivals.  The library keeps the delays of the last 1,048,576
+ * arrivals (older ones are dropped, so a long-lived master does not grow):
+ * ga_get_delays writes the min(max_n, kept) most recent ones, oldest first,
+ * and the number kept to n_out (may be null).  host_out may be null when
+ * max_n is 0. */
 uint64_t ga_step(const ga_ctx* ctx);
 int ga_get_iter(const ga_ctx* ctx, uint64_t* host_iter);
 int ga_get_delays(const ga_ctx* ctx, uint64_t* host_out, uint64_t max_n, uint64_t* n_out);
+/* The configuration the context runs with (as given to ga_create_ex, with
+ * eta = eta_max after ga_set_eta_max and beta, eps after ga_set_beta_eps;
+ * host_layer_sizes is returned null) and, if eta_k is not null, the current
+ * step size set by ga_set_lr.  A checkpoint holds the state, not these: store
+ * them beside it and create the resuming context from them, since Alg. 14
+ * continues with another C under another eta_max, beta or eps. */
+int ga_get_config(const ga_ctx* ctx, ga_config* out, float* eta_k);
 /* Restore k and iter[W] (checkpoint resume; the device arrays are restored
  * with the ga_put_* calls).  Every iter[i] must be <= k. */
 int ga_set_bookkeeping(ga_ctx* ctx, uint64_t k, const uint64_t* host_iter);

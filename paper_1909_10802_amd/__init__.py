@@ -111,6 +111,7 @@ SIGNATURES = {
     "ga_get_iter": (_i, [_p, _p]),
     "ga_get_delays": (_i, [_p, _p, _u64, C.POINTER(_u64)]),
     "ga_set_bookkeeping": (_i, [_p, _u64, _p]),
+    "ga_get_config": (_i, [_p, C.POINTER(ga_config), C.POINTER(_f)]),
     "ga_state_bytes": (C.c_size_t, [_p]),
     "ga_export_state": (_i, [_p, _p, C.c_size_t, C.POINTER(_u64), _p]),
     "ga_import_state": (_i, [_p, _p, C.c_size_t, _u64, _p]),
@@ -441,6 +442,13 @@ def ga_get_delays(ctx):
     out = np.empty(n.value, dtype=np.uint64)
     _check(lib().ga_get_delays(ctx, _np_ptr(out), n.value, C.byref(n)), ctx)
     return out
+
+
+def ga_get_config(ctx):
+    """Returns (ga_config, eta_k)."""
+    cfg, eta_k = ga_config(), _f()
+    _check(lib().ga_get_config(ctx, C.byref(cfg), C.byref(eta_k)), ctx)
+    return cfg, eta_k.value
 
 
 def ga_set_bookkeeping(ctx, k, host_iter):

@@ -33,7 +33,10 @@ struct ga_ctx {
     ga::DiagPartial* dev_partials = nullptr;
     uint64_t k = 0;
     std::vector<uint64_t> iter;
+    // delays of the most recent arrivals: a ring of at most kDelayLog entries (a master that runs for
+    // millions of steps must not grow), delay_next is the slot the next delay goes to
     std::vector<uint64_t> delays;
+    uint64_t delay_next = 0;
     // pinned staging for one chunk of the arrival table (and Adam's rows); `staged` is recorded after
     // the upload so that the next chunk does not overwrite rows that are still being copied
     ga_arrival* rows = nullptr;
@@ -64,6 +67,15 @@ int fail(ga_ctx* ctx, int code, const char* fmt, ...) {
     va_end(ap);
     if (ctx) ctx->err = buf; else g_create_error = buf;
     return code;
+}
+
+void record_delay(ga_ctx* ctx, uint64_t tau) {
+    if (ctx->delays.size() < ga::kDelayLog) {
+        ctx->delays.push_back(tau);
+    } else {
+        ctx->delays[ctx->delay_next] = tau;
+        ctx->delay_next = (ctx->delay_next + 1) % ga::kDelayLog;
+    }
 }
 
 int hip_fail(ga_ctx* ctx, hipError_t e, const char* what) {
@@ -363,7 +375,7 @@ int apply_one(ga_ctx* ctx, uint32_t worker, const void* dev_grad, int dtype, boo
     if (e != hipSuccess) return hip_fail(ctx, e, "apply launch");
     ctx->k = k;
     ctx->iter[worker] = k;
-    ctx->delays.push_back(tau);
+    record_delay(ctx, tau);
     return GA_OK;
 }
 
@@ -758,7 +770,7 @@ static int run_persistent(ga_ctx* ctx, const uint32_t* host_schedule, uint64_t T
             e = ga::launch_persistent(ctx->st, ctx->N, ctx->family, ctx->dev_table, ctx->dev_adam_table, n, ctx->k, src->dev_a,
                                       src->dev_theta_star, ctx->mode, ctx->nesterov, keeps_m(ctx), rcst, ctx->stream);
         if (e != hipSuccess) return hip_fail(ctx, e, "persistent launch");
-        ctx->delays.insert(ctx->delays.end(), taus.begin(), taus.end());
+        for (const uint64_t tau : taus) record_delay(ctx, tau);
         ctx->iter.swap(iter_after);
         ctx->k += n;
         done += n;
@@ -1002,9 +1014,33 @@ int ga_get_iter(const ga_ctx* ctx, uint64_t* host_iter) {
 
 int ga_get_delays(const ga_ctx* ctx, uint64_t* host_out, uint64_t max_n, uint64_t* n_out) {
     if (!ctx || (max_n > 0 && !host_out)) return GA_ERR_ARG;
-    const uint64_t n = ctx->delays.size() < max_n ? ctx->delays.size() : max_n;
-    if (n) std::memcpy(host_out, ctx->delays.data(), n * sizeof(uint64_t));
-    if (n_out) *n_out = ctx->delays.size();
+    const uint64_t held = ctx->delays.size();
+    const uint64_t n = held < max_n ? held : max_n;            // the n most recent, oldest first
+    for (uint64_t i = 0; i < n; ++i) host_out[i] = ctx->delays[(ctx->delay_next + (held - n) + i) % held];
+    if (n_out) *n_out = held;
+    return GA_OK;
+}
+
+int ga_get_config(const ga_ctx* ctx, ga_config* out, float* eta_k) {
+    if (!ctx || !out) return GA_ERR_ARG;
+    ga_config_init(out);
+    out->N = ctx->N;
+    out->n_workers = ctx->W;
+    out->family = ctx->family;
+    out->mode = ctx->mode;
+    out->eta = ctx->eta_max;
+    out->gamma = ctx->gamma;
+    out->beta = ctx->beta;
+    out->eps = ctx->eps;
+    out->adam_beta1 = ctx->beta1;
+    out->adam_beta2 = ctx->beta2;
+    out->adam_eps = ctx->adam_eps;
+    out->track_gap = ctx->track_gap ? 1 : 0;
+    out->gap_scope = ctx->gap_scope;
+    out->n_layers = ctx->gap_scope == GA_GAP_LAYER ? ctx->layers.n_layers : 0;
+    out->host_layer_sizes = nullptr;
+    out->nesterov = ctx->nesterov ? 1 : 0;
+    if (eta_k) *eta_k = ctx->lr;
     return GA_OK;
 }
 

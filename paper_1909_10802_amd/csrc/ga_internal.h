@@ -47,10 +47,7 @@ struct DiagPartial {
 };
 
 // Layer-wise Gap: layers are cut into chunks of at most kLayerChunk parameters; one block per chunk.
-#ifndef GA_LAYER_CHUNK
-#define GA_LAYER_CHUNK 4096
-#endif
-constexpr uint32_t kLayerChunk = GA_LAYER_CHUNK;   // a multiple of 64
+constexpr uint32_t kLayerChunk = 4096;   // a multiple of 64
 struct LayerChunk {
     uint64_t start;   // first parameter
     uint32_t len;     // parameters in the chunk
@@ -72,6 +69,7 @@ struct LayerTables {
 };
 
 constexpr uint32_t kTableCap = 8192;       // arrivals per persistent launch
+constexpr uint64_t kDelayLog = (uint64_t)1 << 20;   // delays of this many most recent arrivals are kept on the host
 constexpr uint32_t kDiagMaxBlocks = 2048;  // partials in the workspace
 
 // State pointers inside the workspace.  snaps is W rows of `stride` floats.

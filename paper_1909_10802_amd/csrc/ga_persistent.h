@@ -14,10 +14,7 @@ constexpr int kSrcF32 = 1;         // read from the float buffer named by the ar
 constexpr int kSrcBf16 = 2;        // the same with bfloat16 buffers
 
 // below this many parameters the persistent kernel gives each thread 2 instead of 4 of them
-#ifndef GA_PERSIST_WIDE_MIN_N
-#define GA_PERSIST_WIDE_MIN_N (1ull << 21)
-#endif
-constexpr uint64_t kPersistWideMinN = GA_PERSIST_WIDE_MIN_N;
+constexpr uint64_t kPersistWideMinN = (uint64_t)1 << 21;
 
 // Gradients j0 .. j0+E-1 of one buffer (N values, base aligned to E values); a pack that reaches
 // past N is read element by element.

@@ -142,6 +142,22 @@ def test_apply_queue_equals_apply_one_by_one(dtype):
     compare_masters(A, O, "apply_queue %s" % dtype)
 
 
+@pytest.mark.parametrize("family", [ga.GA_FAMILY_DANA, ga.GA_FAMILY_ADAM], ids=["dana", "adam"])
+def test_apply_queue_families_bfloat16_four_per_thread(family):
+    # ga_apply_queue itself (worker, gradient pairs) with bfloat16 gradients, at a size where a thread owns four parameters
+    N, W, T = 2_100_003, 4, 14
+    eta = 0.1 if family == ga.GA_FAMILY_DANA else 0.01
+    ref, dbufs = make_bufs(3, N, 41, "bf16")
+    rng = np.random.default_rng(5)
+    workers = rng.integers(0, W, T).astype(np.uint32)
+    which = rng.integers(0, 3, T)
+    M, O = make_pair(family, N, W, ga.GA_MODE_GA, eta)
+    M.apply_queue(workers, [dbufs[b] for b in which])
+    for w, b in zip(workers, which):
+        O.apply(int(w), ref[b])
+    compare_family(M, O, "apply_queue family %d bf16" % family)
+
+
 def test_apply_queue_errors_change_nothing():
     N, W = 1000, 2
     buf = torch.zeros(N + 4, dtype=torch.float32, device=DEV)

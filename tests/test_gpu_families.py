@@ -241,14 +241,17 @@ def test_export_import_state_resumes_bit_identically(family):
 
 
 @pytest.mark.parametrize("family", FAMILIES, ids=["dana", "adam"])
-def test_beyond_the_cache_resident_size_sampled(family):
-    # past 30 M parameters the second state array is streamed (another instantiation of the fused kernel)
-    N, W, T, seed = 33_000_003, 3, 12, 14
+@pytest.mark.parametrize("N,dtype", [(33_000_003, "f32"), (33_000_003, "bf16"), (70_000_001, "bf16")],
+                         ids=["33M-f32", "33M-bf16", "70M-bf16"])
+def test_beyond_the_cache_resident_size_sampled(family, N, dtype):
+    # past 30 M parameters only a leading part of the second state array stays in the memory-side cache, past
+    # 63 M only a leading part of theta: the block-uniform paths of the fused kernel, float and bfloat16 gradients
+    W, T, seed = 3, 12, 14
     eta = 0.1 if family == ga.GA_FAMILY_DANA else 0.01
     idx = ga_inputs.sample_indices(N, 8000, seed)
     idx_dev = torch.from_numpy(idx.astype(np.int64)).to(DEV)
-    bufs = ga_inputs.device_gradient_buffers(2, N, seed, 0.3, "f32", DEV)
-    bufs_s = np.stack([host(b[idx_dev]) for b in bufs])
+    bufs = ga_inputs.device_gradient_buffers(2, N, seed, 0.3, dtype, DEV)
+    bufs_s = np.stack([host(b[idx_dev].to(torch.float32)) for b in bufs])     # widening bfloat16 is exact
     sched = ga.ga_simulate_schedule(W, T, ga.GA_DIST_EXP, 1.0, seed)
     M = ga.Master(N, W, eta=eta, gamma=0.9, mode=ga.GA_MODE_GA, family=family)
     M.run_schedule(sched, ga.buffer_source(bufs, ga.GA_PICK_BY_WORKER))

@@ -166,6 +166,46 @@ def test_sizes_where_only_theta_stays_cached(N):
     free_gpu()
 
 
+@pytest.mark.parametrize("case", ["ga", "sa", "asgd_tracked", "sa_step", "ga_misaligned"])
+def test_one_group_per_thread_with_float_gradients(case):
+    # beyond 128 Mi parameters a thread owns one group of four and only the leading 240 MiB of theta stays in the
+    # memory-side cache: the instantiations a Transformer-XL-sized float model runs (Sec. 6), in every penalty
+    # mode, with and without Gap tracking, and with a gradient pointer that is not 16-byte aligned
+    N, W, T, seed, n_bufs = 140_000_003, 2, 9, 16, 2
+    mode = {"ga": ga.GA_MODE_GA, "sa": ga.GA_MODE_SA, "asgd_tracked": ga.GA_MODE_ASGD, "sa_step": ga.GA_MODE_SA_STEP,
+            "ga_misaligned": ga.GA_MODE_GA}[case]
+    omode = {ga.GA_MODE_SA_STEP: oracle.MODE_SA_STEP, **ORACLE_MODE}[mode]
+    track = case == "asgd_tracked"
+    keep_m = track or mode == ga.GA_MODE_GA
+    shift = 1 if case == "ga_misaligned" else 0
+    idx = ga_inputs.sample_indices(N, 8000, seed)
+    idx_dev = torch.from_numpy(idx.astype(np.int64)).to(DEV)
+    whole = ga_inputs.device_gradient_buffers(n_bufs, N + shift, seed, 0.3, "f32", DEV)
+    bufs = [b[shift:] for b in whole]                              # 4 bytes off a 16-byte boundary when shift = 1
+    assert all(b.data_ptr() % 16 == 4 * shift for b in bufs)
+    bufs_s = np.stack([host(b[idx_dev]) for b in bufs])
+    sched = ga.ga_simulate_schedule(W, T, ga.GA_DIST_EXP, 1.0, seed)
+    M = ga.Master(N, W, mode=mode, track_gap=track)
+    if shift:                                                       # buffer sources want aligned buffers: arrival by arrival
+        for a in range(T):
+            M.apply(int(sched[a]), bufs[int(sched[a]) % n_bufs])
+    else:
+        M.run_schedule(sched, ga.buffer_source(bufs, ga.GA_PICK_BY_WORKER))
+    O = oracle.Master(idx.size, W, omode, oracle.Hyper(), track_gap=track)
+    O.run_buffers(sched, bufs_s, pick_by_worker=True)
+    theta = gather(M.theta(), idx_dev)
+    assert bits_equal(theta, O.theta) == 0
+    assert_step_close(gather(M.v(), idx_dev), O.v, case + " v")
+    if keep_m:
+        assert_step_close(gather(M.m(), idx_dev), O.m, case + " m")
+        for w in range(W):
+            assert_step_close(gather(M.snapshot(w), idx_dev), O.snaps[w], case + " snapshot %d" % w)
+    assert M.k == O.k and np.array_equal(M.iter(), O.iter)
+    assert np.array_equal(M.delays(), np.array(O.tau_log, np.uint64))
+    del M, bufs, whole
+    free_gpu()
+
+
 def test_cfg4_sampled():
     run_quadratic_workload("cfg4", [ga.GA_MODE_GA, ga.GA_MODE_GA_HINGE], n_random=8000)
 

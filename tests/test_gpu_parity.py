@@ -221,6 +221,22 @@ def test_diagnostics(N):
     assert d0 == dict(mean_graw=0.0, frac_gt1=0.0, frac_gt0=0.0, n_nonfinite=0)
 
 
+def test_diagnostics_counts_are_strict_at_graw_equal_one():
+    # beta = 1/2, k = 1: m-hat = 2 m = 1/16, root 1/4; eps = 2^-10, eta_max = 1/2 -> C = 1/8 + 2^-11 exactly.
+    # Distances {0, C/2, C, 2C, inf, nan}: Graw = 1 exactly is penalised by the paper's form and not by the hinge form.
+    Cc = np.float32(0.125 + 2.0 ** -11)
+    diff = np.array([0.0, Cc / 2, -Cc, 2 * Cc, np.inf, np.nan, 0.0], np.float32)
+    snap = np.zeros(7, np.float32)
+    theta, m, v = diff.copy(), np.full(7, 0.03125, np.float32), np.zeros(7, np.float32)
+    M = ga.Master(7, 1, eta=0.5, mode=ga.GA_MODE_GA, beta=0.5, eps=2.0 ** -10)
+    load_state(M, theta, v, m, snap[None, :], 1, np.array([1], np.uint64))
+    d = M.diagnostics(0)
+    r = oracle.gap_statistics(theta, m, snap, 1, oracle.Hyper(eta=0.5, beta=0.5, eps=2.0 ** -10))
+    assert (round(d["frac_gt0"] * 7), round(d["frac_gt1"] * 7), d["n_nonfinite"]) == (3, 1, 2)
+    assert (r["n_gt0"], r["n_gt1"], r["n_nonfinite"]) == (3, 1, 2)
+    assert d["mean_graw"] == r["mean_graw"] == 3.5 / 7
+
+
 def test_diagnostics_under_sa_with_tracking():
     N, W, T, seed = 50_000, 8, 120, 6
     a, ts = ga_inputs.curvatures(N, seed), ga_inputs.optimum(N, seed)
@@ -286,6 +302,39 @@ def test_checkpoint_resume_is_bit_identical():
     for x, y in zip(gpu_state(A), gpu_state(C2)):
         assert bits_equal(x, y) == 0
     assert C2.k == A.k and np.array_equal(C2.iter(), A.iter())
+
+
+def test_delay_log_keeps_the_most_recent_arrivals():
+    # the host keeps the delays of the last 2^20 arrivals only (Sec. 6 runs have 10^5 - 10^6 master steps)
+    N, W, kept = 4, 3, 1 << 20
+    T = kept + 5000
+    a, ts = ga_inputs.curvatures(N, 2), ga_inputs.optimum(N, 2)
+    sched = ga.ga_simulate_schedule(W, T, seed=2)
+    M = ga.Master(N, W, mode=ga.GA_MODE_SA)
+    M.run_schedule(sched[:1000], ga.quadratic_source(dev(a), dev(ts), 2))
+    assert np.array_equal(M.delays(), oracle.delays(W, sched[:1000])[0])
+    M.run_schedule(sched[1000:], ga.quadratic_source(dev(a), dev(ts), 2))
+    torch.cuda.synchronize()
+    taus, it = oracle.delays(W, sched)
+    got = M.delays()
+    assert got.size == kept and np.array_equal(got, taus[-kept:])
+    assert M.k == T and np.array_equal(M.iter(), it)
+    few = np.empty(7, np.uint64)                                   # fewer than kept: the most recent ones
+    n = ga.C.c_uint64()
+    assert ga.lib().ga_get_delays(M.ctx, few.ctypes.data_as(ga.C.c_void_p), 7, ga.C.byref(n)) == ga.GA_OK
+    assert n.value == kept and np.array_equal(few, taus[-7:])
+
+
+def test_get_config_returns_what_the_context_runs_with():
+    M = ga.Master(1000, 5, eta=0.05, gamma=-0.3, mode=ga.GA_MODE_GA_HINGE, beta=0.99, eps=1e-6, eta_max=0.2, nesterov=True)
+    ga.ga_set_lr(M.ctx, 0.0125)
+    cfg, eta_k = ga.ga_get_config(M.ctx)
+    f = np.float32
+    assert (cfg.N, cfg.n_workers, cfg.family, cfg.mode, cfg.nesterov) == (1000, 5, ga.GA_FAMILY_MOMENTUM, ga.GA_MODE_GA_HINGE, 1)
+    assert (f(cfg.eta), f(cfg.gamma), f(cfg.beta), f(cfg.eps), f(eta_k)) == (f(0.2), f(-0.3), f(0.99), f(1e-6), f(0.0125))
+    A = ga.Master(64, 2, eta=0.01, family=ga.GA_FAMILY_ADAM, adam_beta1=0.8, adam_beta2=0.95, adam_eps=1e-5, track_gap=True)
+    cfg, _ = ga.ga_get_config(A.ctx)
+    assert (cfg.family, cfg.track_gap, f(cfg.adam_beta1), f(cfg.adam_beta2), f(cfg.adam_eps)) == (ga.GA_FAMILY_ADAM, 1, f(0.8), f(0.95), f(1e-5))
 
 
 def test_theta0_and_setters():

@@ -316,20 +316,156 @@ def test_quadratic_gradient_is_the_gradient():
     assert np.allclose(g2 - g, 0.01 * oracle.noise_f32(5, 3, 0, N).astype(np.float64), rtol=0, atol=1e-12)
 
 
+def delayed_gradient_descent(schedule, W, a, ts, eta, divide_by_tau):
+    """theta_{k+1} = theta_k - eta_k grad f(theta_{k - tau_k}) (Sec. 2, the ASGD rule without momentum) written on
+    the whole history of iterates: the arriving worker's gradient is taken at the iterate that existed right after
+    its previous arrival (iterate 0 before its first).  SA: eta_k = eta / tau_k (Alg. 3 / Alg. 5 coincide for
+    gamma = 0)."""
+    hist = [np.zeros_like(ts)]
+    last = [0] * W
+    for k, w in enumerate(schedule, start=1):
+        tau = k - last[w]
+        stale = hist[k - tau]
+        lr = eta / tau if divide_by_tau else eta
+        hist.append(hist[-1] - lr * (a * (stale - ts)))
+        last[w] = k
+    return np.array(hist)
+
+
+@pytest.mark.parametrize("schedule_kind", ["round_robin", "simulated"])
+def test_without_momentum_the_master_is_delayed_gradient_descent(schedule_kind):
+    # gamma = 0, no noise: the snapshot mechanism of Alg. 2 / Alg. 5 ("save and send", theta^i) must reproduce
+    # the textbook recursion on stale iterates, step by step.  Round robin: tau_k = min(k, W) in closed form.
+    N, W, T, eta = 5, 4, 300, 0.1
+    a, ts = quad_inputs(N, 8, np.float64)
+    sched = (np.arange(T) % W).astype(np.uint32) if schedule_kind == "round_robin" else oracle.simulate_schedule(W, T, seed=4)
+    for mode, div in ((MODE_ASGD, False), (MODE_SA, True), (MODE_SA_STEP, True)):
+        ref = delayed_gradient_descent([int(w) for w in sched], W, a, ts, eta, div)
+        M = Master(N, W, mode, Hyper(eta, 0.0, f32=False), np.float64)
+        for k in range(T):
+            M.run_quadratic(sched[k:k + 1], a, ts, seed=0, sigma=0.0)
+            assert np.allclose(M.theta, ref[k + 1], rtol=1e-12, atol=1e-15), (mode, k)
+        if schedule_kind == "round_robin":
+            assert M.tau_log == [min(k, W) for k in range(1, T + 1)]
+
+
 def test_minimum_of_the_quadratic_is_reached():
-    # brute force on a tiny problem: the grid minimiser of f is theta*, and the
-    # noise-free trajectories of the penalised modes go there from theta_0 = 0 (to within
-    # 1% of the starting distance: the delayed momentum dynamics keep a small ripple).
-    N, W, T = 3, 3, 4000
+    # Brute force on a tiny problem: the grid minimiser of f is theta*.  Then, without momentum and without
+    # noise, every penalised master is x_{k+1} = x_k - c_k x_{k-d_k} for the error x = theta - theta*, with
+    # 0 < c_k <= eta a <= 0.1 (every penalty divides by a number >= 1) and a delay below W = 3 steps.  As long as
+    # x has not changed sign it shrinks by less than a factor 0.9 per step, so x_{k-d} <= x_k / 0.81 and
+    # c_k x_{k-d} < 0.13 x_k: the error never changes sign and never grows, in every coordinate, at every step.
+    # For SA the contraction is bounded as well: the stale error is at least the current one, so step k shrinks
+    # the error at least by the factor 1 - eta a / tau_k.
+    N, W, T, eta = 3, 3, 4000, 0.1
     a, ts = quad_inputs(N, 8, np.float64)
     grid = np.linspace(-4, 4, 161)
     for j in range(N):
         assert abs(grid[np.argmin(0.5 * a[j] * (grid - ts[j]) ** 2)] - ts[j]) <= 0.025 + 1e-12
     sched = oracle.simulate_schedule(W, T, seed=2)
     for mode in (MODE_SA, MODE_GA, MODE_GA_HINGE):
-        M = Master(N, W, mode, Hyper(f32=False), np.float64)
-        M.run_quadratic(sched, a, ts, seed=0, sigma=0.0)
-        assert np.abs(M.theta - ts).max() < 0.01 * np.abs(ts).max(), mode
+        M = Master(N, W, mode, Hyper(eta, 0.0, f32=False), np.float64)
+        err = [-ts.copy()]
+        for k in range(T):
+            M.run_quadratic(sched[k:k + 1], a, ts, seed=0, sigma=0.0)
+            err.append(M.theta - ts)
+        err = np.array(err)
+        live = np.abs(err[1:]) > 1e-12                                           # above the rounding floor of the run
+        assert np.all((np.sign(err[1:]) == np.sign(err[0])) | ~live), mode       # no overshoot
+        assert np.all((np.abs(err[1:]) <= np.abs(err[:-1])) | ~live), mode       # monotone
+        if mode == MODE_SA:
+            # the step of arrival k is eta a / tau_k times an error that is at least the current one
+            taus = np.array(M.tau_log)
+            rate = np.prod(1.0 - eta * a[None, :] / taus[:, None], axis=0)
+            assert np.all(np.abs(err[-1]) <= rate * np.abs(err[0]) + 1e-12)
+            assert np.abs(err[-1]).max() < 1e-6 * np.abs(ts).max()
+        else:
+            assert np.abs(err[-1]).max() < np.abs(err[0]).max()                  # descends; how fast is not fixed
+
+
+# ---------------------------------------------------------------- which vector feeds Alg. 14
+def gap_aware_in_numpy(sched, W, a, ts, eta, gamma, beta, eps, raw_input):
+    """Alg. 4 with Alg. 14 in plain numpy (double).  raw_input: Alg. 14 exactly as printed, with a momentum
+    buffer of its own fed by the raw gradient; otherwise the reading taken here, fed by the update vector."""
+    N = a.size
+    theta, v, u, m = np.zeros(N), np.zeros(N), np.zeros(N), np.zeros(N)
+    snaps = np.zeros((W, N))
+    c_sum = np.zeros(N)
+    for k, w in enumerate(sched, start=1):
+        g = a * (snaps[w] - ts)
+        mhat = m / (1.0 - beta ** (k - 1)) if k > 1 else np.zeros(N)
+        C = eta * (np.sqrt(mhat) + eps)
+        c_sum += C
+        G = np.abs(theta - snaps[w]) / C + 1.0
+        v = gamma * v + g / G
+        theta = theta - eta * v
+        u = gamma * u + g
+        fed = u if raw_input else v
+        m = beta * m + (1.0 - beta) * fed * fed
+        snaps[w] = theta
+    return theta, c_sum / len(sched)
+
+
+def test_reading_of_the_input_of_alg14_is_recorded():
+    # Alg. 14 prints v <- gamma v + g with the raw gradient; Alg. 4's v holds g / G.  This build keeps one v (the
+    # update vector) and feeds Alg. 14 with it.  The paper does not fix that choice, so nothing pins it: this test
+    # records what it changes.  (1) With one worker there is no Gap, G = 1, and both forms are the same numbers.
+    # (2) With eight workers the reading gives a smaller C (its input is the penalised vector), hence larger
+    # Gaps and a more cautious master; the oracle follows the reading to rounding.
+    N, T, eta, gamma, beta, eps = 64, 400, 0.1, 0.9, 0.999, 1e-8
+    a, ts = quad_inputs(N, 3, np.float64)
+    one = [0] * T
+    th_a, c_a = gap_aware_in_numpy(one, 1, a, ts, eta, gamma, beta, eps, raw_input=False)
+    th_b, c_b = gap_aware_in_numpy(one, 1, a, ts, eta, gamma, beta, eps, raw_input=True)
+    assert np.array_equal(th_a, th_b) and np.array_equal(c_a, c_b)
+    W = 8
+    sched = [int(w) for w in oracle.simulate_schedule(W, T, seed=3)]
+    th_v, c_v = gap_aware_in_numpy(sched, W, a, ts, eta, gamma, beta, eps, raw_input=False)
+    th_g, c_g = gap_aware_in_numpy(sched, W, a, ts, eta, gamma, beta, eps, raw_input=True)
+    M = Master(N, W, MODE_GA, Hyper(eta, gamma, beta=beta, eps=eps, f32=False), np.float64)
+    M.run_quadratic(np.array(sched, np.uint32), a, ts, seed=0, sigma=0.0)
+    assert np.allclose(M.theta, th_v, rtol=1e-9, atol=1e-12)               # the oracle is the reading
+    assert np.all(c_v < c_g)                                               # smaller scale C in every coordinate
+    ratio = float(np.mean(c_v / c_g))
+    apart = float(np.linalg.norm(th_v - th_g) / np.linalg.norm(ts))
+    print("mean C (update vector) / C (raw gradient) = %.3f; trajectories apart by %.3f of |theta*| after %d arrivals"
+          % (ratio, apart, T))
+    assert 0.05 < ratio < 0.95 and 1e-3 < apart < 1.0                      # a real difference, same order of size
+
+
+# ---------------------------------------------------------------- Gap statistics (App. C.8)
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+def test_gap_statistics_counters_on_dyadic_values(dtype):
+    # beta = 1/2, k = 1: 1/(1 - beta^k) = 2; m = 1/32 -> m-hat = 1/16, root 1/4; eps = 0, eta_max = 1/2 -> C = 1/8.
+    # |theta - theta^i| in {0, 1/16, 1/8, 1/4, inf, nan} gives Graw in {0, 1/2, 1, 2, inf, nan}: the parameters
+    # the paper's form penalises (Graw > 0) are three, those the hinge form penalises (Graw > 1, strictly) one,
+    # two are not finite and left out of the sum 1/2 + 1 + 2.
+    h = Hyper(eta=0.5, gamma=0.5, beta=0.5, eps=0.0, f32=(dtype == np.float32))
+    snap = np.array([3.0, -1.0, 0.5, 2.0, 1.0, 1.0], dtype)
+    diff = np.array([0.0, 0.0625, -0.125, 0.25, np.inf, np.nan], dtype)
+    theta = (snap + diff).astype(dtype)
+    m = np.full(6, 0.03125, dtype)
+    r = oracle.gap_statistics(theta, m, snap, 1, h)
+    assert (r["n_gt0"], r["n_gt1"], r["n_nonfinite"]) == (3, 1, 2)
+    assert r["sum_graw"] == 3.5 and r["mean_graw"] == 3.5 / 6
+    assert (r["frac_gt0"], r["frac_gt1"]) == (0.5, 1 / 6)
+    # one parameter at a time: each value lands in exactly the expected counters
+    expect = [(0, 0, 0, 0.0), (1, 0, 0, 0.5), (1, 0, 0, 1.0), (1, 1, 0, 2.0), (0, 0, 1, 0.0), (0, 0, 1, 0.0)]
+    for j, (gt0, gt1, bad, total) in enumerate(expect):
+        one = oracle.gap_statistics(theta[j:j + 1], m[j:j + 1], snap[j:j + 1], 1, h)
+        assert (one["n_gt0"], one["n_gt1"], one["n_nonfinite"], one["sum_graw"]) == (gt0, gt1, bad, total), j
+    # before any arrival (k = 0) m-hat_0 = 0: C = eta_max * eps, here 0, so a zero distance is 0/0 (not finite)
+    # and any other distance is infinite
+    z = oracle.gap_statistics(theta[:4], m[:4], snap[:4], 0, h)
+    assert (z["n_gt0"], z["n_gt1"], z["n_nonfinite"]) == (0, 0, 4)
+    # a master's own statistics use its state: after one arrival of worker 0 the Gap of worker 0 is zero everywhere
+    M = Master(4, 2, MODE_GA, Hyper(f32=(dtype == np.float32)), dtype)
+    M.apply(0, np.array([1.0, -2.0, 0.5, 4.0], dtype))
+    own, other = M.gap_statistics(0), M.gap_statistics(1)
+    assert (own["n_gt0"], own["sum_graw"]) == (0, 0.0)
+    # worker 1 still holds theta_0: distance eta |g|, C_1 = eta (|g| + eps) (Alg. 14 at k = 1), Graw just below 1
+    assert (other["n_gt0"], other["n_gt1"], other["n_nonfinite"]) == (4, 0, 0)
+    assert abs(other["mean_graw"] - 1.0) < 1e-6
 
 
 def test_float_tracks_double_on_a_stable_run():
