@@ -38,7 +38,8 @@ VALU_PER_UPDATE = {"ga": 106.7, "ga_hinge": 106.7}
 # scaled by a copy of known size; profiles/apply_kernel_cfg3.md).  The counters sit in front of the memory-side
 # cache, so hits in that cache are included.  Valid for the kernel source with this hash only.
 TRAFFIC = {
-    ("cfg3", "ga"): {"bytes": 920026388, "read": 511104880, "written": 408921508, "kernels_sha256": "720ea4dcbf4e9080"},
+    ("cfg3", "ga", 25_557_032): {"bytes": 920117019, "read": 511202945, "written": 408914074, "kernels_sha256": "a4f6ddc358882f61"},
+    ("cfg3", "ga", 151_000_000): {"bytes": 5435408561, "read": 3019394901, "written": 2416013660, "kernels_sha256": "a4f6ddc358882f61"},
 }
 BYTES_PER_UPDATE = {           # algorithmic bytes per parameter per arrival, fused update
     ("ga", "f32"): 36, ("ga", "bf16"): 34, ("ga_hinge", "f32"): 36, ("ga_hinge", "bf16"): 34,
@@ -207,7 +208,7 @@ def bench_fused(args, cfg, torch, ga, ga_inputs):
         for _ in range(3):
             dst.copy_(theta)
         torch.cuda.synchronize()
-    t = TRAFFIC.get((args.workload, args.mode))
+    t = TRAFFIC.get((args.workload, args.mode, N))
     traffic = t["bytes"] if t and t["kernels_sha256"] == kernels_hash() and args.gap_scope == "parameter" else None
     # of the algorithmic bytes, the part that HBM itself has to serve: the kernel keeps a leading part of theta, v, m
     # (RESIDENT_BYTES in all; each kept float saves one read and one write per arrival) in the memory-side cache
@@ -243,7 +244,7 @@ def streaming_leg(args, cfg, torch, ga, ga_inputs):
     a2 = argparse.Namespace(**vars(args))
     a2.steps, a2.warmup, a2.diag_every, a2.calibration_copy = leg["steps"], leg["warmup"], 0, False
     wall, roof, desc, _ = bench_fused(a2, c2, torch, ga, ga_inputs)
-    keys = ("achieved", "peak", "unit", "frac", "kernel", "bytes_per_update", "avg_launch_ms",
+    keys = ("achieved", "peak", "unit", "frac", "traffic", "kernel", "bytes_per_update", "avg_launch_ms",
             "algorithmic_bytes_per_launch", "hbm_only_bytes_per_update", "hbm_only_GBs", "hbm_only_frac",
             "cache_resident_bytes", "copy_GBs", "frac_of_copy")
     out = {"N": leg["N"], "n_workers": leg["W"], "steps": leg["steps"], "warmup": leg["warmup"], "workload": desc,

@@ -54,6 +54,11 @@
  * then on the host iter[i] = k.  The scalar 1/(1 - beta^(k-1)) is evaluated in
  * double and rounded once to float (Alg. 14 divides by 1 - beta^k and leaves
  * the rounding open; before the first arrival m-hat_0 = 0).
+ *
+ * Two choices above are readings that nothing in the paper pins: Alg. 14 is
+ * fed with the update vector v actually taken (it prints v <- gamma v + g with
+ * the raw gradient, while Alg. 4 keeps g / G in v; one v is kept here), and
+ * GA_MODE_GA_HINGE is a variant of this library, not the paper's penalty.
  */
 #ifndef GA_H
 #define GA_H

@@ -40,9 +40,20 @@
 // layers of one parameter against the parameter-wise Gap; gamma variates
 // against scipy's gamma distribution and the tail probabilities printed in
 // App. C.3 (27.9 % / 1 %); speed-up ratios against the values printed in App. D;
-// the Nesterov form with one worker against torch.optim.SGD(nesterov=True).
-// Parity unpinned: the hinge penalty max(1, |d|/C) is this project's variant,
-// pinned only by its definition (equals the paper's form with "+1" replaced).
+// the Nesterov form with one worker against torch.optim.SGD(nesterov=True);
+// without momentum every master against delayed gradient descent written on the
+// history of iterates (Sec. 2), with sign-preserving monotone descent for every
+// penalty; the Gap statistics' counters on hand-set dyadic values that make
+// |d|/C exactly 0, 1/2, 1, 2, inf, nan (App. C.8).
+// Parity unpinned (the paper fixes nothing to check these against):
+//   * the hinge penalty max(1, |d|/C): this project's variant, pinned only by
+//     its definition (the paper's form with "+1" replaced);
+//   * which vector feeds Alg. 14: Alg. 14 prints v <- gamma v + g with the raw
+//     gradient, Alg. 4 keeps g / G in v; here one v, the update vector actually
+//     taken, feeds it (for DANA the arriving worker's v_i, for Adam the update
+//     m-hat / (sqrt(v-hat) + eps), for the Nesterov form the step direction).
+//     A test records how far this is from the printed form;
+//   * the Nesterov form beyond one worker.
 
 #include <cmath>
 #include <cstdint>

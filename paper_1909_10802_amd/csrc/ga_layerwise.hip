@@ -67,15 +67,11 @@ __device__ __forceinline__ ChunkRange chunk_range(const LayerChunk& ch) {
     return r;
 }
 
-__global__ __launch_bounds__(kBlock) void layer_partial_kernel(const float* __restrict__ theta,
-                                                               const float* __restrict__ m,
-                                                               const float* __restrict__ snap,
-                                                               const LayerChunk* __restrict__ chunks,
-                                                               LayerPartial* __restrict__ partials) {
-    const ChunkRange r = chunk_range(chunks[blockIdx.x]);
-    double d2 = 0.0, ms = 0.0;
-    auto one = [&](float th, float s, float mm) { gap_terms(d2, ms, th, s, mm); };
-    for (uint64_t j = r.start + threadIdx.x; j < r.a0; j += kBlock) one(theta[j], snap[j], m[j]);
+// The 128-bit body of a chunk of the reduction pass; NT_TH: theta is read with the non-temporal hint.
+template <bool NT_TH>
+__device__ __forceinline__ void partial_body(const float* __restrict__ theta, const float* __restrict__ m,
+                                             const float* __restrict__ snap, const ChunkRange& r, double& d2,
+                                             double& ms) {
     const uint64_t q_end = r.a1 >> 2;
     for (uint64_t q0 = (r.a0 >> 2) + threadIdx.x; q0 < q_end; q0 += (uint64_t)kLayerU * kBlock) {
         f32x4 th[kLayerU], sv[kLayerU], mm[kLayerU];
@@ -83,7 +79,7 @@ __global__ __launch_bounds__(kBlock) void layer_partial_kernel(const float* __re
         for (int u = 0; u < kLayerU; ++u) {
             const uint64_t q = q0 + (uint64_t)u * kBlock;
             if (q < q_end) {
-                th[u] = load4<false>(theta, q);
+                th[u] = load4<NT_TH>(theta, q);
                 sv[u] = load4<true>(snap, q);
                 mm[u] = load4<true>(m, q);
             }
@@ -91,12 +87,27 @@ __global__ __launch_bounds__(kBlock) void layer_partial_kernel(const float* __re
 #pragma unroll
         for (int u = 0; u < kLayerU; ++u) {
             if (q0 + (uint64_t)u * kBlock < q_end) {
-                one(th[u].x, sv[u].x, mm[u].x); one(th[u].y, sv[u].y, mm[u].y);
-                one(th[u].z, sv[u].z, mm[u].z); one(th[u].w, sv[u].w, mm[u].w);
+                gap_terms(d2, ms, th[u].x, sv[u].x, mm[u].x); gap_terms(d2, ms, th[u].y, sv[u].y, mm[u].y);
+                gap_terms(d2, ms, th[u].z, sv[u].z, mm[u].z); gap_terms(d2, ms, th[u].w, sv[u].w, mm[u].w);
             }
         }
     }
-    for (uint64_t j = r.a1 + threadIdx.x; j < r.end; j += kBlock) one(theta[j], snap[j], m[j]);
+}
+
+// keep_theta: parameters [0, keep_theta) of theta are read without the hint (the part the update keeps in the
+// memory-side cache, see ga_device.h)
+__global__ __launch_bounds__(kBlock) void layer_partial_kernel(const float* __restrict__ theta,
+                                                               const float* __restrict__ m,
+                                                               const float* __restrict__ snap,
+                                                               const LayerChunk* __restrict__ chunks,
+                                                               LayerPartial* __restrict__ partials,
+                                                               uint64_t keep_theta) {
+    const ChunkRange r = chunk_range(chunks[blockIdx.x]);
+    double d2 = 0.0, ms = 0.0;
+    for (uint64_t j = r.start + threadIdx.x; j < r.a0; j += kBlock) gap_terms(d2, ms, theta[j], snap[j], m[j]);
+    if (r.end <= keep_theta) GA_HINT_PATH("theta kept", partial_body<false>(theta, m, snap, r, d2, ms));
+    else GA_HINT_PATH("all streamed", partial_body<true>(theta, m, snap, r, d2, ms));
+    for (uint64_t j = r.a1 + threadIdx.x; j < r.end; j += kBlock) gap_terms(d2, ms, theta[j], snap[j], m[j]);
     store_chunk_partial(d2, ms, partials + blockIdx.x);
 }
 
@@ -167,28 +178,12 @@ __device__ __forceinline__ void layer_update_one(float& th, float& v, float& m, 
     m = second_moment(m, dir, c);
 }
 
-// LOOK: also leave the chunk sums of the arrival that follows.  next_snap is the next worker's
-// snapshot, or null when the same worker arrives again (its snapshot is the theta written here:
-// the distance is zero).
-template <int DT, bool ALIGNED, bool STREAM_V, bool NAG, bool LOOK>
-__global__ __launch_bounds__(kBlock) void layer_apply_kernel(float* __restrict__ theta, float* __restrict__ v,
-                                                             float* __restrict__ m, float* __restrict__ snap,
-                                                             const void* __restrict__ g,
-                                                             const LayerChunk* __restrict__ chunks,
-                                                             const float* __restrict__ gaps, StepConst c,
-                                                             const float* __restrict__ next_snap,
-                                                             LayerPartial* __restrict__ partials) {
-    const LayerChunk ch = chunks[blockIdx.x];
-    const ChunkRange r = chunk_range(ch);
-    const float G = gaps[ch.layer];
-    double d2 = 0.0, ms = 0.0;
-    auto scalar = [&](uint64_t j) {
-        float t1 = theta[j], v1 = v[j], m1 = m[j];
-        layer_update_one<NAG>(t1, v1, m1, load_g1<DT>(g, j), G, c);
-        if constexpr (LOOK) gap_terms(d2, ms, t1, next_snap ? next_snap[j] : t1, m1);
-        theta[j] = t1; v[j] = v1; m[j] = m1; snap[j] = t1;
-    };
-    for (uint64_t j = r.start + threadIdx.x; j < r.a0; j += kBlock) scalar(j);
+// The 128-bit body of a chunk of the update pass.  NT_TH / NT_V: theta / v carry the non-temporal hint.
+template <int DT, bool ALIGNED, bool NAG, bool LOOK, bool NT_TH, bool NT_V>
+__device__ __forceinline__ void apply_body(float* __restrict__ theta, float* __restrict__ v, float* __restrict__ m,
+                                           float* __restrict__ snap, const void* __restrict__ g,
+                                           const ChunkRange& r, float G, const StepConst& c,
+                                           const float* __restrict__ next_snap, double& d2, double& ms) {
     constexpr int U = 2;
     const uint64_t q_end = r.a1 >> 2;
     for (uint64_t q0 = (r.a0 >> 2) + threadIdx.x; q0 < q_end; q0 += (uint64_t)U * kBlock) {
@@ -197,8 +192,8 @@ __global__ __launch_bounds__(kBlock) void layer_apply_kernel(float* __restrict__
         for (int u = 0; u < U; ++u) {
             const uint64_t q = q0 + (uint64_t)u * kBlock;
             if (q < q_end) {
-                th[u] = load4<false>(theta, q);
-                vv[u] = load4<STREAM_V>(v, q);
+                th[u] = load4<NT_TH>(theta, q);
+                vv[u] = load4<NT_V>(v, q);
                 mm[u] = load4<true>(m, q);
                 gg[u] = load_g4<DT, ALIGNED>(g, q);
                 if constexpr (LOOK)
@@ -216,13 +211,45 @@ __global__ __launch_bounds__(kBlock) void layer_apply_kernel(float* __restrict__
                     if constexpr (LOOK) gap_terms(d2, ms, t1, next_snap ? nx[u][e] : t1, m1);
                     th[u][e] = t1; vv[u][e] = v1; mm[u][e] = m1;
                 }
-                store4<false>(theta, q, th[u]);
-                store4<STREAM_V>(v, q, vv[u]);
+                store4<NT_TH>(theta, q, th[u]);
+                store4<NT_V>(v, q, vv[u]);
                 store4<true>(m, q, mm[u]);
                 store4<true>(snap, q, th[u]);
             }
         }
     }
+}
+
+// LOOK: also leave the chunk sums of the arrival that follows.  next_snap is the next worker's
+// snapshot, or null when the same worker arrives again (its snapshot is the theta written here:
+// the distance is zero).  keep_theta >= keep_v: the leading parameters whose theta / v stay in the
+// memory-side cache (accessed without the hint), as in the parameter-wise kernel.
+template <int DT, bool ALIGNED, bool NAG, bool LOOK>
+__global__ __launch_bounds__(kBlock) void layer_apply_kernel(float* __restrict__ theta, float* __restrict__ v,
+                                                             float* __restrict__ m, float* __restrict__ snap,
+                                                             const void* __restrict__ g,
+                                                             const LayerChunk* __restrict__ chunks,
+                                                             const float* __restrict__ gaps, StepConst c,
+                                                             const float* __restrict__ next_snap,
+                                                             LayerPartial* __restrict__ partials,
+                                                             uint64_t keep_theta, uint64_t keep_v) {
+    const LayerChunk ch = chunks[blockIdx.x];
+    const ChunkRange r = chunk_range(ch);
+    const float G = gaps[ch.layer];
+    double d2 = 0.0, ms = 0.0;
+    auto scalar = [&](uint64_t j) {
+        float t1 = theta[j], v1 = v[j], m1 = m[j];
+        layer_update_one<NAG>(t1, v1, m1, load_g1<DT>(g, j), G, c);
+        if constexpr (LOOK) gap_terms(d2, ms, t1, next_snap ? next_snap[j] : t1, m1);
+        theta[j] = t1; v[j] = v1; m[j] = m1; snap[j] = t1;
+    };
+    for (uint64_t j = r.start + threadIdx.x; j < r.a0; j += kBlock) scalar(j);
+#define GA_LAYER_BODY(NT_TH, NT_V) \
+    apply_body<DT, ALIGNED, NAG, LOOK, NT_TH, NT_V>(theta, v, m, snap, g, r, G, c, next_snap, d2, ms)
+    if (r.end > keep_theta) GA_HINT_PATH("all streamed", GA_LAYER_BODY(true, true));
+    else if (r.end > keep_v) GA_HINT_PATH("theta kept", GA_LAYER_BODY(false, true));
+    else GA_HINT_PATH("theta and v kept", GA_LAYER_BODY(false, false));
+#undef GA_LAYER_BODY
     for (uint64_t j = r.a1 + threadIdx.x; j < r.end; j += kBlock) scalar(j);
     if constexpr (LOOK) store_chunk_partial(d2, ms, partials + blockIdx.x);
 }
@@ -235,8 +262,13 @@ hipError_t launch_apply_layerwise(const StatePtrs& st, uint64_t N, uint32_t work
     if (lt.n_chunks == 0 || lt.n_layers == 0) return hipErrorInvalidValue;
     float* snap = st.snaps + (uint64_t)worker * st.stride;
     const dim3 block(kBlock), grid(lt.n_chunks), lgrid(lt.n_layers);
+    // leading parameters whose theta, then v, stay in the memory-side cache
+    const uint64_t budget = kResidentBytes / sizeof(float);
+    const uint64_t keep_theta = N < budget ? N : budget;
+    const uint64_t keep_v = N < budget - keep_theta ? N : budget - keep_theta;
     if (!sums_ready)
-        hipLaunchKernelGGL(layer_partial_kernel, grid, block, 0, stream, st.theta, st.m, snap, lt.chunks, lt.partials);
+        hipLaunchKernelGGL(layer_partial_kernel, grid, block, 0, stream, st.theta, st.m, snap, lt.chunks, lt.partials,
+                           keep_theta);
     if (mode == GA_MODE_GA_HINGE)
         hipLaunchKernelGGL(layer_gap_kernel<true>, lgrid, block, 0, stream, lt.partials, lt.spans, c.inv_bc_prev,
                            c.eta_max, c.eps, lt.gaps);
@@ -244,24 +276,23 @@ hipError_t launch_apply_layerwise(const StatePtrs& st, uint64_t N, uint32_t work
         hipLaunchKernelGGL(layer_gap_kernel<false>, lgrid, block, 0, stream, lt.partials, lt.spans, c.inv_bc_prev,
                            c.eta_max, c.eps, lt.gaps);
     const uintptr_t addr = reinterpret_cast<uintptr_t>(g);
-    const bool stream_v = 8 * N > kResidentBytes;   // theta and v both stay in the memory-side cache, or theta alone
     const bool look = next_worker >= 0;
     const float* next_snap =
         (look && (uint32_t)next_worker != worker) ? st.snaps + (uint64_t)next_worker * st.stride : nullptr;
-#define GA_LAYER_APPLY3(DT, AL, SV, NG, LK)                                                                         \
-    hipLaunchKernelGGL((layer_apply_kernel<DT, AL, SV, NG, LK>), grid, block, 0, stream, st.theta, st.v, st.m, snap, \
-                       g, lt.chunks, lt.gaps, c, next_snap, lt.partials)
-#define GA_LAYER_APPLY(DT, AL, SV)                                                                                  \
-    do {                                                                                                            \
-        if (nesterov) { if (look) GA_LAYER_APPLY3(DT, AL, SV, true, true); else GA_LAYER_APPLY3(DT, AL, SV, true, false); } \
-        else { if (look) GA_LAYER_APPLY3(DT, AL, SV, false, true); else GA_LAYER_APPLY3(DT, AL, SV, false, false); } \
+#define GA_LAYER_APPLY3(DT, AL, NG, LK)                                                                         \
+    hipLaunchKernelGGL((layer_apply_kernel<DT, AL, NG, LK>), grid, block, 0, stream, st.theta, st.v, st.m, snap, \
+                       g, lt.chunks, lt.gaps, c, next_snap, lt.partials, keep_theta, keep_v)
+#define GA_LAYER_APPLY(DT, AL)                                                                                  \
+    do {                                                                                                        \
+        if (nesterov) { if (look) GA_LAYER_APPLY3(DT, AL, true, true); else GA_LAYER_APPLY3(DT, AL, true, false); } \
+        else { if (look) GA_LAYER_APPLY3(DT, AL, false, true); else GA_LAYER_APPLY3(DT, AL, false, false); }    \
     } while (0)
     if (grad_dtype == GA_F32) {
-        if ((addr & 15u) == 0) { if (stream_v) GA_LAYER_APPLY(GA_F32, true, true); else GA_LAYER_APPLY(GA_F32, true, false); }
-        else { if (stream_v) GA_LAYER_APPLY(GA_F32, false, true); else GA_LAYER_APPLY(GA_F32, false, false); }
+        if ((addr & 15u) == 0) GA_LAYER_APPLY(GA_F32, true);
+        else GA_LAYER_APPLY(GA_F32, false);
     } else {
-        if ((addr & 7u) == 0) { if (stream_v) GA_LAYER_APPLY(GA_BF16, true, true); else GA_LAYER_APPLY(GA_BF16, true, false); }
-        else { if (stream_v) GA_LAYER_APPLY(GA_BF16, false, true); else GA_LAYER_APPLY(GA_BF16, false, false); }
+        if ((addr & 7u) == 0) GA_LAYER_APPLY(GA_BF16, true);
+        else GA_LAYER_APPLY(GA_BF16, false);
     }
 #undef GA_LAYER_APPLY
 #undef GA_LAYER_APPLY3

@@ -352,9 +352,11 @@ def test_without_momentum_the_master_is_delayed_gradient_descent(schedule_kind):
 def test_minimum_of_the_quadratic_is_reached():
     # Brute force on a tiny problem: the grid minimiser of f is theta*.  Then, without momentum and without
     # noise, every penalised master is x_{k+1} = x_k - c_k x_{k-d_k} for the error x = theta - theta*, with
-    # 0 < c_k <= eta a <= 0.1 (every penalty divides by a number >= 1) and a delay below W = 3 steps.  As long as
-    # x has not changed sign it shrinks by less than a factor 0.9 per step, so x_{k-d} <= x_k / 0.81 and
-    # c_k x_{k-d} < 0.13 x_k: the error never changes sign and never grows, in every coordinate, at every step.
+    # 0 < c_k <= c = eta max(a) (every penalty divides by a number >= 1) and d_k = tau_k - 1.  If the error keeps
+    # its sign and shrinks per step by no more than a factor rho, then x_{k-d} <= x_k rho^-d, and the step is
+    # self-consistent when c_k rho^-d_k <= 1 - rho: the error never changes sign and never grows.
+    #   * round robin over W = 3 workers (d = 2), any penalty: c rho^-2 <= 1 - rho holds for rho = 0.9, c <= 0.081;
+    #   * simulated schedule, SA: c_k = c / tau_k, and (c / tau) rho^-(tau - 1) <= 1 - rho for every delay that occurs.
     # For SA the contraction is bounded as well: the stale error is at least the current one, so step k shrinks
     # the error at least by the factor 1 - eta a / tau_k.
     N, W, T, eta = 3, 3, 4000, 0.1
@@ -362,8 +364,13 @@ def test_minimum_of_the_quadratic_is_reached():
     grid = np.linspace(-4, 4, 161)
     for j in range(N):
         assert abs(grid[np.argmin(0.5 * a[j] * (grid - ts[j]) ** 2)] - ts[j]) <= 0.025 + 1e-12
-    sched = oracle.simulate_schedule(W, T, seed=2)
-    for mode in (MODE_SA, MODE_GA, MODE_GA_HINGE):
+    c, rho = eta * a.max(), 0.9
+    assert c * rho ** -2 <= 1 - rho
+    simulated = oracle.simulate_schedule(W, T, seed=2)
+    taus = oracle.delays(W, simulated)[0].astype(np.float64)
+    assert np.all(c / taus * rho ** -(taus - 1) <= 1 - rho)
+    round_robin = (np.arange(T) % W).astype(np.uint32)
+    for mode, sched in ((MODE_SA, simulated), (MODE_SA, round_robin), (MODE_GA, round_robin), (MODE_GA_HINGE, round_robin)):
         M = Master(N, W, mode, Hyper(eta, 0.0, f32=False), np.float64)
         err = [-ts.copy()]
         for k in range(T):
@@ -374,9 +381,7 @@ def test_minimum_of_the_quadratic_is_reached():
         assert np.all((np.sign(err[1:]) == np.sign(err[0])) | ~live), mode       # no overshoot
         assert np.all((np.abs(err[1:]) <= np.abs(err[:-1])) | ~live), mode       # monotone
         if mode == MODE_SA:
-            # the step of arrival k is eta a / tau_k times an error that is at least the current one
-            taus = np.array(M.tau_log)
-            rate = np.prod(1.0 - eta * a[None, :] / taus[:, None], axis=0)
+            rate = np.prod(1.0 - eta * a[None, :] / np.array(M.tau_log)[:, None], axis=0)
             assert np.all(np.abs(err[-1]) <= rate * np.abs(err[0]) + 1e-12)
             assert np.abs(err[-1]).max() < 1e-6 * np.abs(ts).max()
         else:
