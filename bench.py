@@ -68,6 +68,10 @@ def parse():
     p.add_argument("--queue", type=int, default=0,
                    help="buffer workloads: apply the arrivals as queues of this many per launch (the persistent kernel "
                         "fed from the gradient buffers) instead of one launch per arrival")
+    p.add_argument("--ceiling", action="store_true",
+                   help="instead of a workload, measure what the part delivers for the kernels' access pattern and "
+                        "instruction mix (stream counts at --n floats per array, default 151,000,000; vector "
+                        "instruction rates) and print them as one JSON line")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--calibration-copy", action="store_true",
                    help="after the timed region run three plain device copies of N floats (known size: 4N bytes read, "
@@ -367,6 +371,41 @@ def cpu_baseline_quadratic(cfg, mode, n_slice, n_steps):
                       % (n_slice, W, n_steps - 8, dt)}
 
 
+def ceiling(args, torch, ga):
+    """Rates of the measurement aids of the library (ga_probe_streams, ga_probe_valu), events on the current stream."""
+    dev = "cuda:0"
+    n = (args.n or 151_000_000) // 4 * 4
+    bufs = [torch.full((n,), 0.5 + i, dtype=torch.float32, device=dev) for i in range(9)]
+
+    def timed(launch, reps):
+        for _ in range(3):
+            launch()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            launch()
+        e1.record()
+        e1.synchronize()
+        return e0.elapsed_time(e1) * 1e-3 / reps
+
+    streams = {}
+    for r, w in ((1, 0), (5, 0), (0, 1), (0, 4), (1, 1), (2, 2), (4, 4), (5, 1), (5, 2), (5, 4)):
+        s = timed(lambda: ga.ga_probe_streams(bufs[:r], bufs[5:5 + w], n), 20)
+        streams["%dr%dw" % (r, w)] = 4.0 * (r + w) * n / s / 1e9
+    del bufs
+    torch.cuda.empty_cache()
+    out = torch.zeros(1, dtype=torch.int32, device=dev)
+    blocks, iters = 8 * torch.cuda.get_device_properties(0).multi_processor_count, 4096
+    valu = {}
+    for op in ga.PROBE_OPS:
+        s = timed(lambda: ga.ga_probe_valu(op, blocks, iters, out), 5)
+        valu[op] = blocks * 256.0 * iters * 8 / s / 1e12
+    return {"n_floats_per_array": n, "stream_GBs": streams, "valu_T_lane_ops_per_s": valu,
+            "valu_probe": "%d blocks of 256 threads x %d iterations x 8 independent instructions" % (blocks, iters),
+            "hbm_peak_GBs": HBM_PEAK_GBS, "alu_peak_T_lane_ops_per_s": ALU_PEAK_TLOPS}
+
+
 def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -379,6 +418,10 @@ def main():
     import ga_inputs
     import paper_1909_10802_amd as ga
 
+    if args.ceiling:
+        torch.cuda.set_device(0)
+        print(json.dumps({"ceiling": ceiling(args, torch, ga)}))
+        return
     cfg = dict(ga_inputs.WORKLOADS[args.workload])
     if args.n is not None:
         cfg["N"] = args.n

@@ -486,6 +486,41 @@ int ga_noise_fill(uint64_t seed, uint64_t k, uint64_t j0, uint64_t n, float* dev
 int ga_box_muller_raw(const uint32_t* dev_xa, const uint32_t* dev_xb, uint64_t n, float* dev_zc, float* dev_zs,
                       void* hip_stream);
 
+/* ------------------------------------------------------------ measurement aids
+ * Behind `bench.py --ceiling`.  They run none of the arithmetic above: they
+ * measure what the part delivers for the access pattern and the instruction
+ * mix of the kernels, so that the roofline fractions quoted for the kernels
+ * can be re-derived on any machine.  The caller times them with events on
+ * hip_stream.
+ *
+ * ga_probe_streams: one launch that reads n_read arrays and writes n_write
+ *   arrays of n floats at once (element-wise sum of the inputs to every
+ *   output), with the 128-bit non-temporal accesses and the launch shape of
+ *   the fused update.  host_dev_read / host_dev_write are HOST arrays of
+ *   DEVICE pointers (16-byte aligned, at least n floats each; n a multiple of
+ *   4).  n_read in {0, 1, 2, 4, 5}, n_write in {0, 1, 2, 4}, not both 0.
+ *   Sec. 4.3 makes the update elementwise, which is why a stream count is all
+ *   that characterises its memory side: the GA update is 5 reads + 4 writes.
+ * ga_probe_valu: blocks x 256 threads, each issuing iterations x 8 independent
+ *   vector instructions of kind `op` (ga_probe_op); dev_out: 4 bytes, written
+ *   only formally.  8 x 256 blocks give 8 wavefronts per SIMD on 256 CUs.
+ * Errors: GA_ERR_ARG (counts outside the lists, null or misaligned pointers,
+ * unknown op), GA_ERR_HIP. */
+enum ga_probe_op {
+    GA_PROBE_FMA = 0,        /* v_fma_f32 */
+    GA_PROBE_XOR = 1,        /* v_xor_b32 */
+    GA_PROBE_MUL_HI = 2,     /* v_mul_hi_u32 */
+    GA_PROBE_MAD_U64 = 3,    /* v_mad_u64_u32 (Philox's 32 x 32 -> 64 products) */
+    GA_PROBE_RCP = 4,        /* v_rcp_f32 */
+    GA_PROBE_SQRT = 5,       /* v_sqrt_f32 */
+    GA_PROBE_DIV_SCALE = 6,  /* v_div_scale_f32 */
+    GA_PROBE_DIV_FMAS = 7,   /* v_div_fmas_f32 */
+    GA_PROBE_DIV_FIXUP = 8   /* v_div_fixup_f32 (the three helpers of a correctly rounded division) */
+};
+int ga_probe_streams(uint32_t n_read, uint32_t n_write, uint64_t n, const float* const* host_dev_read,
+                     float* const* host_dev_write, void* hip_stream);
+int ga_probe_valu(int op, uint32_t blocks, uint32_t iterations, uint32_t* dev_out, void* hip_stream);
+
 /* Message of the last error on this context ("" if none).  ctx may be null:
  * then the message of the last failed ga_create on this thread. */
 const char* ga_last_error(const ga_ctx* ctx);

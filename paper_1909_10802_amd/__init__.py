@@ -116,6 +116,8 @@ SIGNATURES = {
     "ga_export_state": (_i, [_p, _p, C.c_size_t, C.POINTER(_u64), _p]),
     "ga_import_state": (_i, [_p, _p, C.c_size_t, _u64, _p]),
     "ga_noise_fill": (_i, [_u64, _u64, _u64, _u64, _p, _p]),
+    "ga_probe_streams": (_i, [_u32, _u32, _u64, _p, _p, _p]),
+    "ga_probe_valu": (_i, [_i, _u32, _u32, _p, _p]),
     "ga_box_muller_raw": (_i, [_p, _p, _u64, _p, _p, _p]),
     "ga_last_error": (C.c_char_p, [_p]),
     "ga_version": (C.c_char_p, []),
@@ -487,6 +489,23 @@ def ga_box_muller_raw(dev_xa, dev_xb, dev_zc, dev_zs, stream=None):
     assert dev_xb.numel() == n and dev_zc.numel() == n and dev_zs.numel() == n
     _check(lib().ga_box_muller_raw(_dev(dev_xa, torch.int32), _dev(dev_xb, torch.int32), n, _dev(dev_zc, torch.float32),
                                    _dev(dev_zs, torch.float32), _stream_ptr(stream)))
+
+
+PROBE_OPS = {"v_fma_f32": 0, "v_xor_b32": 1, "v_mul_hi_u32": 2, "v_mad_u64_u32": 3, "v_rcp_f32": 4, "v_sqrt_f32": 5,
+             "v_div_scale_f32": 6, "v_div_fmas_f32": 7, "v_div_fixup_f32": 8}
+
+
+def ga_probe_streams(reads, writes, n, stream=None):
+    """reads / writes: lists of float32 CUDA tensors of at least n elements."""
+    import torch
+    r = (C.c_void_p * max(1, len(reads)))(*[_dev(t, torch.float32, n) for t in reads])
+    w = (C.c_void_p * max(1, len(writes)))(*[_dev(t, torch.float32, n) for t in writes])
+    _check(lib().ga_probe_streams(len(reads), len(writes), n, r, w, _stream_ptr(stream)))
+
+
+def ga_probe_valu(op, blocks, iterations, dev_out, stream=None):
+    import torch
+    _check(lib().ga_probe_valu(PROBE_OPS.get(op, op), blocks, iterations, _dev(dev_out, torch.int32, 1), _stream_ptr(stream)))
 
 
 def ga_version():

@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libga.so")
-SOURCES = ["ga_apply.hip", "ga_persistent.hip", "ga_batched.hip", "ga_layerwise.hip", "ga_aux.hip", "ga_host.cpp"]
+SOURCES = ["ga_apply.hip", "ga_persistent.hip", "ga_batched.hip", "ga_layerwise.hip", "ga_aux.hip", "ga_probe.hip", "ga_host.cpp"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

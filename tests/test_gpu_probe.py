@@ -1,0 +1,41 @@
+"""The measurement aids behind `bench.py --ceiling` (needs an MI355X): they must touch exactly what they claim to."""
+import numpy as np
+import pytest
+import torch
+
+import paper_1909_10802_amd as ga
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("n_read,n_write", [(1, 1), (5, 4), (2, 0), (0, 2), (4, 1)])
+def test_stream_probe_reads_and_writes_the_named_arrays(n_read, n_write):
+    n = 4 * 70_001                                               # several blocks and a ragged last one
+    guard = 64
+    reads = [torch.full((n + guard,), float(i + 1), device="cuda:0") for i in range(n_read)]
+    writes = [torch.full((n + guard,), -7.0, device="cuda:0") for _ in range(n_write)]
+    ga.ga_probe_streams(reads, writes, n)
+    torch.cuda.synchronize()
+    total = float(sum(range(1, n_read + 1)))
+    for i, w in enumerate(writes):
+        h = w.cpu().numpy()
+        assert np.all(h[:n] == total + i) and np.all(h[n:] == -7.0)
+    for i, r in enumerate(reads):
+        assert bool((r == float(i + 1)).all())
+
+
+def test_probe_argument_errors():
+    x = torch.zeros(64, device="cuda:0")
+    out = torch.zeros(1, dtype=torch.int32, device="cuda:0")
+    with pytest.raises(ga.GaError):
+        ga.ga_probe_streams([x] * 3, [x], 64)                    # three read streams are not offered
+    with pytest.raises(ga.GaError):
+        ga.ga_probe_streams([], [], 64)
+    with pytest.raises(ga.GaError):
+        ga.ga_probe_streams([x], [x], 62)                        # not a multiple of four
+    with pytest.raises(ga.GaError):
+        ga.ga_probe_valu(99, 8, 8, out)
+    for op in ga.PROBE_OPS:
+        ga.ga_probe_valu(op, 4, 16, out)
+    torch.cuda.synchronize()
+    assert int(out.item()) == 0
