@@ -52,7 +52,10 @@ def parse():
     p = argparse.ArgumentParser()
     p.add_argument("--gpus", type=int, default=1)
     p.add_argument("--steps", type=int, default=None, help="arrivals to time (default: the workload's own count)")
-    p.add_argument("--warmup", type=int, default=100)
+    p.add_argument("--warmup", type=int, default=None,
+                   help="untimed arrivals before the timed ones (default: 100 for the gradient-buffer workloads; one "
+                        "pass of the workload's own count for the persistent-kernel workloads, whose first launch of "
+                        "a given length runs slower than the following ones)")
     p.add_argument("--workload", default="cfg3", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
     p.add_argument("--n", type=int, default=None, help="override the workload's number of parameters")
     p.add_argument("--workers", type=int, default=None, help="override the workload's number of workers")
@@ -433,6 +436,8 @@ def main():
         cfg["n_bufs"] = args.bufs
     if args.steps is None:
         args.steps = cfg["T"]
+    if args.warmup is None:
+        args.warmup = 100 if cfg["source"] == "buffers" else cfg["T"]
     torch.cuda.set_device(0)
     fused = cfg["source"] == "buffers"
     if not fused and args.gap_scope != "parameter":
