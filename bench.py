@@ -179,7 +179,8 @@ def bench_fused(args, cfg, torch, ga, ga_inputs):
 
     seg = args.diag_every if args.diag_every > 0 else K
     events = []
-    last_diag = None
+    n_seg = (K + seg - 1) // seg
+    reports = torch.zeros((n_seg, ga.DIAG_BYTES), dtype=torch.uint8, device=dev)   # one Gap report per segment
     t0 = time.perf_counter()
     done = 0
     while done < K:
@@ -190,10 +191,11 @@ def bench_fused(args, cfg, torch, ga, ga_inputs):
         e1.record()
         events.append((e0, e1))
         done += n
-        if args.diag_every > 0:                                    # the Gap the next arrival will meet
-            last_diag = M.diagnostics(int(sched[Wm + done]))
+        if args.diag_every > 0:                                    # the Gap the next arrival will meet; nothing waits
+            M.diagnostics_async(int(sched[Wm + done]), reports[len(events) - 1])
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
+    last_diag = ga.diag_from_device(reports[n_seg - 1]) if args.diag_every > 0 else None
 
     kernel_ms = sum(a.elapsed_time(b) for a, b in events) / K      # average per launch, on the kernel's stream
     bpu = BYTES_PER_UPDATE[(args.mode, cfg["grad_dtype"])]
