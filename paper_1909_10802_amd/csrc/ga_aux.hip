@@ -112,28 +112,27 @@ __device__ __forceinline__ DiagPartial block_reduce(double sum, unsigned long lo
     return r;
 }
 
-__global__ __launch_bounds__(kBlock) void diag_kernel(const float* __restrict__ theta, const float* __restrict__ m,
-                                                      const float* __restrict__ snap, uint64_t N, float inv_bc,
-                                                      float eta_max, float eps,
-                                                      DiagPartial* __restrict__ partials) {
-    const uint64_t n4 = N >> 2;
-    DiagAcc acc = {0.0, 0u, 0u, 0u};
-    constexpr int U = 4;   // groups in flight per thread; the accumulation keeps its order
-    const uint64_t stride = (uint64_t)gridDim.x * kBlock;
-    for (uint64_t q0 = (uint64_t)blockIdx.x * kBlock + threadIdx.x; q0 < n4; q0 += U * stride) {
+// One thread's groups i = i0, i0+1, ... (< i1) of its grid-stride sequence q = q_first + i * stride, four in
+// flight; the accumulation keeps the order of i.  NT_TH: theta is read with the non-temporal hint.
+template <bool NT_TH>
+__device__ __forceinline__ void diag_span(DiagAcc& acc, const float* __restrict__ theta, const float* __restrict__ m,
+                                          const float* __restrict__ snap, uint64_t q_first, uint64_t stride,
+                                          uint64_t i0, uint64_t i1, float inv_bc, float eta_max, float eps) {
+    constexpr int U = 4;
+    for (uint64_t i = i0; i < i1; i += U) {
         f32x4 th[U], s[U], mm[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const uint64_t q = q0 + u * stride;
-            if (q < n4) {
-                th[u] = load4<false>(theta, q);
+            if (i + u < i1) {
+                const uint64_t q = q_first + (i + u) * stride;
+                th[u] = load4<NT_TH>(theta, q);
                 s[u] = load4<true>(snap, q);
                 mm[u] = load4<true>(m, q);
             }
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            if (q0 + u * stride < n4) {
+            if (i + u < i1) {
                 diag_one(acc, th[u].x, s[u].x, mm[u].x, inv_bc, eta_max, eps);
                 diag_one(acc, th[u].y, s[u].y, mm[u].y, inv_bc, eta_max, eps);
                 diag_one(acc, th[u].z, s[u].z, mm[u].z, inv_bc, eta_max, eps);
@@ -141,6 +140,23 @@ __global__ __launch_bounds__(kBlock) void diag_kernel(const float* __restrict__ 
             }
         }
     }
+}
+
+// keep_q: groups [0, keep_q) of theta are read without the hint (the part the update kernels keep in the
+// memory-side cache); reading the rest of theta without it would push that part out.
+__global__ __launch_bounds__(kBlock) void diag_kernel(const float* __restrict__ theta, const float* __restrict__ m,
+                                                      const float* __restrict__ snap, uint64_t N, float inv_bc,
+                                                      float eta_max, float eps, uint64_t keep_q,
+                                                      DiagPartial* __restrict__ partials) {
+    const uint64_t n4 = N >> 2;
+    DiagAcc acc = {0.0, 0u, 0u, 0u};
+    const uint64_t stride = (uint64_t)gridDim.x * kBlock;
+    const uint64_t q_first = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+    const uint64_t n_all = q_first < n4 ? (n4 - q_first + stride - 1) / stride : 0;        // this thread's groups
+    const uint64_t lim = keep_q < n4 ? keep_q : n4;
+    const uint64_t n_kept = q_first < lim ? (lim - q_first + stride - 1) / stride : 0;     // those below keep_q
+    GA_HINT_PATH("theta kept", diag_span<false>(acc, theta, m, snap, q_first, stride, 0, n_kept, inv_bc, eta_max, eps));
+    GA_HINT_PATH("all streamed", diag_span<true>(acc, theta, m, snap, q_first, stride, n_kept, n_all, inv_bc, eta_max, eps));
     if (blockIdx.x == 0 && threadIdx.x < (N & 3)) {
         const uint64_t j = 4 * n4 + threadIdx.x;
         diag_one(acc, theta[j], snap[j], m[j], inv_bc, eta_max, eps);
@@ -226,7 +242,8 @@ hipError_t launch_diagnostics(const StatePtrs& st, uint64_t N, uint32_t worker, 
                               float eps, DiagPartial* dev_partials, ga_diag* dev_report, hipStream_t stream) {
     const uint32_t grid = blocks_for(N >> 2, (uint64_t)kBlock * 4, kDiagMaxBlocks);
     hipLaunchKernelGGL(diag_kernel, dim3(grid), dim3(kBlock), 0, stream, st.theta, st.m,
-                       st.snaps + (uint64_t)worker * st.stride, N, inv_bc, eta_max, eps, dev_partials);
+                       st.snaps + (uint64_t)worker * st.stride, N, inv_bc, eta_max, eps,
+                       kResidentBytes / sizeof(f32x4), dev_partials);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (dev_report)
@@ -262,7 +279,7 @@ hipError_t launch_diagnostics_static(const float* theta, const float* snap, cons
     // every partial that the report kernel reads is written by this launch first: nothing has to start at zero
     const uint32_t grid = blocks_for(N >> 2, (uint64_t)kBlock * 4, kDiagMaxBlocks);
     hipLaunchKernelGGL(diag_kernel, dim3(grid), dim3(kBlock), 0, stream, theta, m, snap, N, inv_bc, eta_max, eps,
-                       partials);
+                       kResidentBytes / sizeof(f32x4), partials);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(diag_report_kernel, dim3(1), dim3(kBlock), 0, stream, partials, grid, N, dev_report);
