@@ -29,7 +29,6 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
-RESIDENT_BYTES = 240 << 20     # part of theta, v, m the fused update keeps in the memory-side cache (kResidentBytes, csrc/ga_device.h)
 STREAMING_LEG = dict(N=151_000_000, W=8, n_bufs=8, steps=300, warmup=24)   # Transformer-XL-base size (Sec. 6)
 ALU_PEAK_TLOPS = 78.65         # fp32 vector 157.3 TFLOP/s / 2 flop per lane-operation
 # VALU lane-operations per parameter-update of the persistent kernel (SQ_INSTS_VALU * 64 / updates, profiles/)
@@ -60,6 +59,8 @@ def parse():
     p.add_argument("--n", type=int, default=None, help="override the workload's number of parameters")
     p.add_argument("--workers", type=int, default=None, help="override the workload's number of workers")
     p.add_argument("--bufs", type=int, default=None, help="buffer workloads: override the number of gradient buffers")
+    p.add_argument("--resident-mib", type=float, default=None,
+                   help="fused-update workloads: MiB of theta, v, m kept in the memory-side cache (library default 240)")
     p.add_argument("--no-streaming-leg", action="store_true",
                    help="default workload only: skip the second leg at N = 151,000,000")
     p.add_argument("--family", default="momentum", choices=["momentum", "dana", "adam"],
@@ -172,6 +173,9 @@ def bench_fused(args, cfg, torch, ga, ga_inputs):
         scope_kw = dict(layer_sizes=ga_inputs.tensor_sizes(N, cfg.get("n_tensors", 161), seed))
     M = ga.Master(N, W, eta=eta, gamma=cfg["gamma"], mode=args.mode, device=dev, family=args.family,
                   track_gap=(args.diag_every > 0), **scope_kw)
+    if args.resident_mib is not None:
+        ga.ga_set_resident_bytes(M.ctx, int(args.resident_mib * (1 << 20)))
+    resident = ga.ga_get_resident_bytes(M.ctx)
     M.run_schedule(sched[:Wm], src)
     if args.diag_every > 0:
         M.diagnostics(int(sched[0]))
@@ -220,9 +224,9 @@ def bench_fused(args, cfg, torch, ga, ga_inputs):
     t = TRAFFIC.get((args.workload, args.mode, N))
     traffic = t["bytes"] if t and t["kernels_sha256"] == kernels_hash() and args.gap_scope == "parameter" else None
     # of the algorithmic bytes, the part that HBM itself has to serve: the kernel keeps a leading part of theta, v, m
-    # (RESIDENT_BYTES in all; each kept float saves one read and one write per arrival) in the memory-side cache
+    # (ga_get_resident_bytes in all; each kept float saves one read and one write per arrival) in the memory-side cache
     n_hot = {"momentum": 3 if (args.mode in ("ga", "ga_hinge") or args.diag_every > 0) else 2}.get(args.family, 2)
-    kept = min(RESIDENT_BYTES, 4 * N * n_hot)
+    kept = min(resident, 4 * N * n_hot)
     hbm_only_bpu = bpu - 2.0 * kept / N
     roof = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
             "traffic": traffic if args.family == "momentum" else None,

@@ -325,6 +325,16 @@ int ga_set_lr(ga_ctx* ctx, float eta_k);
  * Gap under SA / ASGD (costs 8 bytes per parameter per arrival).  Only before
  * the first arrival. */
 int ga_set_track_gap(ga_ctx* ctx, int on);
+/* How many bytes of theta, v, m (theta first) the update kernels of this
+ * master keep in the memory-side cache between arrivals: the leading part of
+ * the arrays is accessed without the non-temporal hint, everything else is
+ * streamed around the cache.  Default 240 MiB of the MI355X's 256 MiB, right
+ * for one master per GPU; masters that share a GPU (or share it with other
+ * users of that cache) should split it, and 0 streams everything.  A budget
+ * above what the cache holds makes the kept lines evict each other and is
+ * slower than 0.  Changes no result, only speed; legal at any step. */
+int ga_set_resident_bytes(ga_ctx* ctx, uint64_t bytes);
+uint64_t ga_get_resident_bytes(const ga_ctx* ctx);
 /* theta_0: copy N floats from dev_theta0 into theta and into every snapshot
  * (App. C.1: theta^i = theta_0).  Only before the first arrival. */
 int ga_set_theta(ga_ctx* ctx, const float* dev_theta0);

@@ -90,6 +90,8 @@ SIGNATURES = {
     "ga_set_lr": (_i, [_p, _f]),
     "ga_set_track_gap": (_i, [_p, _i]),
     "ga_set_theta": (_i, [_p, _p]),
+    "ga_set_resident_bytes": (_i, [_p, _u64]),
+    "ga_get_resident_bytes": (_u64, [_p]),
     "ga_apply": (_i, [_p, _u32, _p, _i]),
     "ga_apply_queue": (_i, [_p, _u64, _p, _p, _i]),
     "ga_run_schedule": (_i, [_p, _p, _u64, C.POINTER(ga_grad_source)]),
@@ -451,6 +453,14 @@ def ga_get_config(ctx):
     cfg, eta_k = ga_config(), _f()
     _check(lib().ga_get_config(ctx, C.byref(cfg), C.byref(eta_k)), ctx)
     return cfg, eta_k.value
+
+
+def ga_set_resident_bytes(ctx, n_bytes):
+    _check(lib().ga_set_resident_bytes(ctx, n_bytes), ctx)
+
+
+def ga_get_resident_bytes(ctx):
+    return lib().ga_get_resident_bytes(ctx)
 
 
 def ga_set_bookkeeping(ctx, k, host_iter):

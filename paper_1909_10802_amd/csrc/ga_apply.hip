@@ -177,7 +177,7 @@ hipError_t launch_apply_u(const StatePtrs& st, float* snap, const void* g, uint6
     const uint64_t blocks = (n4 + per_block - 1) / per_block;
     if (blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
     const dim3 grid(blocks == 0 ? 1u : (uint32_t)blocks), block(kBlock);
-    const Residency keep = residency_for(grid.x, per_block * sizeof(f32x4), true, KEEP_M);
+    const Residency keep = residency_for(st.resident_bytes, grid.x, per_block * sizeof(f32x4), true, KEEP_M);
     hipLaunchKernelGGL((apply_kernel<MODE, DT, KEEP_M, SNAP, ALIGNED, U>), grid, block, 0, stream, st.theta, st.v,
                        st.m, snap, g, N, c, keep);
     return hipGetLastError();
@@ -221,13 +221,13 @@ constexpr int kFamilyU = 1;
 
 template <int FAMILY, int MODE, int DT, bool KEEP_M, bool SNAP, bool ALIGNED>
 hipError_t launch_family_t(float* theta, float* x, float* y, float* m, float* snap, const void* g, uint64_t N,
-                           const StepConst& c, hipStream_t stream) {
+                           const StepConst& c, uint64_t resident_bytes, hipStream_t stream) {
     const uint64_t n4 = N >> 2;
     const uint64_t per_block = (uint64_t)kBlock * kFamilyU;
     const uint64_t blocks = (n4 + per_block - 1) / per_block;
     if (blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
     const dim3 grid(blocks == 0 ? 1u : (uint32_t)blocks), block(kBlock);
-    const Residency keep = residency_for(grid.x, per_block * sizeof(f32x4), true, false);
+    const Residency keep = residency_for(resident_bytes, grid.x, per_block * sizeof(f32x4), true, false);
     hipLaunchKernelGGL((family_apply_kernel<FAMILY, MODE, DT, KEEP_M, SNAP, ALIGNED, kFamilyU>), grid, block, 0,
                        stream, theta, x, y, m, snap, g, N, c, keep);
     return hipGetLastError();
@@ -235,22 +235,24 @@ hipError_t launch_family_t(float* theta, float* x, float* y, float* m, float* sn
 
 template <int FAMILY, int MODE, bool KEEP_M, bool SNAP>
 hipError_t launch_family_m(float* theta, float* x, float* y, float* m, float* snap, const void* g, int dt,
-                           uint64_t N, const StepConst& c, hipStream_t stream) {
+                           uint64_t N, const StepConst& c, uint64_t resident_bytes, hipStream_t stream) {
     const uintptr_t addr = reinterpret_cast<uintptr_t>(g);
     if (dt == GA_F32) {
         if ((addr & 15u) == 0)
-            return launch_family_t<FAMILY, MODE, GA_F32, KEEP_M, SNAP, true>(theta, x, y, m, snap, g, N, c, stream);
-        return launch_family_t<FAMILY, MODE, GA_F32, KEEP_M, SNAP, false>(theta, x, y, m, snap, g, N, c, stream);
+            return launch_family_t<FAMILY, MODE, GA_F32, KEEP_M, SNAP, true>(theta, x, y, m, snap, g, N, c, resident_bytes, stream);
+        return launch_family_t<FAMILY, MODE, GA_F32, KEEP_M, SNAP, false>(theta, x, y, m, snap, g, N, c, resident_bytes, stream);
     }
     if ((addr & 7u) == 0)
-        return launch_family_t<FAMILY, MODE, GA_BF16, KEEP_M, SNAP, true>(theta, x, y, m, snap, g, N, c, stream);
-    return launch_family_t<FAMILY, MODE, GA_BF16, KEEP_M, SNAP, false>(theta, x, y, m, snap, g, N, c, stream);
+        return launch_family_t<FAMILY, MODE, GA_BF16, KEEP_M, SNAP, true>(theta, x, y, m, snap, g, N, c, resident_bytes, stream);
+    return launch_family_t<FAMILY, MODE, GA_BF16, KEEP_M, SNAP, false>(theta, x, y, m, snap, g, N, c, resident_bytes, stream);
 }
 
 template <int FAMILY>
 hipError_t launch_family(float* theta, float* x, float* y, float* m, float* snap, const void* g, int dt, uint64_t N,
-                         int mode, bool keep_m, bool write_snap, const StepConst& c, hipStream_t stream) {
-#define GA_FAM(MODE, KEEP, SNAP) launch_family_m<FAMILY, MODE, KEEP, SNAP>(theta, x, y, m, snap, g, dt, N, c, stream)
+                         int mode, bool keep_m, bool write_snap, const StepConst& c, uint64_t resident_bytes,
+                         hipStream_t stream) {
+#define GA_FAM(MODE, KEEP, SNAP) \
+    launch_family_m<FAMILY, MODE, KEEP, SNAP>(theta, x, y, m, snap, g, dt, N, c, resident_bytes, stream)
     switch (mode) {
         case GA_MODE_GA: return GA_FAM(GA_MODE_GA, true, true);
         case GA_MODE_GA_HINGE: return GA_FAM(GA_MODE_GA_HINGE, true, true);
@@ -271,13 +273,13 @@ hipError_t launch_apply_dana(const StatePtrs& st, uint64_t N, uint32_t worker, c
                              bool keep_m, bool write_snap, const StepConst& c, hipStream_t stream) {
     return launch_family<GA_FAMILY_DANA>(st.theta, st.v, st.worker_v + (uint64_t)worker * st.stride, st.m,
                                          st.snaps + (uint64_t)worker * st.stride, g, grad_dtype, N, mode, keep_m,
-                                         write_snap, c, stream);
+                                         write_snap, c, st.resident_bytes, stream);
 }
 
 hipError_t launch_apply_adam(const StatePtrs& st, uint64_t N, uint32_t worker, const void* g, int grad_dtype, int mode,
                              bool keep_m, bool write_snap, const StepConst& c, hipStream_t stream) {
     return launch_family<GA_FAMILY_ADAM>(st.theta, st.v, st.v2, st.m, st.snaps + (uint64_t)worker * st.stride, g,
-                                         grad_dtype, N, mode, keep_m, write_snap, c, stream);
+                                         grad_dtype, N, mode, keep_m, write_snap, c, st.resident_bytes, stream);
 }
 
 hipError_t launch_apply(const StatePtrs& st, uint64_t N, uint32_t worker, const void* g, int grad_dtype, int mode,

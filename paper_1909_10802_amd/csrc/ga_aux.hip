@@ -243,7 +243,7 @@ hipError_t launch_diagnostics(const StatePtrs& st, uint64_t N, uint32_t worker, 
     const uint32_t grid = blocks_for(N >> 2, (uint64_t)kBlock * 4, kDiagMaxBlocks);
     hipLaunchKernelGGL(diag_kernel, dim3(grid), dim3(kBlock), 0, stream, st.theta, st.m,
                        st.snaps + (uint64_t)worker * st.stride, N, inv_bc, eta_max, eps,
-                       kResidentBytes / sizeof(f32x4), dev_partials);
+                       st.resident_bytes / sizeof(f32x4), dev_partials);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (dev_report)

@@ -209,8 +209,8 @@ __device__ __forceinline__ float load_g1(const void* __restrict__ g, uint64_t j)
 // without the hint, all other accesses carry it.  Measured with the fused update on 70 M - 250 M parameters: the
 // time falls linearly with the kept bytes up to 256 MiB and is back at the all-streamed time from 288 MiB on (the
 // kept lines then evict each other), so the budget stays clear of that edge.  For the same bytes, keeping more
-// of theta beats keeping the same parameters' theta and v.
-constexpr uint64_t kResidentBytes = (uint64_t)240 << 20;
+// of theta beats keeping the same parameters' theta and v.  The default budget is kResidentBytes (ga_internal.h): a
+// master that shares the GPU with other tenants of that cache is given a smaller one.
 
 // Leading blocks of a launch whose theta / v / m accesses go without the hint (theta >= v >= m).
 struct Residency {
@@ -218,8 +218,8 @@ struct Residency {
 };
 
 // blocks: grid size; block_bytes: bytes of ONE array that a block covers.  theta first, then v, then m.
-inline Residency residency_for(uint64_t blocks, uint64_t block_bytes, bool with_v, bool with_m) {
-    uint64_t budget = kResidentBytes / block_bytes;
+inline Residency residency_for(uint64_t resident_bytes, uint64_t blocks, uint64_t block_bytes, bool with_v, bool with_m) {
+    uint64_t budget = resident_bytes / block_bytes;
     Residency r = {0u, 0u, 0u};
     r.theta = (uint32_t)(blocks < budget ? blocks : budget);
     budget -= r.theta;

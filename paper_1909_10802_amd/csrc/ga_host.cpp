@@ -597,6 +597,7 @@ int ga_create_ex(ga_ctx** out, const ga_config* cfg, void* dev_workspace, size_t
     c->st.worker_v = L.off_worker_v ? reinterpret_cast<float*>(base + L.off_worker_v) : nullptr;
     c->st.v2 = L.off_v2 ? reinterpret_cast<float*>(base + L.off_v2) : nullptr;
     c->st.stride = L.Np;
+    c->st.resident_bytes = ga::kResidentBytes;
     c->dev_table = reinterpret_cast<ga_arrival*>(base + L.off_table);
     c->dev_adam_table = reinterpret_cast<ga::AdamRow*>(base + L.off_adam_table);
     c->dev_grad_table = reinterpret_cast<const void**>(base + L.off_grad_table);
@@ -689,6 +690,15 @@ int ga_set_track_gap(ga_ctx* ctx, int on) {
     ctx->track_gap = (on != 0);
     return GA_OK;
 }
+
+int ga_set_resident_bytes(ga_ctx* ctx, uint64_t bytes) {
+    if (!ctx) return GA_ERR_ARG;
+    if (bytes > ((uint64_t)1 << 40)) return fail(ctx, GA_ERR_ARG, "set_resident_bytes: more than 2^40 bytes");
+    ctx->st.resident_bytes = bytes;
+    return GA_OK;
+}
+
+uint64_t ga_get_resident_bytes(const ga_ctx* ctx) { return ctx ? ctx->st.resident_bytes : 0; }
 
 int ga_set_theta(ga_ctx* ctx, const float* dev_theta0) {
     if (!ctx) return GA_ERR_ARG;

@@ -72,6 +72,10 @@ constexpr uint32_t kTableCap = 8192;       // arrivals per persistent launch
 constexpr uint64_t kDelayLog = (uint64_t)1 << 20;   // delays of this many most recent arrivals are kept on the host
 constexpr uint32_t kDiagMaxBlocks = 2048;  // partials in the workspace
 
+// Bytes of theta, v, m that the update kernels keep in the 256 MiB memory-side cache unless the caller sets another
+// budget (ga_set_resident_bytes); the reasons for the value are at Residency in ga_device.h.
+constexpr uint64_t kResidentBytes = (uint64_t)240 << 20;
+
 // State pointers inside the workspace.  snaps is W rows of `stride` floats.
 struct StatePtrs {
     float* theta;
@@ -81,6 +85,7 @@ struct StatePtrs {
     float* worker_v;  // DANA: W rows of v_i, else null
     float* v2;        // ADAM: second moment, else null
     uint64_t stride;  // floats between consecutive workers' rows (N rounded up to 64)
+    uint64_t resident_bytes;  // budget of the cache-resident leading part of theta, v, m
 };
 
 // Fused update of one arrival.  g: N values of grad_dtype.  In the GA modes m

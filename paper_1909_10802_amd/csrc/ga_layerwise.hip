@@ -263,7 +263,7 @@ hipError_t launch_apply_layerwise(const StatePtrs& st, uint64_t N, uint32_t work
     float* snap = st.snaps + (uint64_t)worker * st.stride;
     const dim3 block(kBlock), grid(lt.n_chunks), lgrid(lt.n_layers);
     // leading parameters whose theta, then v, stay in the memory-side cache
-    const uint64_t budget = kResidentBytes / sizeof(float);
+    const uint64_t budget = st.resident_bytes / sizeof(float);
     const uint64_t keep_theta = N < budget ? N : budget;
     const uint64_t keep_v = N < budget - keep_theta ? N : budget - keep_theta;
     if (!sums_ready)

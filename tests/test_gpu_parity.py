@@ -337,6 +337,28 @@ def test_get_config_returns_what_the_context_runs_with():
     assert (cfg.family, cfg.track_gap, f(cfg.adam_beta1), f(cfg.adam_beta2), f(cfg.adam_eps)) == (ga.GA_FAMILY_ADAM, 1, f(0.8), f(0.95), f(1e-5))
 
 
+@pytest.mark.parametrize("mode", [ga.GA_MODE_GA, ga.GA_MODE_ASGD], ids=["ga", "asgd"])
+def test_resident_budget_changes_no_result(mode):
+    # the budget only moves the block thresholds between the four hint paths of the fused update (and of the
+    # Gap statistics): every split of a 1 M parameter vector gives the oracle's bits
+    N, W, T, seed = 1_000_003, 3, 9, 44
+    bufs = ga_inputs.gradient_buffers(2, N, seed, 0.3)
+    dbufs = [dev(b) for b in bufs]
+    sched = ga.ga_simulate_schedule(W, T, seed=seed)
+    O = oracle.Master(N, W, mode, oracle.Hyper(), track_gap=True)
+    O.run_buffers(sched, bufs)
+    ref = O.gap_statistics(1)
+    for budget in (0, 1 << 20, 5 << 20, 9 << 20, 11 << 20, 240 << 20):    # theta is 4 MB: none | part of theta | ... | all
+        M = ga.Master(N, W, mode=mode, track_gap=True)
+        ga.ga_set_resident_bytes(M.ctx, budget)
+        assert ga.ga_get_resident_bytes(M.ctx) == budget
+        M.run_schedule(sched, ga.buffer_source(dbufs))
+        compare_masters(M, O, "budget %d" % budget)
+        d = M.diagnostics(1)
+        assert d["mean_graw"] == pytest.approx(ref["mean_graw"], rel=1e-6) and round(d["frac_gt1"] * N) == ref["n_gt1"]
+        M.close()
+
+
 def test_theta0_and_setters():
     N, W = 3001, 3
     th0 = ga_inputs.optimum(N, 1)
