@@ -61,13 +61,16 @@ def _cases(n, seed):
         source = str(r.choice(["persistent", "per_arrival", "f32", "bf16"]))
         nesterov = bool(family == 0 and r.integers(0, 3) == 0)
         dist = int(r.integers(0, 3))
-        out.append((c, N, W, T, family, mode, source, nesterov, dist))
+        # cache-resident budget: the default, none, or a cut somewhere inside theta, v, m (so that one launch takes
+        # several of the hint paths of the fused update)
+        budget = int(r.choice([240 << 20, 0, int(r.integers(0, 12 * N + 1))]))
+        out.append((c, N, W, T, family, mode, source, nesterov, dist, budget))
     return out
 
 
-@pytest.mark.parametrize("case", _cases(48, 20260), ids=lambda c: "c%d-N%d-W%d-T%d-f%d-m%d-%s%s-d%d" % (c[:7] + ("-nag" if c[7] else "", c[8])))
+@pytest.mark.parametrize("case", _cases(64, 20260), ids=lambda c: "c%d-N%d-W%d-T%d-f%d-m%d-%s%s-d%d-b%d" % (c[:7] + ("-nag" if c[7] else "", c[8], c[9])))
 def test_random_sweep(case):
-    c, N, W, T, family, mode, source, nesterov, dist = case
+    c, N, W, T, family, mode, source, nesterov, dist, budget = case
     seed = 1000 + c
     eta = 0.01 if family == ga.GA_FAMILY_ADAM else 0.1
     sched = ga.ga_simulate_schedule(W, T, dist, 0.7, seed)
@@ -78,6 +81,7 @@ def test_random_sweep(case):
         O = oracle.Master(N, W, mode, oracle.Hyper(eta, 0.9), track_gap=track, nesterov=nesterov)
     else:
         M, O = make_pair(family, N, W, mode, eta, track=track)
+    ga.ga_set_resident_bytes(M.ctx, budget)
     if source in ("persistent", "per_arrival"):
         a, ts = ga_inputs.curvatures(N, seed), ga_inputs.optimum(N, seed)
         scratch = torch.empty(N, dtype=torch.float32, device=DEV)

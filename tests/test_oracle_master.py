@@ -412,7 +412,7 @@ def gap_aware_in_numpy(sched, W, a, ts, eta, gamma, beta, eps, raw_input):
 
 
 def test_reading_of_the_input_of_alg14_is_recorded():
-    # Alg. 14 prints v <- gamma v + g with the raw gradient; Alg. 4's v holds g / G.  This build keeps one v (the
+    # Alg. 14 prints v <- gamma v + g with the raw gradient; Alg. 4's v holds g / G.  This library keeps one v (the
     # update vector) and feeds Alg. 14 with it.  The paper does not fix that choice, so nothing pins it: this test
     # records what it changes.  (1) With one worker there is no Gap, G = 1, and both forms are the same numbers.
     # (2) With eight workers the reading gives a smaller C (its input is the penalised vector), hence larger
