@@ -112,27 +112,27 @@ __device__ __forceinline__ DiagPartial block_reduce(double sum, unsigned long lo
     return r;
 }
 
-// One thread's groups i = i0, i0+1, ... (< i1) of its grid-stride sequence q = q_first + i * stride, four in
-// flight; the accumulation keeps the order of i.  NT_TH: theta is read with the non-temporal hint.
+// One block's groups [q0, q1): thread t takes q0 + t, q0 + t + kBlock, ..., two in flight, accumulated in that order.
+// NT_TH: theta is read with the non-temporal hint.
 template <bool NT_TH>
 __device__ __forceinline__ void diag_span(DiagAcc& acc, const float* __restrict__ theta, const float* __restrict__ m,
-                                          const float* __restrict__ snap, uint64_t q_first, uint64_t stride,
-                                          uint64_t i0, uint64_t i1, float inv_bc, float eta_max, float eps) {
-    constexpr int U = 4;
-    for (uint64_t i = i0; i < i1; i += U) {
+                                          const float* __restrict__ snap, uint64_t q0, uint64_t q1, float inv_bc,
+                                          float eta_max, float eps) {
+    constexpr int U = 2;
+    for (uint64_t q = q0 + threadIdx.x; q < q1; q += (uint64_t)U * kBlock) {
         f32x4 th[U], s[U], mm[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            if (i + u < i1) {
-                const uint64_t q = q_first + (i + u) * stride;
-                th[u] = load4<NT_TH>(theta, q);
-                s[u] = load4<true>(snap, q);
-                mm[u] = load4<true>(m, q);
+            const uint64_t qu = q + (uint64_t)u * kBlock;
+            if (qu < q1) {
+                th[u] = load4<NT_TH>(theta, qu);
+                s[u] = load4<true>(snap, qu);
+                mm[u] = load4<true>(m, qu);
             }
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            if (i + u < i1) {
+            if (q + (uint64_t)u * kBlock < q1) {
                 diag_one(acc, th[u].x, s[u].x, mm[u].x, inv_bc, eta_max, eps);
                 diag_one(acc, th[u].y, s[u].y, mm[u].y, inv_bc, eta_max, eps);
                 diag_one(acc, th[u].z, s[u].z, mm[u].z, inv_bc, eta_max, eps);
@@ -142,21 +142,20 @@ __device__ __forceinline__ void diag_span(DiagAcc& acc, const float* __restrict_
     }
 }
 
-// keep_q: groups [0, keep_q) of theta are read without the hint (the part the update kernels keep in the
-// memory-side cache); reading the rest of theta without it would push that part out.
+// Block b reads the contiguous groups [b * per_block, (b + 1) * per_block) of the three arrays (a grid-stride walk
+// over the same data is a quarter slower at 10^8 parameters).  keep_q: a block whose groups all lie below keep_q
+// reads theta without the hint (the part the update kernels keep in the memory-side cache); reading the rest of
+// theta without it would push that part out.
 __global__ __launch_bounds__(kBlock) void diag_kernel(const float* __restrict__ theta, const float* __restrict__ m,
                                                       const float* __restrict__ snap, uint64_t N, float inv_bc,
-                                                      float eta_max, float eps, uint64_t keep_q,
+                                                      float eta_max, float eps, uint64_t per_block, uint64_t keep_q,
                                                       DiagPartial* __restrict__ partials) {
     const uint64_t n4 = N >> 2;
     DiagAcc acc = {0.0, 0u, 0u, 0u};
-    const uint64_t stride = (uint64_t)gridDim.x * kBlock;
-    const uint64_t q_first = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
-    const uint64_t n_all = q_first < n4 ? (n4 - q_first + stride - 1) / stride : 0;        // this thread's groups
-    const uint64_t lim = keep_q < n4 ? keep_q : n4;
-    const uint64_t n_kept = q_first < lim ? (lim - q_first + stride - 1) / stride : 0;     // those below keep_q
-    GA_HINT_PATH("theta kept", diag_span<false>(acc, theta, m, snap, q_first, stride, 0, n_kept, inv_bc, eta_max, eps));
-    GA_HINT_PATH("all streamed", diag_span<true>(acc, theta, m, snap, q_first, stride, n_kept, n_all, inv_bc, eta_max, eps));
+    const uint64_t q0 = (uint64_t)blockIdx.x * per_block;
+    const uint64_t q1 = q0 + per_block < n4 ? q0 + per_block : n4;
+    if (q1 <= keep_q) GA_HINT_PATH("theta kept", diag_span<false>(acc, theta, m, snap, q0, q1, inv_bc, eta_max, eps));
+    else GA_HINT_PATH("all streamed", diag_span<true>(acc, theta, m, snap, q0, q1, inv_bc, eta_max, eps));
     if (blockIdx.x == 0 && threadIdx.x < (N & 3)) {
         const uint64_t j = 4 * n4 + threadIdx.x;
         diag_one(acc, theta[j], snap[j], m[j], inv_bc, eta_max, eps);
@@ -165,15 +164,40 @@ __global__ __launch_bounds__(kBlock) void diag_kernel(const float* __restrict__ 
     if (threadIdx.x == 0) partials[blockIdx.x] = r;
 }
 
+// Launch shape of diag_kernel: at most kDiagMaxBlocks blocks (all resident at once on 256 compute units), each with a
+// whole number of block-wide steps.
+struct DiagShape {
+    uint32_t grid;
+    uint64_t per_block;
+};
+inline DiagShape diag_shape(uint64_t N) {
+    const uint64_t n4 = N >> 2;
+    DiagShape d;
+    d.grid = blocks_for(n4, (uint64_t)kBlock * 4, kDiagMaxBlocks);
+    d.per_block = ((n4 + d.grid - 1) / d.grid + kBlock - 1) / kBlock * kBlock;
+    if (d.per_block == 0) d.per_block = kBlock;
+    return d;
+}
+
 // All partials added by one block in a fixed order; every thread returns the total.
 __device__ __forceinline__ DiagPartial add_partials(const DiagPartial* __restrict__ partials, uint32_t n_partials) {
     double sum = 0.0;
     unsigned long long gt1 = 0, gt0 = 0, bad = 0;
-    for (uint32_t i = threadIdx.x; i < n_partials; i += kBlock) {
-        sum += partials[i].sum_graw;
-        gt1 += partials[i].n_gt1;
-        gt0 += partials[i].n_gt0;
-        bad += partials[i].n_bad;
+    constexpr uint32_t U = 4;   // loads in flight per thread
+    for (uint32_t i = threadIdx.x; i < n_partials; i += U * kBlock) {
+        DiagPartial p[U];
+#pragma unroll
+        for (uint32_t u = 0; u < U; ++u)
+            if (i + u * kBlock < n_partials) p[u] = partials[i + u * kBlock];
+#pragma unroll
+        for (uint32_t u = 0; u < U; ++u) {
+            if (i + u * kBlock < n_partials) {
+                sum += p[u].sum_graw;
+                gt1 += p[u].n_gt1;
+                gt0 += p[u].n_gt0;
+                bad += p[u].n_bad;
+            }
+        }
     }
     return block_reduce(sum, gt1, gt0, bad);
 }
@@ -240,9 +264,10 @@ hipError_t launch_quadratic_gradient(const StatePtrs& st, uint64_t N, uint32_t w
 
 hipError_t launch_diagnostics(const StatePtrs& st, uint64_t N, uint32_t worker, float inv_bc, float eta_max,
                               float eps, DiagPartial* dev_partials, ga_diag* dev_report, hipStream_t stream) {
-    const uint32_t grid = blocks_for(N >> 2, (uint64_t)kBlock * 4, kDiagMaxBlocks);
+    const DiagShape shape = diag_shape(N);
+    const uint32_t grid = shape.grid;
     hipLaunchKernelGGL(diag_kernel, dim3(grid), dim3(kBlock), 0, stream, st.theta, st.m,
-                       st.snaps + (uint64_t)worker * st.stride, N, inv_bc, eta_max, eps,
+                       st.snaps + (uint64_t)worker * st.stride, N, inv_bc, eta_max, eps, shape.per_block,
                        st.resident_bytes / sizeof(f32x4), dev_partials);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -277,9 +302,10 @@ hipError_t launch_diagnostics_static(const float* theta, const float* snap, cons
     hipError_t e = static_scratch_address(&partials);
     if (e != hipSuccess) return e;
     // every partial that the report kernel reads is written by this launch first: nothing has to start at zero
-    const uint32_t grid = blocks_for(N >> 2, (uint64_t)kBlock * 4, kDiagMaxBlocks);
+    const DiagShape shape = diag_shape(N);
+    const uint32_t grid = shape.grid;
     hipLaunchKernelGGL(diag_kernel, dim3(grid), dim3(kBlock), 0, stream, theta, m, snap, N, inv_bc, eta_max, eps,
-                       kResidentBytes / sizeof(f32x4), partials);
+                       shape.per_block, kResidentBytes / sizeof(f32x4), partials);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(diag_report_kernel, dim3(1), dim3(kBlock), 0, stream, partials, grid, N, dev_report);

@@ -59,3 +59,13 @@ def test_layerwise_hint_paths_survive_the_compiler(tmp_path):
     hinted_loads, plain_loads, hinted_stores, plain_stores = counts(text)
     assert (hinted_loads, plain_loads) == ((5 + 4 + 3) * 2, (0 + 1 + 2) * 2)
     assert hinted_stores == (4 + 3 + 2) * 2 and plain_stores == (0 + 1 + 2) * 2 + 1     # + the chunk's partial sums
+
+
+@pytest.mark.skipif(not os.path.exists(HIPCC), reason="needs hipcc")
+def test_gap_statistics_hint_paths_survive_the_compiler(tmp_path):
+    asm = assembly("ga_aux.hip", tmp_path)
+    # diag_kernel: two groups in flight per thread; loads theta, snapshot, m.  Paths: theta kept | all streamed.
+    text = kernel_text(asm, "11diag_kernel")
+    for name in ("theta kept", "all streamed"):
+        assert "; %s begin" % name in text and "; %s end" % name in text
+    assert counts(text) == ((2 + 3) * 2, (1 + 0) * 2, 0, 2)      # stores: the block's 32-byte partial
