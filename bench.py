@@ -404,13 +404,36 @@ def ceiling(args, torch, ga):
         streams["%dr%dw" % (r, w)] = 4.0 * (r + w) * n / s / 1e9
     del bufs
     torch.cuda.empty_cache()
+    # Data held in the memory-side cache: two arrays of the cfg3 size (204 MB together) accessed without the hint,
+    # alone and inside the fused update's mix: theta, v, m, snapshot updated in place, the gradient read, with the
+    # snapshot and the gradient taken from a pool in turn as the arrivals of different workers do.
+    nr = 25_557_032
+    fixed = [torch.full((nr,), 0.5 + i, dtype=torch.float32, device=dev) for i in range(3)]        # theta, v, m
+    pool = [torch.full((nr,), 3.5 + i, dtype=torch.float32, device=dev) for i in range(16)]        # snapshots, gradients
+    turn = [0]
+
+    def mix(n_resident):
+        i = turn[0] = (turn[0] + 2) % len(pool)
+        arrays = fixed + [pool[i], pool[i + 1]]
+        ga.ga_probe_streams(arrays, arrays[:4], nr, n_resident=n_resident)
+
+    resident = {}
+    for name, r, w in (("2r0w", 2, 0), ("2r2w_in_place", 2, 2)):
+        s = timed(lambda: ga.ga_probe_streams(fixed[:r], fixed[:w], nr, n_resident=2), 40)
+        resident[name] = 4.0 * (r + w) * nr / s / 1e9
+    resident["5r4w_in_place"] = 4.0 * 9 * nr / timed(lambda: mix(2), 48) / 1e9
+    resident["5r4w_in_place_all_streamed"] = 4.0 * 9 * nr / timed(lambda: mix(0), 48) / 1e9
+    del fixed, pool
+    torch.cuda.empty_cache()
     out = torch.zeros(1, dtype=torch.int32, device=dev)
     blocks, iters = 8 * torch.cuda.get_device_properties(0).multi_processor_count, 4096
     valu = {}
     for op in ga.PROBE_OPS:
         s = timed(lambda: ga.ga_probe_valu(op, blocks, iters, out), 5)
         valu[op] = blocks * 256.0 * iters * 8 / s / 1e12
-    return {"n_floats_per_array": n, "stream_GBs": streams, "valu_T_lane_ops_per_s": valu,
+    return {"n_floats_per_array": n, "stream_GBs": streams,
+            "resident_stream_GBs": dict(resident, n_floats_per_array=nr, note="the first two arrays are accessed without the non-temporal hint"),
+            "valu_T_lane_ops_per_s": valu,
             "valu_probe": "%d blocks of 256 threads x %d iterations x 8 independent instructions" % (blocks, iters),
             "hbm_peak_GBs": HBM_PEAK_GBS, "alu_peak_T_lane_ops_per_s": ALU_PEAK_TLOPS}
 

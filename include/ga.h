@@ -511,11 +511,16 @@ int ga_box_muller_raw(const uint32_t* dev_xa, const uint32_t* dev_xb, uint64_t n
  *   4).  n_read in {0, 1, 2, 4, 5}, n_write in {0, 1, 2, 4}, not both 0.
  *   Sec. 4.3 makes the update elementwise, which is why a stream count is all
  *   that characterises its memory side: the GA update is 5 reads + 4 writes.
+ * ga_probe_streams_ex: the same with the first n_resident (0, 1 or 2) input
+ *   arrays and the first n_resident output arrays accessed without the hint,
+ *   as the update accesses the part of theta and v that it keeps in the
+ *   memory-side cache.  An output may be the input of the same index (an
+ *   update in place); other overlaps between arrays give undefined values.
  * ga_probe_valu: blocks x 256 threads, each issuing iterations x 8 independent
  *   vector instructions of kind `op` (ga_probe_op); dev_out: 4 bytes, written
  *   only formally.  8 x 256 blocks give 8 wavefronts per SIMD on 256 CUs.
- * Errors: GA_ERR_ARG (counts outside the lists, null or misaligned pointers,
- * unknown op), GA_ERR_HIP. */
+ * Errors: GA_ERR_ARG (counts outside the lists, n_resident above 2, null or
+ * misaligned pointers, unknown op), GA_ERR_HIP. */
 enum ga_probe_op {
     GA_PROBE_FMA = 0,        /* v_fma_f32 */
     GA_PROBE_XOR = 1,        /* v_xor_b32 */
@@ -529,6 +534,8 @@ enum ga_probe_op {
 };
 int ga_probe_streams(uint32_t n_read, uint32_t n_write, uint64_t n, const float* const* host_dev_read,
                      float* const* host_dev_write, void* hip_stream);
+int ga_probe_streams_ex(uint32_t n_read, uint32_t n_write, uint32_t n_resident, uint64_t n,
+                        const float* const* host_dev_read, float* const* host_dev_write, void* hip_stream);
 int ga_probe_valu(int op, uint32_t blocks, uint32_t iterations, uint32_t* dev_out, void* hip_stream);
 
 /* Message of the last error on this context ("" if none).  ctx may be null:

@@ -24,6 +24,20 @@ def test_stream_probe_reads_and_writes_the_named_arrays(n_read, n_write):
         assert bool((r == float(i + 1)).all())
 
 
+@pytest.mark.parametrize("n_resident", [0, 1, 2])
+def test_stream_probe_in_place_with_a_resident_prefix(n_resident):
+    # outputs that are the inputs of the same index (the fused update's pattern); the hint changes no value
+    n = 4 * 70_001
+    guard = 64
+    arrays = [torch.full((n + guard,), float(i + 1), device="cuda:0") for i in range(5)]
+    ga.ga_probe_streams(arrays, arrays[:4], n, n_resident=n_resident)
+    torch.cuda.synchronize()
+    for i, a in enumerate(arrays):
+        h = a.cpu().numpy()
+        want = 15.0 + i if i < 4 else 5.0
+        assert np.all(h[:n] == want) and np.all(h[n:] == float(i + 1))
+
+
 def test_probe_argument_errors():
     x = torch.zeros(64, device="cuda:0")
     out = torch.zeros(1, dtype=torch.int32, device="cuda:0")
@@ -33,6 +47,8 @@ def test_probe_argument_errors():
         ga.ga_probe_streams([], [], 64)
     with pytest.raises(ga.GaError):
         ga.ga_probe_streams([x], [x], 62)                        # not a multiple of four
+    with pytest.raises(ga.GaError):
+        ga.ga_probe_streams([x], [x], 64, n_resident=3)          # at most two arrays without the hint
     with pytest.raises(ga.GaError):
         ga.ga_probe_valu(99, 8, 8, out)
     for op in ga.PROBE_OPS:
