@@ -125,3 +125,21 @@ def device_gradient_buffers(n_bufs, N, seed, std=1e-2, dtype="f32", device="cuda
         x = torch.randn(N, dtype=torch.float32, device=device, generator=g).mul_(std)
         out.append(x.to(torch.bfloat16) if dtype == "bf16" else x)
     return out
+
+
+def device_gap_state(N, seed, device="cuda:0"):
+    """(theta, snapshot, m) as device tensors for a full-size check of the Gap statistics: snapshot = theta plus a small
+    normal offset, every fifth parameter unmoved (Gap exactly zero), m uniform in [0, 1e-4), and a few planted
+    non-finite and extreme entries at fixed places."""
+    import torch
+    g = device_generator(seed, 6, device)
+    theta = torch.randn(N, dtype=torch.float32, device=device, generator=g)
+    snap = torch.randn(N, dtype=torch.float32, device=device, generator=g).mul_(0.002).add_(theta)
+    snap[::5] = theta[::5]
+    m = torch.rand(N, dtype=torch.float32, device=device, generator=g).mul_(1e-4)
+    m[12345] = float("nan")
+    snap[N - 2] = float("inf")
+    m[7] = float("inf")              # C infinite: Gap 0, finite
+    m[N // 2] = 0.0                  # C at its floor eta_max * eps: a huge Gap
+    theta[N // 3] = float("nan")
+    return theta, snap, m

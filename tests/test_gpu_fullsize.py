@@ -217,3 +217,31 @@ def test_cfg5_capacity_sampled():
     if free < need:
         pytest.skip("needs %.0f GB of free HBM" % (need / 1e9))
     run_buffer_workload("cfg5", [ga.GA_MODE_GA], n_random=20000)
+
+
+def test_gap_statistics_of_the_whole_vector_against_the_oracle():
+    # K3 in the launch shape of the large workloads (2048 blocks, each with many steps over its run of the arrays; the
+    # leading 240 MiB of theta read without the hint, the rest with it), on all N = 151,000,003 parameters: the
+    # counts are exact, the mean agrees to 1e-6 (double accumulation on both sides, different order)
+    N, k = 151_000_003, 40
+    theta, snap, m = ga_inputs.device_gap_state(N, 2027, DEV)
+    out = torch.zeros(ga.DIAG_BYTES, dtype=torch.uint8, device=DEV)
+    hy = oracle.Hyper(0.1, 0.9)
+    ga.ga_gap_statistics_static(theta, snap, m, N, k, hy.beta, hy.eta_max, hy.eps, out)
+    got = ga.diag_from_device(out)
+    ref = oracle.gap_statistics(host(theta), host(m), host(snap), k, hy)
+    assert got["n_nonfinite"] == ref["n_nonfinite"] == 3
+    assert round(got["frac_gt1"] * N) == ref["n_gt1"] and ref["n_gt1"] > N // 10
+    assert round(got["frac_gt0"] * N) == ref["n_gt0"] and N // 2 < ref["n_gt0"] < N - N // 5 + 10
+    assert abs(got["mean_graw"] - ref["mean_graw"]) <= 1e-6 * abs(ref["mean_graw"])
+    # the same arrays as the state of a master (the partials in its workspace, theta kept by its budget)
+    del out
+    M = ga.Master(N, 1, mode=ga.GA_MODE_GA)
+    ga.ga_put_theta(M.ctx, theta)
+    ga.ga_put_m(M.ctx, m)
+    ga.ga_put_snapshot(M.ctx, 0, snap)
+    ga.ga_set_bookkeeping(M.ctx, k, np.array([k], np.uint64))
+    d = M.diagnostics(0)
+    assert d == got
+    del M
+    free_gpu()
