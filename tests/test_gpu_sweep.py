@@ -68,7 +68,7 @@ def _cases(n, seed):
     return out
 
 
-@pytest.mark.parametrize("case", _cases(64, 20260), ids=lambda c: "c%d-N%d-W%d-T%d-f%d-m%d-%s%s-d%d-b%d" % (c[:7] + ("-nag" if c[7] else "", c[8], c[9])))
+@pytest.mark.parametrize("case", _cases(192, 20260), ids=lambda c: "c%d-N%d-W%d-T%d-f%d-m%d-%s%s-d%d-b%d" % (c[:7] + ("-nag" if c[7] else "", c[8], c[9])))
 def test_random_sweep(case):
     c, N, W, T, family, mode, source, nesterov, dist, budget = case
     seed = 1000 + c
