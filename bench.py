@@ -37,8 +37,8 @@ VALU_PER_UPDATE = {"ga": 106.7, "ga_hinge": 106.7}
 # scaled by a copy of known size; profiles/apply_kernel_cfg3.md).  The counters sit in front of the memory-side
 # cache, so hits in that cache are included.  Valid for the kernel source with this hash only.
 TRAFFIC = {
-    ("cfg3", "ga", 25_557_032): {"bytes": 920116824, "read": 511203027, "written": 408913797, "kernels_sha256": "fb495730c41527a8"},
-    ("cfg3", "ga", 151_000_000): {"bytes": 5435407926, "read": 3019394163, "written": 2416013763, "kernels_sha256": "fb495730c41527a8"},
+    ("cfg3", "ga", 25_557_032): {"bytes": 920117578, "read": 511202990, "written": 408914588, "kernels_sha256": "86cd429118cd73c8"},
+    ("cfg3", "ga", 151_000_000): {"bytes": 5435407485, "read": 3019393781, "written": 2416013704, "kernels_sha256": "86cd429118cd73c8"},
 }
 BYTES_PER_UPDATE = {           # algorithmic bytes per parameter per arrival, fused update
     ("ga", "f32"): 36, ("ga", "bf16"): 34, ("ga_hinge", "f32"): 36, ("ga_hinge", "bf16"): 34,

@@ -231,12 +231,14 @@ inline Residency residency_for(uint64_t resident_bytes, uint64_t blocks, uint64_
 
 // Two block-uniform paths that differ only in cache hints are one path to the optimiser, which merges them and
 // drops the hints.  An empty asm statement at both ends of each path keeps them apart.
+#ifndef GA_HINT_PATH   // a build of these sources for another target (the CPU build of the tests) brings its own
 #define GA_HINT_PATH(name, ...)                          \
     do {                                                 \
         asm volatile("; " name " begin" ::: "memory");   \
         __VA_ARGS__;                                     \
         asm volatile("; " name " end" ::: "memory");     \
     } while (0)
+#endif
 
 inline uint32_t blocks_for(uint64_t items, uint64_t per_block, uint32_t cap) {
     const uint64_t b = (items + per_block - 1) / per_block;

@@ -1,4 +1,4 @@
-// Test scaffolding (CPU only): drives the host side of libga (ga_host.cpp linked against fake_device.cpp) through
+// Test scaffolding (CPU only): drives the host side of libga (ga_host.cpp linked against fake_runtime.cpp and fake_launchers.cpp) through
 // one scenario and writes what the host decided -- the schedule, k, iter[], the delay log and one record per
 // arrival as handed to the launchers -- to a binary file that tests/test_host_sim.py compares with the oracle.
 //

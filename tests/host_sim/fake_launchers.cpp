@@ -1,8 +1,8 @@
-// Test scaffolding (CPU only): stand-ins for the HIP runtime calls and for the kernel launchers that ga_host.cpp uses,
-// so that the host side of the library -- argument checks, the bookkeeping of Alg. 3 / Alg. 5 (k, iter[], tau), the
-// per-arrival scalars, the chunking of a schedule into arrival tables, the delay log, checkpoints -- runs on a CPU
-// under AddressSanitizer and UndefinedBehaviorSanitizer.  "Device" memory is host memory; copies are memcpy; a launch
-// does no arithmetic and only records the scalars it was given (one line per arrival) in g_rows.
+// Test scaffolding (CPU only): stand-ins for the kernel launchers that ga_host.cpp uses (the HIP runtime's are in
+// fake_runtime.cpp), so that the host side of the library -- argument checks, the bookkeeping of Alg. 3 / Alg. 5
+// (k, iter[], tau), the per-arrival scalars, the chunking of a schedule into arrival tables, the delay log,
+// checkpoints -- runs on a CPU under AddressSanitizer and UndefinedBehaviorSanitizer.  A launch does no arithmetic
+// and only records the scalars it was given (one line per arrival) in g_rows.
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
@@ -17,33 +17,6 @@ struct LoggedArrival {
 };
 std::vector<LoggedArrival> g_rows;
 uint64_t g_first_k_of_last_table = 0;
-
-extern "C" {
-hipError_t hipMemcpyAsync(void* dst, const void* src, size_t bytes, hipMemcpyKind, hipStream_t) {
-    std::memmove(dst, src, bytes);
-    return hipSuccess;
-}
-hipError_t hipHostMalloc(void** p, size_t bytes, unsigned int) {
-    *p = std::malloc(bytes);
-    return *p ? hipSuccess : hipErrorOutOfMemory;
-}
-hipError_t hipHostFree(void* p) {
-    std::free(p);
-    return hipSuccess;
-}
-hipError_t hipStreamSynchronize(hipStream_t) { return hipSuccess; }
-hipError_t hipEventCreateWithFlags(hipEvent_t* e, unsigned) {
-    *e = reinterpret_cast<hipEvent_t>(std::malloc(1));
-    return hipSuccess;
-}
-hipError_t hipEventDestroy(hipEvent_t e) {
-    std::free(e);
-    return hipSuccess;
-}
-hipError_t hipEventRecord(hipEvent_t, hipStream_t) { return hipSuccess; }
-hipError_t hipEventSynchronize(hipEvent_t) { return hipSuccess; }
-const char* hipGetErrorString(hipError_t) { return "fake device"; }
-}
 
 namespace ga {
 

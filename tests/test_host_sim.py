@@ -30,7 +30,8 @@ def driver(tmp_path_factory):
     subprocess.check_call(["g++", "-std=c++17", "-D__HIP_PLATFORM_AMD__", "-I" + HIP_INCLUDE,
                            "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,
                            "-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-g", "-O1", "-Wall", "-Wextra",
-                           os.path.join(CSRC, "ga_host.cpp"), os.path.join(SIM, "fake_device.cpp"),
+                           os.path.join(CSRC, "ga_host.cpp"), os.path.join(SIM, "fake_runtime.cpp"),
+                           os.path.join(SIM, "fake_launchers.cpp"),
                            os.path.join(SIM, "driver.cpp"), "-o", exe])
     return exe
 
