@@ -37,8 +37,8 @@ VALU_PER_UPDATE = {"ga": 106.7, "ga_hinge": 106.7}
 # scaled by a copy of known size; profiles/apply_kernel_cfg3.md).  The counters sit in front of the memory-side
 # cache, so hits in that cache are included.  Valid for the kernel source with this hash only.
 TRAFFIC = {
-    ("cfg3", "ga", 25_557_032): {"bytes": 920117578, "read": 511202990, "written": 408914588, "kernels_sha256": "86cd429118cd73c8"},
-    ("cfg3", "ga", 151_000_000): {"bytes": 5435407485, "read": 3019393781, "written": 2416013704, "kernels_sha256": "86cd429118cd73c8"},
+    ("cfg3", "ga", 25_557_032): {"bytes": 920037094, "read": 511124165, "written": 408912929, "kernels_sha256": "7e6d1c376216fc85"},
+    ("cfg3", "ga", 151_000_000): {"bytes": 5435410664, "read": 3019391399, "written": 2416019266, "kernels_sha256": "7e6d1c376216fc85"},
 }
 BYTES_PER_UPDATE = {           # algorithmic bytes per parameter per arrival, fused update
     ("ga", "f32"): 36, ("ga", "bf16"): 34, ("ga_hinge", "f32"): 36, ("ga_hinge", "bf16"): 34,
@@ -132,10 +132,11 @@ def cpu_baseline(cfg, mode, n_slice, n_steps):
 
 
 def kernels_hash():
-    """Hash of the sources of the fused-update kernel (its own file and the shared device header)."""
+    """Hash of the sources of the fused-update kernel (its own file, the shared device header and the header with the
+    layout of the state arrays)."""
     import hashlib
     h = hashlib.sha256()
-    for name in ("ga_device.h", "ga_apply.hip"):
+    for name in ("ga_device.h", "ga_apply.hip", "ga_internal.h"):
         h.update(open(os.path.join(ROOT, "paper_1909_10802_amd", "csrc", name), "rb").read())
     return h.hexdigest()[:16]
 

@@ -24,28 +24,30 @@ __device__ __forceinline__ void apply_tile(float* __restrict__ theta, float* __r
                                            float* __restrict__ snap, const void* __restrict__ g, uint64_t n4,
                                            uint64_t base, const StepConst& c) {
     constexpr bool GAP = is_gap(MODE);
+    static_assert((kStateTile / 4) % (kBlock * U) == 0, "a block's groups lie in one tile of the state arrays");
+    const uint64_t base_s = state_index<4>(base);   // the same groups in theta, v, m (tiled; ga_internal.h)
     f32x4 th[U], vv[U], mm[U], ss[U], gg[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        const uint64_t q = base + (uint64_t)u * kBlock;
+        const uint64_t q = base + (uint64_t)u * kBlock, qs = base_s + (uint64_t)u * kBlock;
         mm[u] = f32x4{0.f, 0.f, 0.f, 0.f};
         ss[u] = f32x4{0.f, 0.f, 0.f, 0.f};
         if (q < n4) {
-            th[u] = load4<NT_TH>(theta, q);
-            vv[u] = load4<NT_V>(v, q);
-            if constexpr (KEEP_M) mm[u] = load4<NT_M>(m, q);
+            th[u] = load4<NT_TH>(theta, qs);
+            vv[u] = load4<NT_V>(v, qs);
+            if constexpr (KEEP_M) mm[u] = load4<NT_M>(m, qs);
             if constexpr (GAP) ss[u] = load4<true>(snap, q);
             gg[u] = load_g4<DT, ALIGNED>(g, q);
         }
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        const uint64_t q = base + (uint64_t)u * kBlock;
+        const uint64_t q = base + (uint64_t)u * kBlock, qs = base_s + (uint64_t)u * kBlock;
         if (q < n4) {
             update4<MODE, KEEP_M>(th[u], vv[u], mm[u], ss[u], gg[u], c);
-            store4<NT_TH>(theta, q, th[u]);
-            store4<NT_V>(v, q, vv[u]);
-            if constexpr (KEEP_M) store4<NT_M>(m, q, mm[u]);
+            store4<NT_TH>(theta, qs, th[u]);
+            store4<NT_V>(v, qs, vv[u]);
+            if constexpr (KEEP_M) store4<NT_M>(m, qs, mm[u]);
             if constexpr (SNAP) store4<true>(snap, q, th[u]);
         }
     }
@@ -70,14 +72,14 @@ __global__ __launch_bounds__(kBlock) void apply_kernel(float* __restrict__ theta
 
     // ragged tail: the last N % 4 parameters, one per thread of block 0
     if (b == 0 && threadIdx.x < (N & 3)) {
-        const uint64_t j = 4 * n4 + threadIdx.x;
-        float t1 = theta[j], v1 = v[j], m1 = 0.0f, s1 = 0.0f;
-        if constexpr (KEEP_M) m1 = m[j];
+        const uint64_t j = 4 * n4 + threadIdx.x, js = state_index<1>(j);
+        float t1 = theta[js], v1 = v[js], m1 = 0.0f, s1 = 0.0f;
+        if constexpr (KEEP_M) m1 = m[js];
         if constexpr (GAP) s1 = snap[j];
         update_one<MODE, KEEP_M>(t1, v1, m1, s1, load_g1<DT>(g, j), c);
-        theta[j] = t1;
-        v[j] = v1;
-        if constexpr (KEEP_M) m[j] = m1;
+        theta[js] = t1;
+        v[js] = v1;
+        if constexpr (KEEP_M) m[js] = m1;
         if constexpr (SNAP) snap[j] = t1;
     }
 }
@@ -94,24 +96,26 @@ __device__ __forceinline__ void family_tile(float* __restrict__ theta, float* __
                                             const void* __restrict__ g, uint64_t n4, uint64_t base,
                                             const StepConst& c) {
     constexpr bool GAP = is_gap(MODE);
+    static_assert((kStateTile / 4) % (kBlock * U) == 0, "a block's groups lie in one tile of the state arrays");
+    const uint64_t base_s = state_index<4>(base);   // the same groups in theta, x, m (tiled); y and the snapshot are rows
     f32x4 th[U], xx[U], yy[U], mm[U], ss[U], gg[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        const uint64_t q = base + (uint64_t)u * kBlock;
+        const uint64_t q = base + (uint64_t)u * kBlock, qs = base_s + (uint64_t)u * kBlock;
         mm[u] = f32x4{0.f, 0.f, 0.f, 0.f};
         ss[u] = f32x4{0.f, 0.f, 0.f, 0.f};
         if (q < n4) {
-            th[u] = load4<NT_TH>(theta, q);
-            xx[u] = load4<NT_X>(x, q);
+            th[u] = load4<NT_TH>(theta, qs);
+            xx[u] = load4<NT_X>(x, qs);
             yy[u] = load4<true>(y, q);
-            if constexpr (KEEP_M) mm[u] = load4<true>(m, q);
+            if constexpr (KEEP_M) mm[u] = load4<true>(m, qs);
             if constexpr (GAP) ss[u] = load4<true>(snap, q);
             gg[u] = load_g4<DT, ALIGNED>(g, q);
         }
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        const uint64_t q = base + (uint64_t)u * kBlock;
+        const uint64_t q = base + (uint64_t)u * kBlock, qs = base_s + (uint64_t)u * kBlock;
         if (q < n4) {
             f32x4 out;
 #pragma unroll
@@ -121,10 +125,10 @@ __device__ __forceinline__ void family_tile(float* __restrict__ theta, float* __
                 else out[e] = adam_one<MODE, KEEP_M>(t1, x1, y1, m1, ss[u][e], gg[u][e], c);
                 th[u][e] = t1; xx[u][e] = x1; yy[u][e] = y1; mm[u][e] = m1;
             }
-            store4<NT_TH>(theta, q, th[u]);
-            store4<NT_X>(x, q, xx[u]);
+            store4<NT_TH>(theta, qs, th[u]);
+            store4<NT_X>(x, qs, xx[u]);
             store4<true>(y, q, yy[u]);
-            if constexpr (KEEP_M) store4<true>(m, q, mm[u]);
+            if constexpr (KEEP_M) store4<true>(m, qs, mm[u]);
             if constexpr (SNAP) store4<true>(snap, q, out);
         }
     }
@@ -148,16 +152,16 @@ __global__ __launch_bounds__(kBlock) void family_apply_kernel(float* __restrict_
 #undef GA_FAMILY_TILE
 
     if (b == 0 && threadIdx.x < (N & 3)) {
-        const uint64_t j = 4 * n4 + threadIdx.x;
-        float t1 = theta[j], x1 = x[j], y1 = y[j], m1 = 0.0f, s1 = 0.0f, out;
-        if constexpr (KEEP_M) m1 = m[j];
+        const uint64_t j = 4 * n4 + threadIdx.x, js = state_index<1>(j);
+        float t1 = theta[js], x1 = x[js], y1 = y[j], m1 = 0.0f, s1 = 0.0f, out;
+        if constexpr (KEEP_M) m1 = m[js];
         if constexpr (GAP) s1 = snap[j];
         if constexpr (FAMILY == GA_FAMILY_DANA) out = dana_one<MODE, KEEP_M>(t1, x1, y1, m1, s1, load_g1<DT>(g, j), c);
         else out = adam_one<MODE, KEEP_M>(t1, x1, y1, m1, s1, load_g1<DT>(g, j), c);
-        theta[j] = t1;
-        x[j] = x1;
+        theta[js] = t1;
+        x[js] = x1;
         y[j] = y1;
-        if constexpr (KEEP_M) m[j] = m1;
+        if constexpr (KEEP_M) m[js] = m1;
         if constexpr (SNAP) snap[j] = out;
     }
 }
@@ -165,9 +169,10 @@ __global__ __launch_bounds__(kBlock) void family_apply_kernel(float* __restrict_
 // ---------------------------------------------------------------------------
 // Dispatch of the apply kernel over (mode, dtype, keep_m, aligned).
 // ---------------------------------------------------------------------------
-// Two groups per thread up to this many parameters, one beyond (measured with a 240 MiB resident part:
-// 80 M +1.8 %, 100 M +0.7 %, 151 M -0.3 %, 250 M -1.2 % of HBM peak for two against one).
-constexpr uint64_t kTwoGroupsMaxN = (uint64_t)128 << 20;
+// One group of four per thread (U = 1).  With separate state arrays two groups per thread were 1 - 2 % faster up to
+// 10^8 parameters; with the tiled state arrays one group is faster at every size (cfg3 129.0 against 130.4 us,
+// 100 M 527 against 545 us, 128 M 689 against 715 us).
+constexpr int kApplyU = 1;
 
 template <int MODE, int DT, bool KEEP_M, bool SNAP, bool ALIGNED, int U>
 hipError_t launch_apply_u(const StatePtrs& st, float* snap, const void* g, uint64_t N, const StepConst& c,
@@ -186,8 +191,7 @@ hipError_t launch_apply_u(const StatePtrs& st, float* snap, const void* g, uint6
 template <int MODE, int DT, bool KEEP_M, bool SNAP, bool ALIGNED>
 hipError_t launch_apply_t(const StatePtrs& st, float* snap, const void* g, uint64_t N, const StepConst& c,
                           hipStream_t stream) {
-    if (N <= kTwoGroupsMaxN) return launch_apply_u<MODE, DT, KEEP_M, SNAP, ALIGNED, 2>(st, snap, g, N, c, stream);
-    return launch_apply_u<MODE, DT, KEEP_M, SNAP, ALIGNED, 1>(st, snap, g, N, c, stream);
+    return launch_apply_u<MODE, DT, KEEP_M, SNAP, ALIGNED, kApplyU>(st, snap, g, N, c, stream);
 }
 
 template <int MODE, bool KEEP_M, bool SNAP>

@@ -118,25 +118,27 @@ bool build_layer_tables(uint64_t N, uint32_t n_layers, const uint64_t* sizes, st
     return start == N && n_chunks < 0x7FFFFFFFull;
 }
 
-// theta | v | m | W snapshots | [DANA: W worker momenta] | [ADAM: v2] | arrival, Adam and gradient-pointer tables | reduction partials
+// theta, v, m interleaved by tiles (ga_internal.h) | W snapshots | [DANA: W worker momenta] | [ADAM: v2] | arrival, Adam
+// and gradient-pointer tables | reduction partials
 Layout layout_for(uint64_t N, uint32_t W, int family, uint64_t n_chunks = 0, uint32_t n_layers = 0) {
     Layout L;
-    L.Np = round_up(N, 64);                  // every array starts 256-byte aligned
+    L.Np = round_up(N, 64);                  // every row starts 256-byte aligned
     const size_t row = (size_t)L.Np * sizeof(float);
+    const size_t tile = (size_t)ga::kStateTile * sizeof(float);
     L.off_theta = 0;
-    L.off_v = row;
-    L.off_m = 2 * row;
-    L.off_snaps = 3 * row;
-    L.n_rows = 3 + (uint64_t)W;
+    L.off_v = tile;
+    L.off_m = 2 * tile;
+    L.off_snaps = 3 * (size_t)round_up(N, ga::kStateTile) * sizeof(float);
+    L.n_rows = (uint64_t)W;                  // plain rows after the tiled part
     L.off_worker_v = L.off_v2 = 0;
     if (family == GA_FAMILY_DANA) {
-        L.off_worker_v = L.n_rows * row;
+        L.off_worker_v = L.off_snaps + L.n_rows * row;
         L.n_rows += W;
     } else if (family == GA_FAMILY_ADAM) {
-        L.off_v2 = L.n_rows * row;
+        L.off_v2 = L.off_snaps + L.n_rows * row;
         L.n_rows += 1;
     }
-    L.off_table = L.n_rows * row;
+    L.off_table = L.off_snaps + L.n_rows * row;
     L.off_adam_table = L.off_table + round_up((uint64_t)ga::kTableCap * sizeof(ga_arrival), 256);
     L.off_grad_table = L.off_adam_table + round_up((uint64_t)ga::kTableCap * sizeof(ga::AdamRow), 256);
     L.off_partials = L.off_grad_table + round_up((uint64_t)ga::kTableCap * sizeof(void*), 256);
@@ -379,17 +381,24 @@ int apply_one(ga_ctx* ctx, uint32_t worker, const void* dev_grad, int dtype, boo
     return GA_OK;
 }
 
+// theta, v and m are tiled in the workspace (ga_internal.h): a kernel gathers / scatters them; the rows are copied.
+bool is_tiled(const ga_ctx* ctx, const float* p) { return p == ctx->st.theta || p == ctx->st.v || p == ctx->st.m; }
+
 int copy_out(ga_ctx* ctx, float* dst, const float* src) {
     if (!ctx) return GA_ERR_ARG;
     if (!dst) return fail(ctx, GA_ERR_ARG, "destination is null");
-    const hipError_t e = hipMemcpyAsync(dst, src, ctx->N * sizeof(float), hipMemcpyDeviceToDevice, ctx->stream);
+    const hipError_t e = is_tiled(ctx, src)
+                             ? ga::launch_state_get(src, dst, ctx->N, ctx->stream)
+                             : hipMemcpyAsync(dst, src, ctx->N * sizeof(float), hipMemcpyDeviceToDevice, ctx->stream);
     return e == hipSuccess ? GA_OK : hip_fail(ctx, e, "copy");
 }
 
 int copy_in(ga_ctx* ctx, float* dst, const float* src) {
     if (!ctx) return GA_ERR_ARG;
     if (!src) return fail(ctx, GA_ERR_ARG, "source is null");
-    const hipError_t e = hipMemcpyAsync(dst, src, ctx->N * sizeof(float), hipMemcpyDeviceToDevice, ctx->stream);
+    const hipError_t e = is_tiled(ctx, dst)
+                             ? ga::launch_state_put(dst, src, ctx->N, ctx->stream)
+                             : hipMemcpyAsync(dst, src, ctx->N * sizeof(float), hipMemcpyDeviceToDevice, ctx->stream);
     return e == hipSuccess ? GA_OK : hip_fail(ctx, e, "copy");
 }
 
@@ -605,9 +614,9 @@ int ga_create_ex(ga_ctx** out, const ga_config* cfg, void* dev_workspace, size_t
     c->iter.assign(n_workers, 0);
 
     c->gap_scope = cfg->gap_scope;
-    c->state_bytes = (size_t)L.n_rows * L.Np * sizeof(float);
-    // all state rows are contiguous: one fill
-    hipError_t e = ga::launch_fill(c->st.theta, L.n_rows * L.Np, 0.0f, c->stream);
+    c->state_bytes = L.off_table;
+    // the tiled arrays and all rows are contiguous: one fill
+    hipError_t e = ga::launch_fill(c->st.theta, L.off_table / sizeof(float), 0.0f, c->stream);
     if (e == hipSuccess && n_layers > 0) {
         uint64_t nc = 0;
         build_layer_tables(N, n_layers, cfg->gap_scope == GA_GAP_LAYER ? cfg->host_layer_sizes : nullptr,
@@ -704,7 +713,7 @@ int ga_set_theta(ga_ctx* ctx, const float* dev_theta0) {
     if (!ctx) return GA_ERR_ARG;
     if (!dev_theta0) return fail(ctx, GA_ERR_ARG, "set_theta: source is null");
     if (ctx->k != 0) return fail(ctx, GA_ERR_STATE, "set_theta: only before the first arrival");
-    hipError_t e = ga::launch_broadcast_rows(ctx->st.theta, ctx->st.stride, 1, dev_theta0, ctx->N, ctx->stream);
+    hipError_t e = ga::launch_state_put(ctx->st.theta, dev_theta0, ctx->N, ctx->stream);
     if (e == hipSuccess) e = ga::launch_broadcast_rows(ctx->st.snaps, ctx->st.stride, ctx->W, dev_theta0, ctx->N, ctx->stream);
     return e == hipSuccess ? GA_OK : hip_fail(ctx, e, "set_theta");
 }

@@ -79,9 +79,10 @@ __device__ __forceinline__ void partial_body(const float* __restrict__ theta, co
         for (int u = 0; u < kLayerU; ++u) {
             const uint64_t q = q0 + (uint64_t)u * kBlock;
             if (q < q_end) {
-                th[u] = load4<NT_TH>(theta, q);
+                const uint64_t qs = state_index<4>(q);   // theta and m are tiled (ga_internal.h); a chunk may cross tiles
+                th[u] = load4<NT_TH>(theta, qs);
                 sv[u] = load4<true>(snap, q);
-                mm[u] = load4<true>(m, q);
+                mm[u] = load4<true>(m, qs);
             }
         }
 #pragma unroll
@@ -104,10 +105,14 @@ __global__ __launch_bounds__(kBlock) void layer_partial_kernel(const float* __re
                                                                uint64_t keep_theta) {
     const ChunkRange r = chunk_range(chunks[blockIdx.x]);
     double d2 = 0.0, ms = 0.0;
-    for (uint64_t j = r.start + threadIdx.x; j < r.a0; j += kBlock) gap_terms(d2, ms, theta[j], snap[j], m[j]);
+    auto scalar = [&](uint64_t j) {
+        const uint64_t js = state_index<1>(j);
+        gap_terms(d2, ms, theta[js], snap[j], m[js]);
+    };
+    for (uint64_t j = r.start + threadIdx.x; j < r.a0; j += kBlock) scalar(j);
     if (r.end <= keep_theta) GA_HINT_PATH("theta kept", partial_body<false>(theta, m, snap, r, d2, ms));
     else GA_HINT_PATH("all streamed", partial_body<true>(theta, m, snap, r, d2, ms));
-    for (uint64_t j = r.a1 + threadIdx.x; j < r.end; j += kBlock) gap_terms(d2, ms, theta[j], snap[j], m[j]);
+    for (uint64_t j = r.a1 + threadIdx.x; j < r.end; j += kBlock) scalar(j);
     store_chunk_partial(d2, ms, partials + blockIdx.x);
 }
 
@@ -192,9 +197,10 @@ __device__ __forceinline__ void apply_body(float* __restrict__ theta, float* __r
         for (int u = 0; u < U; ++u) {
             const uint64_t q = q0 + (uint64_t)u * kBlock;
             if (q < q_end) {
-                th[u] = load4<NT_TH>(theta, q);
-                vv[u] = load4<NT_V>(v, q);
-                mm[u] = load4<true>(m, q);
+                const uint64_t qs = state_index<4>(q);   // theta, v, m are tiled; a chunk may cross tiles
+                th[u] = load4<NT_TH>(theta, qs);
+                vv[u] = load4<NT_V>(v, qs);
+                mm[u] = load4<true>(m, qs);
                 gg[u] = load_g4<DT, ALIGNED>(g, q);
                 if constexpr (LOOK)
                     if (next_snap) nx[u] = load4<true>(next_snap, q);
@@ -211,9 +217,10 @@ __device__ __forceinline__ void apply_body(float* __restrict__ theta, float* __r
                     if constexpr (LOOK) gap_terms(d2, ms, t1, next_snap ? nx[u][e] : t1, m1);
                     th[u][e] = t1; vv[u][e] = v1; mm[u][e] = m1;
                 }
-                store4<NT_TH>(theta, q, th[u]);
-                store4<NT_V>(v, q, vv[u]);
-                store4<true>(m, q, mm[u]);
+                const uint64_t qs = state_index<4>(q);
+                store4<NT_TH>(theta, qs, th[u]);
+                store4<NT_V>(v, qs, vv[u]);
+                store4<true>(m, qs, mm[u]);
                 store4<true>(snap, q, th[u]);
             }
         }
@@ -238,10 +245,11 @@ __global__ __launch_bounds__(kBlock) void layer_apply_kernel(float* __restrict__
     const float G = gaps[ch.layer];
     double d2 = 0.0, ms = 0.0;
     auto scalar = [&](uint64_t j) {
-        float t1 = theta[j], v1 = v[j], m1 = m[j];
+        const uint64_t js = state_index<1>(j);
+        float t1 = theta[js], v1 = v[js], m1 = m[js];
         layer_update_one<NAG>(t1, v1, m1, load_g1<DT>(g, j), G, c);
         if constexpr (LOOK) gap_terms(d2, ms, t1, next_snap ? next_snap[j] : t1, m1);
-        theta[j] = t1; v[j] = v1; m[j] = m1; snap[j] = t1;
+        theta[js] = t1; v[js] = v1; m[js] = m1; snap[j] = t1;
     };
     for (uint64_t j = r.start + threadIdx.x; j < r.a0; j += kBlock) scalar(j);
 #define GA_LAYER_BODY(NT_TH, NT_V) \

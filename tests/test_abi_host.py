@@ -122,8 +122,10 @@ def test_workspace_size_and_create_validation():
     n1 = ga.ga_workspace_bytes(1, 1)
     assert n1 % 256 == 0 and n1 >= 4 * 256
     big = ga.ga_workspace_bytes(350_000_000, 128)
-    assert big >= 131 * 350_000_000 * 4 and big < 131 * 350_000_064 * 4 + (1 << 20)
-    assert ga.ga_workspace_bytes(65, 3) - ga.ga_workspace_bytes(64, 3) == 6 * 64 * 4   # rows padded to 64 floats
+    assert big >= 131 * 350_000_000 * 4 and big < 131 * 350_000_064 * 4 + (1 << 20) + 3 * 8192 * 4
+    # the W snapshot rows are padded to 64 floats; theta, v, m are interleaved by tiles of 8192 floats
+    assert ga.ga_workspace_bytes(65, 3) - ga.ga_workspace_bytes(64, 3) == 3 * 64 * 4
+    assert ga.ga_workspace_bytes(8193, 3) - ga.ga_workspace_bytes(8192, 3) == 3 * 8192 * 4 + 3 * 64 * 4
 
     ctx = C.c_void_p()
     fake = C.c_void_p(0x7F0000000000)               # never dereferenced: validation fails first
