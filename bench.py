@@ -403,7 +403,16 @@ def ceiling(args, torch, ga):
     for r, w in ((1, 0), (5, 0), (0, 1), (0, 4), (1, 1), (2, 2), (4, 4), (5, 1), (5, 2), (5, 4)):
         s = timed(lambda: ga.ga_probe_streams(bufs[:r], bufs[5:5 + w], n), 20)
         streams["%dr%dw" % (r, w)] = 4.0 * (r + w) * n / s / 1e9
-    del bufs
+    # the update's own pattern: four arrays rewritten in place and one more read; then the same with the first three
+    # laid out as the library lays out theta, v, m (interleaved by tiles of 8192 floats in one buffer)
+    s = timed(lambda: ga.ga_probe_streams(bufs[:5], bufs[:4], n), 20)
+    streams["5r4w_in_place"] = 4.0 * 9 * n / s / 1e9
+    tile = 8192
+    state = torch.full((3 * ((n + tile - 1) // tile) * tile,), 0.5, dtype=torch.float32, device=dev)
+    tiled = [state, state[tile:], state[2 * tile:], bufs[3], bufs[4]]
+    s = timed(lambda: ga.ga_probe_streams(tiled, tiled[:4], n, tiled=True), 20)
+    streams["5r4w_in_place_state_tiled"] = 4.0 * 9 * n / s / 1e9
+    del bufs, state, tiled
     torch.cuda.empty_cache()
     # Data held in the memory-side cache: two arrays of the cfg3 size (204 MB together) accessed without the hint,
     # alone and inside the fused update's mix: theta, v, m, snapshot updated in place, the gradient read, with the

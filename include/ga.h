@@ -516,6 +516,11 @@ int ga_box_muller_raw(const uint32_t* dev_xa, const uint32_t* dev_xb, uint64_t n
  *   as the update accesses the part of theta and v that it keeps in the
  *   memory-side cache.  An output may be the input of the same index (an
  *   update in place); other overlaps between arrays give undefined values.
+ *   tiled = 1: the first three input and the first three output arrays are
+ *   laid out as a master lays out theta, v, m -- interleaved by tiles of 8192
+ *   floats, [a0 tile 0 | a1 tile 0 | a2 tile 0 | a0 tile 1 | ...]: pointer i
+ *   (i < 3) is the start of array i's tile 0, i.e. base + 8192 i floats of
+ *   one buffer of 3 x (n rounded up to 8192) floats.
  * ga_probe_valu: blocks x 256 threads, each issuing iterations x 8 independent
  *   vector instructions of kind `op` (ga_probe_op); dev_out: 4 bytes, written
  *   only formally.  8 x 256 blocks give 8 wavefronts per SIMD on 256 CUs.
@@ -534,7 +539,7 @@ enum ga_probe_op {
 };
 int ga_probe_streams(uint32_t n_read, uint32_t n_write, uint64_t n, const float* const* host_dev_read,
                      float* const* host_dev_write, void* hip_stream);
-int ga_probe_streams_ex(uint32_t n_read, uint32_t n_write, uint32_t n_resident, uint64_t n,
+int ga_probe_streams_ex(uint32_t n_read, uint32_t n_write, uint32_t n_resident, int tiled, uint64_t n,
                         const float* const* host_dev_read, float* const* host_dev_write, void* hip_stream);
 int ga_probe_valu(int op, uint32_t blocks, uint32_t iterations, uint32_t* dev_out, void* hip_stream);
 

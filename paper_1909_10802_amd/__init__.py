@@ -119,7 +119,7 @@ SIGNATURES = {
     "ga_import_state": (_i, [_p, _p, C.c_size_t, _u64, _p]),
     "ga_noise_fill": (_i, [_u64, _u64, _u64, _u64, _p, _p]),
     "ga_probe_streams": (_i, [_u32, _u32, _u64, _p, _p, _p]),
-    "ga_probe_streams_ex": (_i, [_u32, _u32, _u32, _u64, _p, _p, _p]),
+    "ga_probe_streams_ex": (_i, [_u32, _u32, _u32, _i, _u64, _p, _p, _p]),
     "ga_probe_valu": (_i, [_i, _u32, _u32, _p, _p]),
     "ga_box_muller_raw": (_i, [_p, _p, _u64, _p, _p, _p]),
     "ga_last_error": (C.c_char_p, [_p]),
@@ -506,14 +506,15 @@ PROBE_OPS = {"v_fma_f32": 0, "v_xor_b32": 1, "v_mul_hi_u32": 2, "v_mad_u64_u32":
              "v_div_scale_f32": 6, "v_div_fmas_f32": 7, "v_div_fixup_f32": 8}
 
 
-def ga_probe_streams(reads, writes, n, stream=None, n_resident=0):
+def ga_probe_streams(reads, writes, n, stream=None, n_resident=0, tiled=False):
     """reads / writes: lists of float32 CUDA tensors of at least n elements; the first n_resident of each are
-    accessed without the non-temporal hint (writes[i] may be reads[i])."""
+    accessed without the non-temporal hint (writes[i] may be reads[i]).  tiled: the first three of each are views
+    of one buffer laid out as a master's theta, v, m (see ga_probe_streams_ex in include/ga.h)."""
     import torch
     r = (C.c_void_p * max(1, len(reads)))(*[_dev(t, torch.float32, n) for t in reads])
     w = (C.c_void_p * max(1, len(writes)))(*[_dev(t, torch.float32, n) for t in writes])
-    if n_resident:
-        _check(lib().ga_probe_streams_ex(len(reads), len(writes), n_resident, n, r, w, _stream_ptr(stream)))
+    if n_resident or tiled:
+        _check(lib().ga_probe_streams_ex(len(reads), len(writes), n_resident, int(tiled), n, r, w, _stream_ptr(stream)))
     else:
         _check(lib().ga_probe_streams(len(reads), len(writes), n, r, w, _stream_ptr(stream)))
 

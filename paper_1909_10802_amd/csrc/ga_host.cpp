@@ -1106,25 +1106,26 @@ int ga_import_state(ga_ctx* ctx, const void* dev_src, size_t bytes, uint64_t k, 
     return GA_OK;
 }
 
-int ga_probe_streams_ex(uint32_t n_read, uint32_t n_write, uint32_t n_resident, uint64_t n,
+int ga_probe_streams_ex(uint32_t n_read, uint32_t n_write, uint32_t n_resident, int tiled, uint64_t n,
                         const float* const* host_dev_read, float* const* host_dev_write, void* hip_stream) {
     const bool r_ok = n_read == 0 || n_read == 1 || n_read == 2 || n_read == 4 || n_read == 5;
     const bool w_ok = n_write == 0 || n_write == 1 || n_write == 2 || n_write == 4;
     if (!r_ok || !w_ok || n_read + n_write == 0) return fail(nullptr, GA_ERR_ARG, "probe_streams: n_read must be 0, 1, 2, 4 or 5 and n_write 0, 1, 2 or 4, not both 0");
     if (n_resident > 2) return fail(nullptr, GA_ERR_ARG, "probe_streams: n_resident must be 0, 1 or 2");
+    if (tiled != 0 && tiled != 1) return fail(nullptr, GA_ERR_ARG, "probe_streams: tiled must be 0 or 1");
     if (n == 0 || (n & 3u)) return fail(nullptr, GA_ERR_ARG, "probe_streams: n must be a positive multiple of 4");
     if ((n_read && !host_dev_read) || (n_write && !host_dev_write)) return fail(nullptr, GA_ERR_ARG, "probe_streams: null pointer table");
     for (uint32_t i = 0; i < n_read; ++i)
         if (!host_dev_read[i] || ((uintptr_t)host_dev_read[i] & 15u)) return fail(nullptr, GA_ERR_ARG, "probe_streams: input %u is null or not 16-byte aligned", i);
     for (uint32_t i = 0; i < n_write; ++i)
         if (!host_dev_write[i] || ((uintptr_t)host_dev_write[i] & 15u)) return fail(nullptr, GA_ERR_ARG, "probe_streams: output %u is null or not 16-byte aligned", i);
-    const hipError_t e = ga::launch_probe_streams(n_read, n_write, n_resident, n, host_dev_read, host_dev_write, static_cast<hipStream_t>(hip_stream));
+    const hipError_t e = ga::launch_probe_streams(n_read, n_write, n_resident, tiled != 0, n, host_dev_read, host_dev_write, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? GA_OK : hip_fail(nullptr, e, "probe_streams launch");
 }
 
 int ga_probe_streams(uint32_t n_read, uint32_t n_write, uint64_t n, const float* const* host_dev_read,
                      float* const* host_dev_write, void* hip_stream) {
-    return ga_probe_streams_ex(n_read, n_write, 0, n, host_dev_read, host_dev_write, hip_stream);
+    return ga_probe_streams_ex(n_read, n_write, 0, 0, n, host_dev_read, host_dev_write, hip_stream);
 }
 
 int ga_probe_valu(int op, uint32_t blocks, uint32_t iterations, uint32_t* dev_out, void* hip_stream) {

@@ -158,7 +158,7 @@ hipError_t launch_noise_fill(uint64_t seed, uint64_t k, uint64_t j0, uint64_t n,
 
 // Measurement aids (ga_probe.hip): n_read arrays read and n_write arrays written at once (n floats each); blocks x 256
 // threads each issuing iterations x 8 independent instructions of kind op (ga_probe_op).
-hipError_t launch_probe_streams(uint32_t n_read, uint32_t n_write, uint32_t n_resident, uint64_t n,
+hipError_t launch_probe_streams(uint32_t n_read, uint32_t n_write, uint32_t n_resident, bool tiled, uint64_t n,
                                 const float* const* reads, float* const* writes, hipStream_t stream);
 hipError_t launch_probe_valu(int op, uint32_t blocks, uint32_t iterations, uint32_t* dev_out, hipStream_t stream);
 

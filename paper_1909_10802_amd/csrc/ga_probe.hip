@@ -2,7 +2,8 @@
 // measure what this part delivers for the access pattern and the instruction mix of the kernels, so that the
 // roofline fractions quoted for those kernels can be re-derived on any machine:
 //   stream_probe_kernel   R arrays read and W arrays written at once, 128-bit accesses with the non-temporal hint
-//                         (the first KEEP read and written arrays without it: data held in the memory-side cache),
+//                         (the first KEEP read and written arrays without it: data held in the memory-side cache;
+//                         TILED: the first three as the tile-interleaved state arrays of a master),
 //                         the launch shape of the fused update (one group of four per thread)
 //   valu_probe_kernel     8 independent instructions of one kind per loop iteration
 
@@ -22,25 +23,28 @@ struct ProbePtrs {
 // Streams I = 0 .. of one group: the first KEEP without the hint.  The choice is made per instantiation (a fold over
 // the stream indices): a run-time or loop-carried choice between two accesses that differ only in the hint is merged
 // by the optimiser, which drops the hint.
-template <int KEEP, int... I>
-__device__ __forceinline__ f32x4 probe_load(const ProbePtrs& p, uint64_t q, std::integer_sequence<int, I...>) {
+// TILED: the first three arrays are the three tile-interleaved state arrays of a master (ga_internal.h): group q of
+// each is at state_index<4>(q) from its pointer.
+template <int KEEP, bool TILED, int... I>
+__device__ __forceinline__ f32x4 probe_load(const ProbePtrs& p, uint64_t q, uint64_t qs, std::integer_sequence<int, I...>) {
     f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
-    ((acc += load4<(I >= KEEP)>(p.r[I], q)), ...);
+    ((acc += load4<(I >= KEEP)>(p.r[I], (TILED && I < 3) ? qs : q)), ...);
     return acc;
 }
-template <int KEEP, int... I>
-__device__ __forceinline__ void probe_store(const ProbePtrs& p, uint64_t q, const f32x4& acc,
+template <int KEEP, bool TILED, int... I>
+__device__ __forceinline__ void probe_store(const ProbePtrs& p, uint64_t q, uint64_t qs, const f32x4& acc,
                                             std::integer_sequence<int, I...>) {
-    ((store4<(I >= KEEP)>(p.w[I], q, acc + (float)I)), ...);
+    ((store4<(I >= KEEP)>(p.w[I], (TILED && I < 3) ? qs : q, acc + (float)I)), ...);
 }
 
 // An output may be the input of the same index (an update in place): a thread loads its group before it stores it.
-template <int R, int W, int KEEP>
+template <int R, int W, int KEEP, bool TILED>
 __global__ __launch_bounds__(kBlock) void stream_probe_kernel(ProbePtrs p, uint64_t n4) {
     const uint64_t q = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
     if (q >= n4) return;
-    const f32x4 acc = probe_load<KEEP>(p, q, std::make_integer_sequence<int, R>{});
-    probe_store<KEEP>(p, q, acc, std::make_integer_sequence<int, W>{});
+    const uint64_t qs = state_index<4>(q);
+    const f32x4 acc = probe_load<KEEP, TILED>(p, q, qs, std::make_integer_sequence<int, R>{});
+    probe_store<KEEP, TILED>(p, q, qs, acc, std::make_integer_sequence<int, W>{});
     if constexpr (W == 0)
         if (acc.x == 12345.678f) const_cast<float*>(p.r[0])[0] = acc.y;   // keeps the loads alive; never true for the probe's data
 }
@@ -89,34 +93,34 @@ __global__ __launch_bounds__(kBlock) void valu_mad64_kernel(uint32_t* out, uint3
     if ((a0 ^ a1 ^ a2 ^ a3) == 0x12345678ull) out[0] = (uint32_t)a0;
 }
 
-template <int R, int KEEP>
+template <int R, int KEEP, bool TILED>
 hipError_t launch_streams_w(const ProbePtrs& p, uint32_t n_write, uint64_t n4, dim3 grid, hipStream_t stream) {
     switch (n_write) {
-        case 0: hipLaunchKernelGGL((stream_probe_kernel<R, 0, KEEP>), grid, dim3(kBlock), 0, stream, p, n4); break;
-        case 1: hipLaunchKernelGGL((stream_probe_kernel<R, 1, KEEP>), grid, dim3(kBlock), 0, stream, p, n4); break;
-        case 2: hipLaunchKernelGGL((stream_probe_kernel<R, 2, KEEP>), grid, dim3(kBlock), 0, stream, p, n4); break;
-        case 4: hipLaunchKernelGGL((stream_probe_kernel<R, 4, KEEP>), grid, dim3(kBlock), 0, stream, p, n4); break;
+        case 0: hipLaunchKernelGGL((stream_probe_kernel<R, 0, KEEP, TILED>), grid, dim3(kBlock), 0, stream, p, n4); break;
+        case 1: hipLaunchKernelGGL((stream_probe_kernel<R, 1, KEEP, TILED>), grid, dim3(kBlock), 0, stream, p, n4); break;
+        case 2: hipLaunchKernelGGL((stream_probe_kernel<R, 2, KEEP, TILED>), grid, dim3(kBlock), 0, stream, p, n4); break;
+        case 4: hipLaunchKernelGGL((stream_probe_kernel<R, 4, KEEP, TILED>), grid, dim3(kBlock), 0, stream, p, n4); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
 }
 
-template <int KEEP>
+template <int KEEP, bool TILED>
 hipError_t launch_streams_r(const ProbePtrs& p, uint32_t n_read, uint32_t n_write, uint64_t n4, dim3 grid,
                             hipStream_t stream) {
     switch (n_read) {
-        case 0: return launch_streams_w<0, KEEP>(p, n_write, n4, grid, stream);
-        case 1: return launch_streams_w<1, KEEP>(p, n_write, n4, grid, stream);
-        case 2: return launch_streams_w<2, KEEP>(p, n_write, n4, grid, stream);
-        case 4: return launch_streams_w<4, KEEP>(p, n_write, n4, grid, stream);
-        case 5: return launch_streams_w<5, KEEP>(p, n_write, n4, grid, stream);
+        case 0: return launch_streams_w<0, KEEP, TILED>(p, n_write, n4, grid, stream);
+        case 1: return launch_streams_w<1, KEEP, TILED>(p, n_write, n4, grid, stream);
+        case 2: return launch_streams_w<2, KEEP, TILED>(p, n_write, n4, grid, stream);
+        case 4: return launch_streams_w<4, KEEP, TILED>(p, n_write, n4, grid, stream);
+        case 5: return launch_streams_w<5, KEEP, TILED>(p, n_write, n4, grid, stream);
         default: return hipErrorInvalidValue;
     }
 }
 
 }  // namespace
 
-hipError_t launch_probe_streams(uint32_t n_read, uint32_t n_write, uint32_t n_resident, uint64_t n,
+hipError_t launch_probe_streams(uint32_t n_read, uint32_t n_write, uint32_t n_resident, bool tiled, uint64_t n,
                                 const float* const* reads, float* const* writes, hipStream_t stream) {
     if (n_read > (uint32_t)kProbeMaxStreams || n_write > (uint32_t)kProbeMaxStreams || n_read + n_write == 0)
         return hipErrorInvalidValue;
@@ -127,10 +131,13 @@ hipError_t launch_probe_streams(uint32_t n_read, uint32_t n_write, uint32_t n_re
     const uint64_t blocks = (n4 + kBlock - 1) / kBlock;
     if (blocks == 0 || blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
     const dim3 grid((uint32_t)blocks);
-    switch (n_resident) {
-        case 0: return launch_streams_r<0>(p, n_read, n_write, n4, grid, stream);
-        case 1: return launch_streams_r<1>(p, n_read, n_write, n4, grid, stream);
-        case 2: return launch_streams_r<2>(p, n_read, n_write, n4, grid, stream);
+    switch (n_resident * 2 + (tiled ? 1 : 0)) {
+        case 0: return launch_streams_r<0, false>(p, n_read, n_write, n4, grid, stream);
+        case 1: return launch_streams_r<0, true>(p, n_read, n_write, n4, grid, stream);
+        case 2: return launch_streams_r<1, false>(p, n_read, n_write, n4, grid, stream);
+        case 3: return launch_streams_r<1, true>(p, n_read, n_write, n4, grid, stream);
+        case 4: return launch_streams_r<2, false>(p, n_read, n_write, n4, grid, stream);
+        case 5: return launch_streams_r<2, true>(p, n_read, n_write, n4, grid, stream);
         default: return hipErrorInvalidValue;
     }
 }

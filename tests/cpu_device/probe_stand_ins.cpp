@@ -3,7 +3,7 @@
 #include "ga_internal.h"
 
 namespace ga {
-hipError_t launch_probe_streams(uint32_t, uint32_t, uint32_t, uint64_t, const float* const*, float* const*, hipStream_t) {
+hipError_t launch_probe_streams(uint32_t, uint32_t, uint32_t, bool, uint64_t, const float* const*, float* const*, hipStream_t) {
     return hipErrorNotSupported;
 }
 hipError_t launch_probe_valu(int, uint32_t, uint32_t, uint32_t*, hipStream_t) { return hipErrorNotSupported; }

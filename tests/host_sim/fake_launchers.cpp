@@ -83,7 +83,7 @@ hipError_t static_scratch_address(DiagPartial** out) {
 }
 hipError_t launch_box_muller_raw(const uint32_t*, const uint32_t*, uint64_t, float*, float*, hipStream_t) { return hipSuccess; }
 hipError_t launch_noise_fill(uint64_t, uint64_t, uint64_t, uint64_t, float*, hipStream_t) { return hipSuccess; }
-hipError_t launch_probe_streams(uint32_t, uint32_t, uint32_t, uint64_t, const float* const*, float* const*, hipStream_t) { return hipSuccess; }
+hipError_t launch_probe_streams(uint32_t, uint32_t, uint32_t, bool, uint64_t, const float* const*, float* const*, hipStream_t) { return hipSuccess; }
 hipError_t launch_probe_valu(int, uint32_t, uint32_t, uint32_t*, hipStream_t) { return hipSuccess; }
 hipError_t launch_state_get(const float* state, float* dst, uint64_t n, hipStream_t) {
     for (uint64_t i = 0; i < n; ++i) dst[i] = state[state_index<1>(i)];

@@ -74,7 +74,8 @@ def test_gap_statistics_hint_paths_survive_the_compiler(tmp_path):
 @pytest.mark.skipif(not os.path.exists(HIPCC), reason="needs hipcc")
 def test_stream_probe_hints_are_what_its_arguments_say(tmp_path):
     asm = assembly("ga_probe.hip", tmp_path)
-    # stream_probe_kernel<R, W, KEEP>: the first KEEP inputs and outputs without the hint, all others with it
+    # stream_probe_kernel<R, W, KEEP, TILED>: the first KEEP inputs and outputs without the hint, all others with it
     for R, W, KEEP in ((5, 4, 0), (5, 4, 2), (2, 2, 2), (1, 1, 1), (4, 4, 1)):
-        text = kernel_text(asm, "19stream_probe_kernelILi%dELi%dELi%dEE" % (R, W, KEEP))
-        assert counts(text) == (R - KEEP, KEEP, W - KEEP, KEEP), (R, W, KEEP)
+        for tiled in (0, 1):
+            text = kernel_text(asm, "19stream_probe_kernelILi%dELi%dELi%dELb%dEE" % (R, W, KEEP, tiled))
+            assert counts(text) == (R - KEEP, KEEP, W - KEEP, KEEP), (R, W, KEEP, tiled)

@@ -38,6 +38,31 @@ def test_stream_probe_in_place_with_a_resident_prefix(n_resident):
         assert np.all(h[:n] == want) and np.all(h[n:] == float(i + 1))
 
 
+def test_stream_probe_with_tiled_state_arrays():
+    # the first three arrays interleaved by tiles of 8192 floats in one buffer, as a master lays out theta, v, m
+    n, tile = 4 * 6_001, 8192                                   # three tiles, the last one ragged
+    tiles = (n + tile - 1) // tile
+    state = torch.full((3 * tiles * tile,), -1.0, device="cuda:0")
+    idx = torch.arange(n, device="cuda:0")
+    where = (idx // tile) * (3 * tile) + idx % tile
+    for a in range(3):
+        state[where + a * tile] = float(a + 1)
+    rows = [torch.full((n + 64,), float(i + 1), device="cuda:0") for i in (3, 4)]
+    arrays = [state, state[tile:], state[2 * tile:]] + rows
+    ga.ga_probe_streams(arrays, arrays[:4], n, tiled=True)
+    torch.cuda.synchronize()
+    h = state.cpu().numpy()
+    w = where.cpu().numpy()
+    for a in range(3):
+        assert np.all(h[w + a * tile] == 15.0 + a)
+    untouched = np.ones(h.size, bool)
+    for a in range(3):
+        untouched[w + a * tile] = False
+    assert np.all(h[untouched] == -1.0)
+    assert np.all(rows[0].cpu().numpy()[:n] == 18.0) and np.all(rows[0].cpu().numpy()[n:] == 4.0)
+    assert bool((rows[1] == 5.0).all())
+
+
 def test_probe_argument_errors():
     x = torch.zeros(64, device="cuda:0")
     out = torch.zeros(1, dtype=torch.int32, device="cuda:0")
