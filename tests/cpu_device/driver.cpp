@@ -6,7 +6,7 @@
 //
 // <directory>/scenario.txt: "name value" lines (integers; eta as a decimal).  Binary inputs beside it: sched.bin
 // (uint32 worker ids), a.bin / ts.bin (float, quadratic source), bufs.bin (n_bufs x N float or bfloat16 bits),
-// layers.bin (uint64 layer sizes).  Output: state.bin.
+// layers.bin (uint64 layer sizes), theta0.bin (float, optional start).  Output: state.bin.
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
@@ -79,6 +79,10 @@ int main(int argc, char** argv) {
     void* ws = device_alloc(ws_bytes);
     REQUIRE(ga_create_ex(&ctx, &cfg, ws, ws_bytes, nullptr) == GA_OK);
     REQUIRE(ga_set_resident_bytes(ctx, (uint64_t)s["resident_bytes"]) == GA_OK);
+    if ((int)s["theta0"]) {   // a start other than zero: theta and every snapshot (Alg. 2: theta^i = theta_0)
+        const std::vector<float> theta0 = read_file<float>(dir + "/theta0.bin", N);
+        REQUIRE(ga_set_theta(ctx, theta0.data()) == GA_OK);
+    }
 
     const std::vector<uint32_t> sched = read_file<uint32_t>(dir + "/sched.bin", T);
     std::vector<float> a, ts;

@@ -53,23 +53,28 @@ def driver(tmp_path_factory):
 
 
 def run(driver, tmp_path, N, W, T, seed, family=0, mode=3, source=0, scope=0, layers=None, nesterov=0, track_gap=0,
-        bf16=0, n_bufs=3, pick=0, queue=0, resident_bytes=240 << 20, eta=0.1, gamma=0.9, sigma=0.02, static_diag=0):
+        bf16=0, n_bufs=3, pick=0, queue=0, resident_bytes=240 << 20, eta=0.1, gamma=0.9, sigma=0.02, static_diag=0,
+        theta0=False):
     """Runs one scenario in the CPU build and the same in the oracle; returns (state arrays of the build, oracle)."""
     d = str(tmp_path)
     sched = oracle.simulate_schedule(W, T, oracle.DIST_EXP, 0.7, seed)
     sched.astype(np.uint32).tofile(os.path.join(d, "sched.bin"))
     diag_worker = int(sched[-2]) if W > 1 and sched[-2] != sched[-1] else int((sched[-1] + 1) % W)
     hy = oracle.Hyper(eta, 0.0 if family == 2 else gamma)
+    start = None
+    if theta0:
+        start = ga_inputs.optimum(N, seed + 1)
+        start.tofile(os.path.join(d, "theta0.bin"))
     if scope:
         sizes = [N] if scope == 2 else layers
         np.array(sizes, np.uint64).tofile(os.path.join(d, "layers.bin"))
-        O = oracle.LayerwiseMaster(N, W, MODE[mode], hy, layer_sizes=sizes, nesterov=bool(nesterov))
+        O = oracle.LayerwiseMaster(N, W, MODE[mode], hy, layer_sizes=sizes, nesterov=bool(nesterov), theta0=start)
     elif family == 0:
-        O = oracle.Master(N, W, MODE[mode], hy, track_gap=bool(track_gap), nesterov=bool(nesterov))
+        O = oracle.Master(N, W, MODE[mode], hy, track_gap=bool(track_gap), nesterov=bool(nesterov), theta0=start)
     elif family == 1:
-        O = oracle.DanaMaster(N, W, MODE[mode], hy, track_gap=bool(track_gap))
+        O = oracle.DanaMaster(N, W, MODE[mode], hy, track_gap=bool(track_gap), theta0=start)
     else:
-        O = oracle.AdamMaster(N, W, MODE[mode], hy, track_gap=bool(track_gap))
+        O = oracle.AdamMaster(N, W, MODE[mode], hy, track_gap=bool(track_gap), theta0=start)
     if source <= 1:
         a, ts = ga_inputs.curvatures(N, seed), ga_inputs.optimum(N, seed)
         a.tofile(os.path.join(d, "a.bin")); ts.tofile(os.path.join(d, "ts.bin"))
@@ -87,7 +92,7 @@ def run(driver, tmp_path, N, W, T, seed, family=0, mode=3, source=0, scope=0, la
     text = dict(N=N, W=W, T=T, seed=seed, family=family, mode=mode, source=source, gap_scope=scope,
                 n_layers=len(layers) if layers else 0, nesterov=nesterov, track_gap=track_gap, bf16=bf16, n_bufs=n_bufs,
                 pick=pick, queue=queue, resident_bytes=resident_bytes, eta=eta, gamma=gamma, sigma=sigma,
-                diag_worker=diag_worker, static_diag=static_diag)
+                diag_worker=diag_worker, static_diag=static_diag, theta0=int(theta0))
     with open(os.path.join(d, "scenario.txt"), "w") as f:
         for k, v in text.items():
             f.write("%s %r\n" % (k, v))
@@ -181,6 +186,16 @@ def test_quadratic_source_one_launch_per_arrival_and_queues(driver, tmp_path, N,
     got, O = run(driver, tmp_path, N, 3, 11, 600 + N, family=family, mode=3, source=3, bf16=1, eta=eta)
     check(got, O, family)
     got, O = run(driver, tmp_path, N, 3, 11, 700 + N, family=family, mode=3, source=2, queue=1, eta=eta)
+    check(got, O, family)
+
+
+@pytest.mark.parametrize("family", [0, 1, 2])
+def test_start_other_than_zero(driver, tmp_path, family):
+    # ga_set_theta scatters theta_0 into the tiled state and copies it to every snapshot
+    eta = 0.01 if family == 2 else 0.1
+    got, O = run(driver, tmp_path, 20483, 3, 9, 900 + family, family=family, mode=3, source=0, eta=eta, theta0=True)
+    check(got, O, family)
+    got, O = run(driver, tmp_path, 9001, 3, 9, 910 + family, family=family, mode=3, source=2, eta=eta, theta0=True)
     check(got, O, family)
 
 
