@@ -37,8 +37,8 @@ VALU_PER_UPDATE = {"ga": 106.7, "ga_hinge": 106.7}
 # scaled by a copy of known size; profiles/apply_kernel_cfg3.md).  The counters sit in front of the memory-side
 # cache, so hits in that cache are included.  Valid for the kernel source with this hash only.
 TRAFFIC = {
-    ("cfg3", "ga", 25_557_032): {"bytes": 920037094, "read": 511124165, "written": 408912929, "kernels_sha256": "7e6d1c376216fc85"},
-    ("cfg3", "ga", 151_000_000): {"bytes": 5435410664, "read": 3019391399, "written": 2416019266, "kernels_sha256": "7e6d1c376216fc85"},
+    ("cfg3", "ga", 25_557_032): {"bytes": 920050419, "read": 511137397, "written": 408913021, "kernels_sha256": "983771737102685a"},
+    ("cfg3", "ga", 151_000_000): {"bytes": 5435414232, "read": 3019394772, "written": 2416019460, "kernels_sha256": "983771737102685a"},
 }
 BYTES_PER_UPDATE = {           # algorithmic bytes per parameter per arrival, fused update
     ("ga", "f32"): 36, ("ga", "bf16"): 34, ("ga_hinge", "f32"): 36, ("ga_hinge", "bf16"): 34,

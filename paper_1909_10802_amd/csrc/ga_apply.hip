@@ -97,7 +97,11 @@ __device__ __forceinline__ void family_tile(float* __restrict__ theta, float* __
                                             const StepConst& c) {
     constexpr bool GAP = is_gap(MODE);
     static_assert((kStateTile / 4) % (kBlock * U) == 0, "a block's groups lie in one tile of the state arrays");
-    const uint64_t base_s = state_index<4>(base);   // the same groups in theta, x, m (tiled); y and the snapshot are rows
+    // the same groups in theta, x, m (tiled, ga_internal.h); Adam's y = v2 is the fourth tiled array, DANA's y = v_i
+    // and the snapshot are rows
+    constexpr int ROWS = state_rows(FAMILY);
+    constexpr bool Y_TILED = (FAMILY == GA_FAMILY_ADAM);
+    const uint64_t base_s = state_index<4, ROWS>(base);
     f32x4 th[U], xx[U], yy[U], mm[U], ss[U], gg[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -107,7 +111,7 @@ __device__ __forceinline__ void family_tile(float* __restrict__ theta, float* __
         if (q < n4) {
             th[u] = load4<NT_TH>(theta, qs);
             xx[u] = load4<NT_X>(x, qs);
-            yy[u] = load4<true>(y, q);
+            yy[u] = load4<true>(y, Y_TILED ? qs : q);
             if constexpr (KEEP_M) mm[u] = load4<true>(m, qs);
             if constexpr (GAP) ss[u] = load4<true>(snap, q);
             gg[u] = load_g4<DT, ALIGNED>(g, q);
@@ -127,7 +131,7 @@ __device__ __forceinline__ void family_tile(float* __restrict__ theta, float* __
             }
             store4<NT_TH>(theta, qs, th[u]);
             store4<NT_X>(x, qs, xx[u]);
-            store4<true>(y, q, yy[u]);
+            store4<true>(y, Y_TILED ? qs : q, yy[u]);
             if constexpr (KEEP_M) store4<true>(m, qs, mm[u]);
             if constexpr (SNAP) store4<true>(snap, q, out);
         }
@@ -152,15 +156,16 @@ __global__ __launch_bounds__(kBlock) void family_apply_kernel(float* __restrict_
 #undef GA_FAMILY_TILE
 
     if (b == 0 && threadIdx.x < (N & 3)) {
-        const uint64_t j = 4 * n4 + threadIdx.x, js = state_index<1>(j);
-        float t1 = theta[js], x1 = x[js], y1 = y[j], m1 = 0.0f, s1 = 0.0f, out;
+        const uint64_t j = 4 * n4 + threadIdx.x, js = state_index<1, state_rows(FAMILY)>(j);
+        const uint64_t jy = (FAMILY == GA_FAMILY_ADAM) ? js : j;
+        float t1 = theta[js], x1 = x[js], y1 = y[jy], m1 = 0.0f, s1 = 0.0f, out;
         if constexpr (KEEP_M) m1 = m[js];
         if constexpr (GAP) s1 = snap[j];
         if constexpr (FAMILY == GA_FAMILY_DANA) out = dana_one<MODE, KEEP_M>(t1, x1, y1, m1, s1, load_g1<DT>(g, j), c);
         else out = adam_one<MODE, KEEP_M>(t1, x1, y1, m1, s1, load_g1<DT>(g, j), c);
         theta[js] = t1;
         x[js] = x1;
-        y[j] = y1;
+        y[jy] = y1;
         if constexpr (KEEP_M) m[js] = m1;
         if constexpr (SNAP) snap[j] = out;
     }

@@ -114,8 +114,9 @@ __device__ __forceinline__ DiagPartial block_reduce(double sum, unsigned long lo
 
 // One block's groups [q0, q1): thread t takes q0 + t, q0 + t + kBlock, ..., two in flight, accumulated in that order.
 // NT_TH: theta is read with the non-temporal hint.
-// TILED: theta and m are the tiled state arrays of a master (ga_internal.h); otherwise plain arrays of the caller.
-template <bool NT_TH, bool TILED>
+// ROWS: theta and m are tiled state arrays of a master with that many arrays per tile (ga_internal.h); 0: plain
+// arrays of the caller.
+template <bool NT_TH, int ROWS>
 __device__ __forceinline__ void diag_span(DiagAcc& acc, const float* __restrict__ theta, const float* __restrict__ m,
                                           const float* __restrict__ snap, uint64_t q0, uint64_t q1, float inv_bc,
                                           float eta_max, float eps) {
@@ -126,7 +127,7 @@ __device__ __forceinline__ void diag_span(DiagAcc& acc, const float* __restrict_
         for (int u = 0; u < U; ++u) {
             const uint64_t qu = q + (uint64_t)u * kBlock;
             if (qu < q1) {
-                const uint64_t qs = TILED ? state_index<4>(qu) : qu;
+                const uint64_t qs = ROWS ? state_index<4, ROWS ? ROWS : 3>(qu) : qu;
                 th[u] = load4<NT_TH>(theta, qs);
                 s[u] = load4<true>(snap, qu);
                 mm[u] = load4<true>(m, qs);
@@ -148,7 +149,7 @@ __device__ __forceinline__ void diag_span(DiagAcc& acc, const float* __restrict_
 // over the same data is a quarter slower at 10^8 parameters).  keep_q: a block whose groups all lie below keep_q
 // reads theta without the hint (the part the update kernels keep in the memory-side cache); reading the rest of
 // theta without it would push that part out.
-template <bool TILED>
+template <int ROWS>
 __global__ __launch_bounds__(kBlock) void diag_kernel(const float* __restrict__ theta, const float* __restrict__ m,
                                                       const float* __restrict__ snap, uint64_t N, float inv_bc,
                                                       float eta_max, float eps, uint64_t per_block, uint64_t keep_q,
@@ -157,10 +158,10 @@ __global__ __launch_bounds__(kBlock) void diag_kernel(const float* __restrict__ 
     DiagAcc acc = {0.0, 0u, 0u, 0u};
     const uint64_t q0 = (uint64_t)blockIdx.x * per_block;
     const uint64_t q1 = q0 + per_block < n4 ? q0 + per_block : n4;
-    if (q1 <= keep_q) GA_HINT_PATH("theta kept", diag_span<false, TILED>(acc, theta, m, snap, q0, q1, inv_bc, eta_max, eps));
-    else GA_HINT_PATH("all streamed", diag_span<true, TILED>(acc, theta, m, snap, q0, q1, inv_bc, eta_max, eps));
+    if (q1 <= keep_q) GA_HINT_PATH("theta kept", diag_span<false, ROWS>(acc, theta, m, snap, q0, q1, inv_bc, eta_max, eps));
+    else GA_HINT_PATH("all streamed", diag_span<true, ROWS>(acc, theta, m, snap, q0, q1, inv_bc, eta_max, eps));
     if (blockIdx.x == 0 && threadIdx.x < (N & 3)) {
-        const uint64_t j = 4 * n4 + threadIdx.x, js = TILED ? state_index<1>(j) : j;
+        const uint64_t j = 4 * n4 + threadIdx.x, js = ROWS ? state_index<1, ROWS ? ROWS : 3>(j) : j;
         diag_one(acc, theta[js], snap[j], m[js], inv_bc, eta_max, eps);
     }
     const DiagPartial r = block_reduce(acc.sum, acc.gt1, acc.gt0, acc.bad);
@@ -244,11 +245,11 @@ __global__ __launch_bounds__(kBlock) void fill_kernel(float* __restrict__ dst, u
 }
 
 // One tiled state array (theta, v or m of a master; ga_internal.h) copied to or from a plain array of n floats.
-template <bool TO_STATE>
+template <bool TO_STATE, int ROWS>
 __global__ __launch_bounds__(kBlock) void state_copy_kernel(float* __restrict__ state, float* __restrict__ plain, uint64_t n) {
     for (uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += (uint64_t)gridDim.x * kBlock) {
-        if constexpr (TO_STATE) state[state_index<1>(i)] = plain[i];
-        else plain[i] = state[state_index<1>(i)];
+        if constexpr (TO_STATE) state[state_index<1, ROWS>(i)] = plain[i];
+        else plain[i] = state[state_index<1, ROWS>(i)];
     }
 }
 
@@ -278,9 +279,14 @@ hipError_t launch_diagnostics(const StatePtrs& st, uint64_t N, uint32_t worker, 
                               float eps, DiagPartial* dev_partials, ga_diag* dev_report, hipStream_t stream) {
     const DiagShape shape = diag_shape(N);
     const uint32_t grid = shape.grid;
-    hipLaunchKernelGGL(diag_kernel<true>, dim3(grid), dim3(kBlock), 0, stream, st.theta, st.m,
-                       st.snaps + (uint64_t)worker * st.stride, N, inv_bc, eta_max, eps, shape.per_block,
-                       st.resident_bytes / sizeof(f32x4), dev_partials);
+    if (st.rows == 4)
+        hipLaunchKernelGGL(diag_kernel<4>, dim3(grid), dim3(kBlock), 0, stream, st.theta, st.m,
+                           st.snaps + (uint64_t)worker * st.stride, N, inv_bc, eta_max, eps, shape.per_block,
+                           st.resident_bytes / sizeof(f32x4), dev_partials);
+    else
+        hipLaunchKernelGGL(diag_kernel<3>, dim3(grid), dim3(kBlock), 0, stream, st.theta, st.m,
+                           st.snaps + (uint64_t)worker * st.stride, N, inv_bc, eta_max, eps, shape.per_block,
+                           st.resident_bytes / sizeof(f32x4), dev_partials);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (dev_report)
@@ -316,7 +322,7 @@ hipError_t launch_diagnostics_static(const float* theta, const float* snap, cons
     // every partial that the report kernel reads is written by this launch first: nothing has to start at zero
     const DiagShape shape = diag_shape(N);
     const uint32_t grid = shape.grid;
-    hipLaunchKernelGGL(diag_kernel<false>, dim3(grid), dim3(kBlock), 0, stream, theta, m, snap, N, inv_bc, eta_max, eps,
+    hipLaunchKernelGGL(diag_kernel<0>, dim3(grid), dim3(kBlock), 0, stream, theta, m, snap, N, inv_bc, eta_max, eps,
                        shape.per_block, kResidentBytes / sizeof(f32x4), partials);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -356,17 +362,21 @@ hipError_t launch_broadcast_rows(float* dst, uint64_t stride, uint32_t rows, con
     return hipGetLastError();
 }
 
-hipError_t launch_state_get(const float* state, float* dst, uint64_t n, hipStream_t stream) {
+hipError_t launch_state_get(const float* state, int rows, float* dst, uint64_t n, hipStream_t stream) {
     if (n == 0) return hipSuccess;
-    hipLaunchKernelGGL(state_copy_kernel<false>, dim3(blocks_for(n, kBlock * 8, 65536)), dim3(kBlock), 0, stream,
-                       const_cast<float*>(state), dst, n);
+    const dim3 grid(blocks_for(n, kBlock * 8, 65536)), block(kBlock);
+    if (rows == 4) hipLaunchKernelGGL((state_copy_kernel<false, 4>), grid, block, 0, stream, const_cast<float*>(state), dst, n);
+    else if (rows == 3) hipLaunchKernelGGL((state_copy_kernel<false, 3>), grid, block, 0, stream, const_cast<float*>(state), dst, n);
+    else return hipErrorInvalidValue;
     return hipGetLastError();
 }
 
-hipError_t launch_state_put(float* state, const float* src, uint64_t n, hipStream_t stream) {
+hipError_t launch_state_put(float* state, int rows, const float* src, uint64_t n, hipStream_t stream) {
     if (n == 0) return hipSuccess;
-    hipLaunchKernelGGL(state_copy_kernel<true>, dim3(blocks_for(n, kBlock * 8, 65536)), dim3(kBlock), 0, stream, state,
-                       const_cast<float*>(src), n);
+    const dim3 grid(blocks_for(n, kBlock * 8, 65536)), block(kBlock);
+    if (rows == 4) hipLaunchKernelGGL((state_copy_kernel<true, 4>), grid, block, 0, stream, state, const_cast<float*>(src), n);
+    else if (rows == 3) hipLaunchKernelGGL((state_copy_kernel<true, 3>), grid, block, 0, stream, state, const_cast<float*>(src), n);
+    else return hipErrorInvalidValue;
     return hipGetLastError();
 }
 

@@ -118,8 +118,8 @@ bool build_layer_tables(uint64_t N, uint32_t n_layers, const uint64_t* sizes, st
     return start == N && n_chunks < 0x7FFFFFFFull;
 }
 
-// theta, v, m interleaved by tiles (ga_internal.h) | W snapshots | [DANA: W worker momenta] | [ADAM: v2] | arrival, Adam
-// and gradient-pointer tables | reduction partials
+// theta, v, m [ADAM: and v2] interleaved by tiles (ga_internal.h) | W snapshots | [DANA: W worker momenta] | arrival,
+// Adam and gradient-pointer tables | reduction partials
 Layout layout_for(uint64_t N, uint32_t W, int family, uint64_t n_chunks = 0, uint32_t n_layers = 0) {
     Layout L;
     L.Np = round_up(N, 64);                  // every row starts 256-byte aligned
@@ -128,15 +128,13 @@ Layout layout_for(uint64_t N, uint32_t W, int family, uint64_t n_chunks = 0, uin
     L.off_theta = 0;
     L.off_v = tile;
     L.off_m = 2 * tile;
-    L.off_snaps = 3 * (size_t)round_up(N, ga::kStateTile) * sizeof(float);
+    L.off_v2 = family == GA_FAMILY_ADAM ? 3 * tile : 0;      // ADAM: the fourth tiled array
+    L.off_snaps = (size_t)ga::state_rows(family) * (size_t)round_up(N, ga::kStateTile) * sizeof(float);
     L.n_rows = (uint64_t)W;                  // plain rows after the tiled part
-    L.off_worker_v = L.off_v2 = 0;
+    L.off_worker_v = 0;
     if (family == GA_FAMILY_DANA) {
         L.off_worker_v = L.off_snaps + L.n_rows * row;
         L.n_rows += W;
-    } else if (family == GA_FAMILY_ADAM) {
-        L.off_v2 = L.off_snaps + L.n_rows * row;
-        L.n_rows += 1;
     }
     L.off_table = L.off_snaps + L.n_rows * row;
     L.off_adam_table = L.off_table + round_up((uint64_t)ga::kTableCap * sizeof(ga_arrival), 256);
@@ -382,13 +380,15 @@ int apply_one(ga_ctx* ctx, uint32_t worker, const void* dev_grad, int dtype, boo
 }
 
 // theta, v and m are tiled in the workspace (ga_internal.h): a kernel gathers / scatters them; the rows are copied.
-bool is_tiled(const ga_ctx* ctx, const float* p) { return p == ctx->st.theta || p == ctx->st.v || p == ctx->st.m; }
+bool is_tiled(const ga_ctx* ctx, const float* p) {
+    return p == ctx->st.theta || p == ctx->st.v || p == ctx->st.m || (ctx->st.v2 && p == ctx->st.v2);
+}
 
 int copy_out(ga_ctx* ctx, float* dst, const float* src) {
     if (!ctx) return GA_ERR_ARG;
     if (!dst) return fail(ctx, GA_ERR_ARG, "destination is null");
     const hipError_t e = is_tiled(ctx, src)
-                             ? ga::launch_state_get(src, dst, ctx->N, ctx->stream)
+                             ? ga::launch_state_get(src, ctx->st.rows, dst, ctx->N, ctx->stream)
                              : hipMemcpyAsync(dst, src, ctx->N * sizeof(float), hipMemcpyDeviceToDevice, ctx->stream);
     return e == hipSuccess ? GA_OK : hip_fail(ctx, e, "copy");
 }
@@ -397,7 +397,7 @@ int copy_in(ga_ctx* ctx, float* dst, const float* src) {
     if (!ctx) return GA_ERR_ARG;
     if (!src) return fail(ctx, GA_ERR_ARG, "source is null");
     const hipError_t e = is_tiled(ctx, dst)
-                             ? ga::launch_state_put(dst, src, ctx->N, ctx->stream)
+                             ? ga::launch_state_put(dst, ctx->st.rows, src, ctx->N, ctx->stream)
                              : hipMemcpyAsync(dst, src, ctx->N * sizeof(float), hipMemcpyDeviceToDevice, ctx->stream);
     return e == hipSuccess ? GA_OK : hip_fail(ctx, e, "copy");
 }
@@ -605,6 +605,7 @@ int ga_create_ex(ga_ctx** out, const ga_config* cfg, void* dev_workspace, size_t
     c->st.snaps = reinterpret_cast<float*>(base + L.off_snaps);
     c->st.worker_v = L.off_worker_v ? reinterpret_cast<float*>(base + L.off_worker_v) : nullptr;
     c->st.v2 = L.off_v2 ? reinterpret_cast<float*>(base + L.off_v2) : nullptr;
+    c->st.rows = ga::state_rows(cfg->family);
     c->st.stride = L.Np;
     c->st.resident_bytes = ga::kResidentBytes;
     c->dev_table = reinterpret_cast<ga_arrival*>(base + L.off_table);
@@ -713,7 +714,7 @@ int ga_set_theta(ga_ctx* ctx, const float* dev_theta0) {
     if (!ctx) return GA_ERR_ARG;
     if (!dev_theta0) return fail(ctx, GA_ERR_ARG, "set_theta: source is null");
     if (ctx->k != 0) return fail(ctx, GA_ERR_STATE, "set_theta: only before the first arrival");
-    hipError_t e = ga::launch_state_put(ctx->st.theta, dev_theta0, ctx->N, ctx->stream);
+    hipError_t e = ga::launch_state_put(ctx->st.theta, ctx->st.rows, dev_theta0, ctx->N, ctx->stream);
     if (e == hipSuccess) e = ga::launch_broadcast_rows(ctx->st.snaps, ctx->st.stride, ctx->W, dev_theta0, ctx->N, ctx->stream);
     return e == hipSuccess ? GA_OK : hip_fail(ctx, e, "set_theta");
 }

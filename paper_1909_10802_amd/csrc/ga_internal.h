@@ -83,12 +83,16 @@ constexpr uint64_t kResidentBytes = (uint64_t)240 << 20;
 // arrays at 151 M and 350 M parameters (16 and 64 KiB tiles less, 128 KiB and more nothing).  Element j of one of
 // the arrays is at state_index<1>(j) floats from that array's pointer in StatePtrs; a group of four (an aligned pair)
 // at state_index<4> (state_index<2>) such units.  The snapshots and the other per-worker arrays are plain rows.
+// The Adam master has a fourth array of that kind, the second moment v2: its tiles follow m's (ROWS = 4; measured
+// with the same stand-alone kernel at 151 M parameters: 5.99 TB/s with v2 as a separate array, 6.40 TB/s as the
+// fourth tiled one).
 constexpr uint64_t kStateTile = 8192;
-template <int UNIT>
+template <int UNIT, int ROWS = 3>
 __host__ __device__ inline uint64_t state_index(uint64_t i) {
     constexpr uint64_t per_tile = kStateTile / UNIT;
-    return (i / per_tile) * (3 * per_tile) + (i % per_tile);
+    return (i / per_tile) * (ROWS * per_tile) + (i % per_tile);
 }
+constexpr int state_rows(int family) { return family == GA_FAMILY_ADAM ? 4 : 3; }
 
 // State pointers inside the workspace.  snaps is W rows of `stride` floats.
 struct StatePtrs {
@@ -97,7 +101,8 @@ struct StatePtrs {
     float* m;         // tile 0 of the Alg. 14 state (= theta + 2 kStateTile)
     float* snaps;
     float* worker_v;  // DANA: W rows of v_i, else null
-    float* v2;        // ADAM: second moment, else null
+    float* v2;        // ADAM: tile 0 of the second moment (= theta + 3 kStateTile; index with state_index<.., 4>), else null
+    int rows;         // tiled arrays per tile: state_rows(family)
     uint64_t stride;  // floats between consecutive workers' rows (N rounded up to 64)
     uint64_t resident_bytes;  // budget of the cache-resident leading part of theta, v, m
 };
@@ -162,9 +167,10 @@ hipError_t launch_probe_streams(uint32_t n_read, uint32_t n_write, uint32_t n_re
                                 const float* const* reads, float* const* writes, hipStream_t stream);
 hipError_t launch_probe_valu(int op, uint32_t blocks, uint32_t iterations, uint32_t* dev_out, hipStream_t stream);
 
-// One tiled state array (the theta, v or m pointer of StatePtrs) read into / written from a plain array of n floats.
-hipError_t launch_state_get(const float* state, float* dst, uint64_t n, hipStream_t stream);
-hipError_t launch_state_put(float* state, const float* src, uint64_t n, hipStream_t stream);
+// One tiled state array (the theta, v, m or v2 pointer of StatePtrs) read into / written from a plain array of n
+// floats; rows = state_rows(family).
+hipError_t launch_state_get(const float* state, int rows, float* dst, uint64_t n, hipStream_t stream);
+hipError_t launch_state_put(float* state, int rows, const float* src, uint64_t n, hipStream_t stream);
 
 // dst[0..n) = value;  dst[r][0..n) = src[0..n) for r < rows (row stride in floats).
 hipError_t launch_fill(float* dst, uint64_t n, float value, hipStream_t stream);

@@ -89,13 +89,13 @@ __global__ __launch_bounds__(kBlock) void persistent_kernel(float* __restrict__ 
     const uint32_t n_valid = (N - j0 >= (uint64_t)E) ? (uint32_t)E : (uint32_t)(N - j0);
 
     // every array is padded so that the vector access is always in bounds; theta, x and m are tiled (ga_internal.h)
-    const uint64_t ps = state_index<E>(p);
+    const uint64_t ps = state_index<E, state_rows(FAMILY)>(p);
     Pack<E> th = pack_load<E>(theta, ps);
     Pack<E> xx = pack_load<E>(x, ps);                          // v | sum_j v_j | m1
     Pack<E> mm = pack_zero<E>();
     if constexpr (KEEP_M) mm = pack_load<E>(m, ps);
     Pack<E> yy = pack_zero<E>();                               // ADAM: v2 (registers); DANA: v_i of the arriving worker
-    if constexpr (ADAM) yy = pack_load<E>(v2, p);
+    if constexpr (ADAM) yy = pack_load<E>(v2, ps);           // the fourth tiled array
     Pack<E> a4 = pack_zero<E>(), t4 = pack_zero<E>();
     if constexpr (QUAD) {
         if (n_valid == (uint32_t)E) {
@@ -181,7 +181,7 @@ __global__ __launch_bounds__(kBlock) void persistent_kernel(float* __restrict__ 
     pack_store<E>(theta, ps, th);
     pack_store<E>(x, ps, xx);
     if constexpr (KEEP_M) pack_store<E>(m, ps, mm);
-    if constexpr (ADAM) pack_store<E>(v2, p, yy);
+    if constexpr (ADAM) pack_store<E>(v2, ps, yy);
 }
 
 // Picks the instantiation for the family, penalty and vector length and launches it.

@@ -85,12 +85,12 @@ hipError_t launch_box_muller_raw(const uint32_t*, const uint32_t*, uint64_t, flo
 hipError_t launch_noise_fill(uint64_t, uint64_t, uint64_t, uint64_t, float*, hipStream_t) { return hipSuccess; }
 hipError_t launch_probe_streams(uint32_t, uint32_t, uint32_t, bool, uint64_t, const float* const*, float* const*, hipStream_t) { return hipSuccess; }
 hipError_t launch_probe_valu(int, uint32_t, uint32_t, uint32_t*, hipStream_t) { return hipSuccess; }
-hipError_t launch_state_get(const float* state, float* dst, uint64_t n, hipStream_t) {
-    for (uint64_t i = 0; i < n; ++i) dst[i] = state[state_index<1>(i)];
+hipError_t launch_state_get(const float* state, int rows, float* dst, uint64_t n, hipStream_t) {
+    for (uint64_t i = 0; i < n; ++i) dst[i] = state[rows == 4 ? state_index<1, 4>(i) : state_index<1, 3>(i)];
     return hipSuccess;
 }
-hipError_t launch_state_put(float* state, const float* src, uint64_t n, hipStream_t) {
-    for (uint64_t i = 0; i < n; ++i) state[state_index<1>(i)] = src[i];
+hipError_t launch_state_put(float* state, int rows, const float* src, uint64_t n, hipStream_t) {
+    for (uint64_t i = 0; i < n; ++i) state[rows == 4 ? state_index<1, 4>(i) : state_index<1, 3>(i)] = src[i];
     return hipSuccess;
 }
 hipError_t launch_fill(float* dst, uint64_t n, float value, hipStream_t) {

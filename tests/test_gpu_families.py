@@ -176,8 +176,9 @@ def test_family_argument_errors():
     assert e.value.status == ga.GA_ERR_WORKER
     assert ga.ga_workspace_bytes_ex(ga.ga_config_init(N=128, n_workers=4, family=ga.GA_FAMILY_DANA)) \
         - ga.ga_workspace_bytes(128, 4) == 4 * 128 * 4
+    # Adam's second moment is a fourth array in the tile structure of theta, m1, m (tiles of 8192 floats)
     assert ga.ga_workspace_bytes_ex(ga.ga_config_init(N=128, n_workers=4, family=ga.GA_FAMILY_ADAM)) \
-        - ga.ga_workspace_bytes(128, 4) == 128 * 4
+        - ga.ga_workspace_bytes(128, 4) == 8192 * 4
 
 
 @pytest.mark.parametrize("family", FAMILIES, ids=["dana", "adam"])
