@@ -99,27 +99,28 @@ __device__ __forceinline__ void family_tile(float* __restrict__ theta, float* __
     static_assert((kStateTile / 4) % (kBlock * U) == 0, "a block's groups lie in one tile of the state arrays");
     // the same groups in theta, x, m (tiled, ga_internal.h); Adam's y = v2 is the fourth tiled array, DANA's y = v_i
     // and the snapshot are rows
-    constexpr int ROWS = state_rows(FAMILY);
-    constexpr bool Y_TILED = (FAMILY == GA_FAMILY_ADAM);
+    constexpr int ROWS = state_rows(FAMILY), SROWS = snapshot_rows(FAMILY);
+    constexpr bool ADAM = (FAMILY == GA_FAMILY_ADAM);
     const uint64_t base_s = state_index<4, ROWS>(base);
+    const uint64_t base_r = row_index<4, SROWS>(base);   // the same groups in the worker's snapshot (DANA: and in its v_i)
     f32x4 th[U], xx[U], yy[U], mm[U], ss[U], gg[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        const uint64_t q = base + (uint64_t)u * kBlock, qs = base_s + (uint64_t)u * kBlock;
+        const uint64_t q = base + (uint64_t)u * kBlock, qs = base_s + (uint64_t)u * kBlock, qr = base_r + (uint64_t)u * kBlock;
         mm[u] = f32x4{0.f, 0.f, 0.f, 0.f};
         ss[u] = f32x4{0.f, 0.f, 0.f, 0.f};
         if (q < n4) {
             th[u] = load4<NT_TH>(theta, qs);
             xx[u] = load4<NT_X>(x, qs);
-            yy[u] = load4<true>(y, Y_TILED ? qs : q);
+            yy[u] = load4<true>(y, ADAM ? qs : qr);
             if constexpr (KEEP_M) mm[u] = load4<true>(m, qs);
-            if constexpr (GAP) ss[u] = load4<true>(snap, q);
+            if constexpr (GAP) ss[u] = load4<true>(snap, qr);
             gg[u] = load_g4<DT, ALIGNED>(g, q);
         }
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        const uint64_t q = base + (uint64_t)u * kBlock, qs = base_s + (uint64_t)u * kBlock;
+        const uint64_t q = base + (uint64_t)u * kBlock, qs = base_s + (uint64_t)u * kBlock, qr = base_r + (uint64_t)u * kBlock;
         if (q < n4) {
             f32x4 out;
 #pragma unroll
@@ -131,9 +132,9 @@ __device__ __forceinline__ void family_tile(float* __restrict__ theta, float* __
             }
             store4<NT_TH>(theta, qs, th[u]);
             store4<NT_X>(x, qs, xx[u]);
-            store4<true>(y, Y_TILED ? qs : q, yy[u]);
+            store4<true>(y, ADAM ? qs : qr, yy[u]);
             if constexpr (KEEP_M) store4<true>(m, qs, mm[u]);
-            if constexpr (SNAP) store4<true>(snap, q, out);
+            if constexpr (SNAP) store4<true>(snap, qr, out);
         }
     }
 }
@@ -157,17 +158,18 @@ __global__ __launch_bounds__(kBlock) void family_apply_kernel(float* __restrict_
 
     if (b == 0 && threadIdx.x < (N & 3)) {
         const uint64_t j = 4 * n4 + threadIdx.x, js = state_index<1, state_rows(FAMILY)>(j);
-        const uint64_t jy = (FAMILY == GA_FAMILY_ADAM) ? js : j;
+        const uint64_t jr = row_index<1, snapshot_rows(FAMILY)>(j);
+        const uint64_t jy = (FAMILY == GA_FAMILY_ADAM) ? js : jr;
         float t1 = theta[js], x1 = x[js], y1 = y[jy], m1 = 0.0f, s1 = 0.0f, out;
         if constexpr (KEEP_M) m1 = m[js];
-        if constexpr (GAP) s1 = snap[j];
+        if constexpr (GAP) s1 = snap[jr];
         if constexpr (FAMILY == GA_FAMILY_DANA) out = dana_one<MODE, KEEP_M>(t1, x1, y1, m1, s1, load_g1<DT>(g, j), c);
         else out = adam_one<MODE, KEEP_M>(t1, x1, y1, m1, s1, load_g1<DT>(g, j), c);
         theta[js] = t1;
         x[js] = x1;
         y[jy] = y1;
         if constexpr (KEEP_M) m[js] = m1;
-        if constexpr (SNAP) snap[j] = out;
+        if constexpr (SNAP) snap[jr] = out;
     }
 }
 

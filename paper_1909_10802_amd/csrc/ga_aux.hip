@@ -29,6 +29,8 @@ __global__ __launch_bounds__(kBlock) void box_muller_raw_kernel(const uint32_t* 
     zs[i] = s;
 }
 
+// SROWS: snapshot_rows of the master's family (ga_internal.h).
+template <int SROWS>
 __global__ __launch_bounds__(kBlock) void quadratic_gradient_kernel(const float* __restrict__ snap,
                                                                     const float* __restrict__ a,
                                                                     const float* __restrict__ ts, uint64_t N,
@@ -39,7 +41,7 @@ __global__ __launch_bounds__(kBlock) void quadratic_gradient_kernel(const float*
     if (j0 >= N) return;
     const f32x4 z = noise4(rc.seed_lo, rc.seed_hi, q, k);
     if (j0 + 3 < N) {
-        const f32x4 s = reinterpret_cast<const f32x4*>(snap)[q];
+        const f32x4 s = reinterpret_cast<const f32x4*>(snap)[row_index<4, SROWS>(q)];
         const f32x4 a4 = reinterpret_cast<const f32x4*>(a)[q];
         const f32x4 t4 = reinterpret_cast<const f32x4*>(ts)[q];
         f32x4 g;
@@ -51,7 +53,7 @@ __global__ __launch_bounds__(kBlock) void quadratic_gradient_kernel(const float*
     } else {
         const float zz[4] = {z.x, z.y, z.z, z.w};
         for (int e = 0; e < 4 && j0 + e < N; ++e)
-            g_out[j0 + e] = quadratic_g(snap[j0 + e], a[j0 + e], ts[j0 + e], rc.sigma, zz[e]);
+            g_out[j0 + e] = quadratic_g(snap[row_index<1, SROWS>(j0 + e)], a[j0 + e], ts[j0 + e], rc.sigma, zz[e]);
     }
 }
 
@@ -116,7 +118,7 @@ __device__ __forceinline__ DiagPartial block_reduce(double sum, unsigned long lo
 // NT_TH: theta is read with the non-temporal hint.
 // ROWS: theta and m are tiled state arrays of a master with that many arrays per tile (ga_internal.h); 0: plain
 // arrays of the caller.
-template <bool NT_TH, int ROWS>
+template <bool NT_TH, int ROWS, int SROWS>
 __device__ __forceinline__ void diag_span(DiagAcc& acc, const float* __restrict__ theta, const float* __restrict__ m,
                                           const float* __restrict__ snap, uint64_t q0, uint64_t q1, float inv_bc,
                                           float eta_max, float eps) {
@@ -129,7 +131,7 @@ __device__ __forceinline__ void diag_span(DiagAcc& acc, const float* __restrict_
             if (qu < q1) {
                 const uint64_t qs = ROWS ? state_index<4, ROWS ? ROWS : 3>(qu) : qu;
                 th[u] = load4<NT_TH>(theta, qs);
-                s[u] = load4<true>(snap, qu);
+                s[u] = load4<true>(snap, row_index<4, SROWS>(qu));
                 mm[u] = load4<true>(m, qs);
             }
         }
@@ -149,7 +151,7 @@ __device__ __forceinline__ void diag_span(DiagAcc& acc, const float* __restrict_
 // over the same data is a quarter slower at 10^8 parameters).  keep_q: a block whose groups all lie below keep_q
 // reads theta without the hint (the part the update kernels keep in the memory-side cache); reading the rest of
 // theta without it would push that part out.
-template <int ROWS>
+template <int ROWS, int SROWS>
 __global__ __launch_bounds__(kBlock) void diag_kernel(const float* __restrict__ theta, const float* __restrict__ m,
                                                       const float* __restrict__ snap, uint64_t N, float inv_bc,
                                                       float eta_max, float eps, uint64_t per_block, uint64_t keep_q,
@@ -158,11 +160,11 @@ __global__ __launch_bounds__(kBlock) void diag_kernel(const float* __restrict__ 
     DiagAcc acc = {0.0, 0u, 0u, 0u};
     const uint64_t q0 = (uint64_t)blockIdx.x * per_block;
     const uint64_t q1 = q0 + per_block < n4 ? q0 + per_block : n4;
-    if (q1 <= keep_q) GA_HINT_PATH("theta kept", diag_span<false, ROWS>(acc, theta, m, snap, q0, q1, inv_bc, eta_max, eps));
-    else GA_HINT_PATH("all streamed", diag_span<true, ROWS>(acc, theta, m, snap, q0, q1, inv_bc, eta_max, eps));
+    if (q1 <= keep_q) GA_HINT_PATH("theta kept", diag_span<false, ROWS, SROWS>(acc, theta, m, snap, q0, q1, inv_bc, eta_max, eps));
+    else GA_HINT_PATH("all streamed", diag_span<true, ROWS, SROWS>(acc, theta, m, snap, q0, q1, inv_bc, eta_max, eps));
     if (blockIdx.x == 0 && threadIdx.x < (N & 3)) {
         const uint64_t j = 4 * n4 + threadIdx.x, js = ROWS ? state_index<1, ROWS ? ROWS : 3>(j) : j;
-        diag_one(acc, theta[js], snap[j], m[js], inv_bc, eta_max, eps);
+        diag_one(acc, theta[js], snap[row_index<1, SROWS>(j)], m[js], inv_bc, eta_max, eps);
     }
     const DiagPartial r = block_reduce(acc.sum, acc.gt1, acc.gt0, acc.bad);
     if (threadIdx.x == 0) partials[blockIdx.x] = r;
@@ -253,12 +255,14 @@ __global__ __launch_bounds__(kBlock) void state_copy_kernel(float* __restrict__ 
     }
 }
 
+template <int SROWS>
 __global__ __launch_bounds__(kBlock) void broadcast_rows_kernel(float* __restrict__ dst, uint64_t stride,
                                                                 uint32_t rows, const float* __restrict__ src,
                                                                 uint64_t n) {
     for (uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += (uint64_t)gridDim.x * kBlock) {
         const float x = src[i];
-        for (uint32_t r = 0; r < rows; ++r) dst[(uint64_t)r * stride + i] = x;
+        const uint64_t ir = row_index<1, SROWS>(i);
+        for (uint32_t r = 0; r < rows; ++r) dst[(uint64_t)r * stride + ir] = x;
     }
 }
 
@@ -270,8 +274,12 @@ hipError_t launch_quadratic_gradient(const StatePtrs& st, uint64_t N, uint32_t w
     const uint64_t groups = (N + 3) >> 2;
     const uint64_t blocks = (groups + kBlock - 1) / kBlock;
     if (blocks == 0 || blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(quadratic_gradient_kernel, dim3((uint32_t)blocks), dim3(kBlock), 0, stream,
-                       st.snaps + (uint64_t)worker * st.stride, a, theta_star, N, k, rc, g_out);
+    if (st.snap_rows == 2)
+        hipLaunchKernelGGL(quadratic_gradient_kernel<2>, dim3((uint32_t)blocks), dim3(kBlock), 0, stream,
+                           st.snaps + (uint64_t)worker * st.stride, a, theta_star, N, k, rc, g_out);
+    else
+        hipLaunchKernelGGL(quadratic_gradient_kernel<1>, dim3((uint32_t)blocks), dim3(kBlock), 0, stream,
+                           st.snaps + (uint64_t)worker * st.stride, a, theta_star, N, k, rc, g_out);
     return hipGetLastError();
 }
 
@@ -279,14 +287,14 @@ hipError_t launch_diagnostics(const StatePtrs& st, uint64_t N, uint32_t worker, 
                               float eps, DiagPartial* dev_partials, ga_diag* dev_report, hipStream_t stream) {
     const DiagShape shape = diag_shape(N);
     const uint32_t grid = shape.grid;
-    if (st.rows == 4)
-        hipLaunchKernelGGL(diag_kernel<4>, dim3(grid), dim3(kBlock), 0, stream, st.theta, st.m,
-                           st.snaps + (uint64_t)worker * st.stride, N, inv_bc, eta_max, eps, shape.per_block,
-                           st.resident_bytes / sizeof(f32x4), dev_partials);
-    else
-        hipLaunchKernelGGL(diag_kernel<3>, dim3(grid), dim3(kBlock), 0, stream, st.theta, st.m,
-                           st.snaps + (uint64_t)worker * st.stride, N, inv_bc, eta_max, eps, shape.per_block,
-                           st.resident_bytes / sizeof(f32x4), dev_partials);
+#define GA_DIAG(ROWS, SROWS)                                                                                       \
+    hipLaunchKernelGGL((diag_kernel<ROWS, SROWS>), dim3(grid), dim3(kBlock), 0, stream, st.theta, st.m,             \
+                       st.snaps + (uint64_t)worker * st.stride, N, inv_bc, eta_max, eps, shape.per_block,           \
+                       st.resident_bytes / sizeof(f32x4), dev_partials)
+    if (st.rows == 4) GA_DIAG(4, 1);
+    else if (st.snap_rows == 2) GA_DIAG(3, 2);
+    else GA_DIAG(3, 1);
+#undef GA_DIAG
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (dev_report)
@@ -322,7 +330,7 @@ hipError_t launch_diagnostics_static(const float* theta, const float* snap, cons
     // every partial that the report kernel reads is written by this launch first: nothing has to start at zero
     const DiagShape shape = diag_shape(N);
     const uint32_t grid = shape.grid;
-    hipLaunchKernelGGL(diag_kernel<0>, dim3(grid), dim3(kBlock), 0, stream, theta, m, snap, N, inv_bc, eta_max, eps,
+    hipLaunchKernelGGL((diag_kernel<0, 1>), dim3(grid), dim3(kBlock), 0, stream, theta, m, snap, N, inv_bc, eta_max, eps,
                        shape.per_block, kResidentBytes / sizeof(f32x4), partials);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -354,11 +362,12 @@ hipError_t launch_fill(float* dst, uint64_t n, float value, hipStream_t stream) 
     return hipGetLastError();
 }
 
-hipError_t launch_broadcast_rows(float* dst, uint64_t stride, uint32_t rows, const float* src, uint64_t n,
+hipError_t launch_broadcast_rows(float* dst, uint64_t stride, uint32_t rows, int snap_rows, const float* src, uint64_t n,
                                  hipStream_t stream) {
     if (n == 0 || rows == 0) return hipSuccess;
-    hipLaunchKernelGGL(broadcast_rows_kernel, dim3(blocks_for(n, kBlock * 4, 65536)), dim3(kBlock), 0, stream, dst,
-                       stride, rows, src, n);
+    const dim3 grid(blocks_for(n, kBlock * 4, 65536)), block(kBlock);
+    if (snap_rows == 2) hipLaunchKernelGGL(broadcast_rows_kernel<2>, grid, block, 0, stream, dst, stride, rows, src, n);
+    else hipLaunchKernelGGL(broadcast_rows_kernel<1>, grid, block, 0, stream, dst, stride, rows, src, n);
     return hipGetLastError();
 }
 
@@ -366,6 +375,7 @@ hipError_t launch_state_get(const float* state, int rows, float* dst, uint64_t n
     if (n == 0) return hipSuccess;
     const dim3 grid(blocks_for(n, kBlock * 8, 65536)), block(kBlock);
     if (rows == 4) hipLaunchKernelGGL((state_copy_kernel<false, 4>), grid, block, 0, stream, const_cast<float*>(state), dst, n);
+    else if (rows == 2) hipLaunchKernelGGL((state_copy_kernel<false, 2>), grid, block, 0, stream, const_cast<float*>(state), dst, n);
     else if (rows == 3) hipLaunchKernelGGL((state_copy_kernel<false, 3>), grid, block, 0, stream, const_cast<float*>(state), dst, n);
     else return hipErrorInvalidValue;
     return hipGetLastError();
@@ -375,6 +385,7 @@ hipError_t launch_state_put(float* state, int rows, const float* src, uint64_t n
     if (n == 0) return hipSuccess;
     const dim3 grid(blocks_for(n, kBlock * 8, 65536)), block(kBlock);
     if (rows == 4) hipLaunchKernelGGL((state_copy_kernel<true, 4>), grid, block, 0, stream, state, const_cast<float*>(src), n);
+    else if (rows == 2) hipLaunchKernelGGL((state_copy_kernel<true, 2>), grid, block, 0, stream, state, const_cast<float*>(src), n);
     else if (rows == 3) hipLaunchKernelGGL((state_copy_kernel<true, 3>), grid, block, 0, stream, state, const_cast<float*>(src), n);
     else return hipErrorInvalidValue;
     return hipGetLastError();

@@ -90,6 +90,7 @@ uint64_t round_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
 struct Layout {
     uint64_t Np, n_rows;
     size_t off_theta, off_v, off_m, off_snaps, off_worker_v, off_v2, off_table, off_partials, total;
+    size_t worker_bytes;   // bytes between consecutive workers' regions
     size_t off_chunks, off_spans, off_layer_partials, off_gaps, off_adam_table, off_grad_table;
 };
 
@@ -118,8 +119,8 @@ bool build_layer_tables(uint64_t N, uint32_t n_layers, const uint64_t* sizes, st
     return start == N && n_chunks < 0x7FFFFFFFull;
 }
 
-// theta, v, m [ADAM: and v2] interleaved by tiles (ga_internal.h) | W snapshots | [DANA: W worker momenta] | arrival,
-// Adam and gradient-pointer tables | reduction partials
+// theta, v, m [ADAM: and v2] interleaved by tiles (ga_internal.h) | W snapshot rows [DANA: W tiled pairs of snapshot
+// and worker momentum] | arrival, Adam and gradient-pointer tables | reduction partials
 Layout layout_for(uint64_t N, uint32_t W, int family, uint64_t n_chunks = 0, uint32_t n_layers = 0) {
     Layout L;
     L.Np = round_up(N, 64);                  // every row starts 256-byte aligned
@@ -129,14 +130,16 @@ Layout layout_for(uint64_t N, uint32_t W, int family, uint64_t n_chunks = 0, uin
     L.off_v = tile;
     L.off_m = 2 * tile;
     L.off_v2 = family == GA_FAMILY_ADAM ? 3 * tile : 0;      // ADAM: the fourth tiled array
-    L.off_snaps = (size_t)ga::state_rows(family) * (size_t)round_up(N, ga::kStateTile) * sizeof(float);
-    L.n_rows = (uint64_t)W;                  // plain rows after the tiled part
+    const size_t tiled_row = (size_t)round_up(N, ga::kStateTile) * sizeof(float);
+    L.off_snaps = (size_t)ga::state_rows(family) * tiled_row;
+    L.n_rows = (uint64_t)W;                  // per-worker regions after the tiled state
     L.off_worker_v = 0;
-    if (family == GA_FAMILY_DANA) {
-        L.off_worker_v = L.off_snaps + L.n_rows * row;
-        L.n_rows += W;
+    L.worker_bytes = row;                    // a snapshot row
+    if (family == GA_FAMILY_DANA) {          // snapshot and v_i of a worker: a tiled pair (ga_internal.h)
+        L.worker_bytes = 2 * tiled_row;
+        L.off_worker_v = L.off_snaps + tile;
     }
-    L.off_table = L.off_snaps + L.n_rows * row;
+    L.off_table = L.off_snaps + L.n_rows * L.worker_bytes;
     L.off_adam_table = L.off_table + round_up((uint64_t)ga::kTableCap * sizeof(ga_arrival), 256);
     L.off_grad_table = L.off_adam_table + round_up((uint64_t)ga::kTableCap * sizeof(ga::AdamRow), 256);
     L.off_partials = L.off_grad_table + round_up((uint64_t)ga::kTableCap * sizeof(void*), 256);
@@ -379,16 +382,20 @@ int apply_one(ga_ctx* ctx, uint32_t worker, const void* dev_grad, int dtype, boo
     return GA_OK;
 }
 
-// theta, v and m are tiled in the workspace (ga_internal.h): a kernel gathers / scatters them; the rows are copied.
-bool is_tiled(const ga_ctx* ctx, const float* p) {
-    return p == ctx->st.theta || p == ctx->st.v || p == ctx->st.m || (ctx->st.v2 && p == ctx->st.v2);
+// theta, v, m (v2) and, in the DANA master, the per-worker arrays are tiled in the workspace (ga_internal.h): a kernel
+// gathers / scatters them; plain rows are copied.
+// Arrays per tile at p: theta, v, m (v2) are tiled with the state, a DANA worker's snapshot and v_i as a pair; 1: a row.
+int tiled_rows(const ga_ctx* ctx, const float* p) {
+    if (p == ctx->st.theta || p == ctx->st.v || p == ctx->st.m || (ctx->st.v2 && p == ctx->st.v2)) return ctx->st.rows;
+    return ctx->st.snap_rows;   // every other array handed to the copy helpers is a per-worker one
 }
 
 int copy_out(ga_ctx* ctx, float* dst, const float* src) {
     if (!ctx) return GA_ERR_ARG;
     if (!dst) return fail(ctx, GA_ERR_ARG, "destination is null");
-    const hipError_t e = is_tiled(ctx, src)
-                             ? ga::launch_state_get(src, ctx->st.rows, dst, ctx->N, ctx->stream)
+    const int rows = tiled_rows(ctx, src);
+    const hipError_t e = rows > 1
+                             ? ga::launch_state_get(src, rows, dst, ctx->N, ctx->stream)
                              : hipMemcpyAsync(dst, src, ctx->N * sizeof(float), hipMemcpyDeviceToDevice, ctx->stream);
     return e == hipSuccess ? GA_OK : hip_fail(ctx, e, "copy");
 }
@@ -396,8 +403,9 @@ int copy_out(ga_ctx* ctx, float* dst, const float* src) {
 int copy_in(ga_ctx* ctx, float* dst, const float* src) {
     if (!ctx) return GA_ERR_ARG;
     if (!src) return fail(ctx, GA_ERR_ARG, "source is null");
-    const hipError_t e = is_tiled(ctx, dst)
-                             ? ga::launch_state_put(dst, ctx->st.rows, src, ctx->N, ctx->stream)
+    const int rows = tiled_rows(ctx, dst);
+    const hipError_t e = rows > 1
+                             ? ga::launch_state_put(dst, rows, src, ctx->N, ctx->stream)
                              : hipMemcpyAsync(dst, src, ctx->N * sizeof(float), hipMemcpyDeviceToDevice, ctx->stream);
     return e == hipSuccess ? GA_OK : hip_fail(ctx, e, "copy");
 }
@@ -606,7 +614,8 @@ int ga_create_ex(ga_ctx** out, const ga_config* cfg, void* dev_workspace, size_t
     c->st.worker_v = L.off_worker_v ? reinterpret_cast<float*>(base + L.off_worker_v) : nullptr;
     c->st.v2 = L.off_v2 ? reinterpret_cast<float*>(base + L.off_v2) : nullptr;
     c->st.rows = ga::state_rows(cfg->family);
-    c->st.stride = L.Np;
+    c->st.snap_rows = ga::snapshot_rows(cfg->family);
+    c->st.stride = L.worker_bytes / sizeof(float);
     c->st.resident_bytes = ga::kResidentBytes;
     c->dev_table = reinterpret_cast<ga_arrival*>(base + L.off_table);
     c->dev_adam_table = reinterpret_cast<ga::AdamRow*>(base + L.off_adam_table);
@@ -715,7 +724,7 @@ int ga_set_theta(ga_ctx* ctx, const float* dev_theta0) {
     if (!dev_theta0) return fail(ctx, GA_ERR_ARG, "set_theta: source is null");
     if (ctx->k != 0) return fail(ctx, GA_ERR_STATE, "set_theta: only before the first arrival");
     hipError_t e = ga::launch_state_put(ctx->st.theta, ctx->st.rows, dev_theta0, ctx->N, ctx->stream);
-    if (e == hipSuccess) e = ga::launch_broadcast_rows(ctx->st.snaps, ctx->st.stride, ctx->W, dev_theta0, ctx->N, ctx->stream);
+    if (e == hipSuccess) e = ga::launch_broadcast_rows(ctx->st.snaps, ctx->st.stride, ctx->W, ctx->st.snap_rows, dev_theta0, ctx->N, ctx->stream);
     return e == hipSuccess ? GA_OK : hip_fail(ctx, e, "set_theta");
 }
 

@@ -94,16 +94,29 @@ __host__ __device__ inline uint64_t state_index(uint64_t i) {
 }
 constexpr int state_rows(int family) { return family == GA_FAMILY_ADAM ? 4 : 3; }
 
+// The per-worker arrays.  A worker's snapshot is a plain row of N floats, except in the DANA master, whose arrival
+// reads and rewrites two arrays of the arriving worker, the snapshot and the momentum v_i: there the two are a tiled
+// pair, [snapshot tile 0 | v_i tile 0 | snapshot tile 1 | ...] (stand-alone kernel with DANA's traffic at 151 M
+// parameters: 5.98 TB/s with two rows, 6.37 TB/s with the pair).  row_index<UNIT, ROWS> is the index inside one
+// worker's region: the identity for ROWS = 1.
+constexpr int snapshot_rows(int family) { return family == GA_FAMILY_DANA ? 2 : 1; }
+template <int UNIT, int ROWS>
+__host__ __device__ inline uint64_t row_index(uint64_t i) {
+    if constexpr (ROWS == 1) return i;
+    else return state_index<UNIT, ROWS>(i);
+}
+
 // State pointers inside the workspace.  snaps is W rows of `stride` floats.
 struct StatePtrs {
     float* theta;     // tile 0 of theta; index with state_index
     float* v;         // tile 0 of: MOMENTUM: v;  DANA: vsum;  ADAM: m1 (= theta + kStateTile)
     float* m;         // tile 0 of the Alg. 14 state (= theta + 2 kStateTile)
-    float* snaps;
-    float* worker_v;  // DANA: W rows of v_i, else null
+    float* snaps;     // worker 0's snapshot (DANA: tile 0 of it); worker w's is `stride` floats further per w
+    float* worker_v;  // DANA: tile 0 of worker 0's v_i (= snaps + kStateTile), else null
+    int snap_rows;    // snapshot_rows(family)
     float* v2;        // ADAM: tile 0 of the second moment (= theta + 3 kStateTile; index with state_index<.., 4>), else null
     int rows;         // tiled arrays per tile: state_rows(family)
-    uint64_t stride;  // floats between consecutive workers' rows (N rounded up to 64)
+    uint64_t stride;  // floats between consecutive workers' regions (N rounded up to 64; DANA: 2 x N rounded up to a tile)
     uint64_t resident_bytes;  // budget of the cache-resident leading part of theta, v, m
 };
 
@@ -167,14 +180,15 @@ hipError_t launch_probe_streams(uint32_t n_read, uint32_t n_write, uint32_t n_re
                                 const float* const* reads, float* const* writes, hipStream_t stream);
 hipError_t launch_probe_valu(int op, uint32_t blocks, uint32_t iterations, uint32_t* dev_out, hipStream_t stream);
 
-// One tiled state array (the theta, v, m or v2 pointer of StatePtrs) read into / written from a plain array of n
-// floats; rows = state_rows(family).
+// One tiled array (the theta, v, m or v2 pointer of StatePtrs with rows = state_rows(family); in the DANA master a
+// worker's snapshot or v_i with rows = 2) read into / written from a plain array of n floats.
 hipError_t launch_state_get(const float* state, int rows, float* dst, uint64_t n, hipStream_t stream);
 hipError_t launch_state_put(float* state, int rows, const float* src, uint64_t n, hipStream_t stream);
 
-// dst[0..n) = value;  dst[r][0..n) = src[0..n) for r < rows (row stride in floats).
+// dst[0..n) = value;  worker r's snapshot = src[0..n) for r < rows (stride in floats between workers; snap_rows as in
+// StatePtrs).
 hipError_t launch_fill(float* dst, uint64_t n, float value, hipStream_t stream);
-hipError_t launch_broadcast_rows(float* dst, uint64_t stride, uint32_t rows, const float* src, uint64_t n,
+hipError_t launch_broadcast_rows(float* dst, uint64_t stride, uint32_t rows, int snap_rows, const float* src, uint64_t n,
                                  hipStream_t stream);
 
 }  // namespace ga

@@ -90,6 +90,7 @@ __global__ __launch_bounds__(kBlock) void persistent_kernel(float* __restrict__ 
 
     // every array is padded so that the vector access is always in bounds; theta, x and m are tiled (ga_internal.h)
     const uint64_t ps = state_index<E, state_rows(FAMILY)>(p);
+    const uint64_t pr = row_index<E, snapshot_rows(FAMILY)>(p);   // this pack in a worker's snapshot (DANA: and in its v_i)
     Pack<E> th = pack_load<E>(theta, ps);
     Pack<E> xx = pack_load<E>(x, ps);                          // v | sum_j v_j | m1
     Pack<E> mm = pack_zero<E>();
@@ -119,8 +120,8 @@ __global__ __launch_bounds__(kBlock) void persistent_kernel(float* __restrict__ 
 
     ga_arrival row = table[0];
     Pack<E> s = pack_zero<E>();                                // this thread's part of the arriving worker's snapshot
-    if constexpr (SNAP) s = pack_load<E>(snaps + (uint64_t)row.worker * stride, p);
-    if constexpr (DANA) yy = pack_load<E>(worker_v + (uint64_t)row.worker * stride, p);
+    if constexpr (SNAP) s = pack_load<E>(snaps + (uint64_t)row.worker * stride, pr);
+    if constexpr (DANA) yy = pack_load<E>(worker_v + (uint64_t)row.worker * stride, pr);
     Pack<E> gb = pack_zero<E>();
     if constexpr (!QUAD) gb = grad_pack<E, SRC>(grads[0], p, n_valid);
 
@@ -130,8 +131,8 @@ __global__ __launch_bounds__(kBlock) void persistent_kernel(float* __restrict__ 
         Pack<E> s_next = s, y_next = yy, g_next = gb;
         if (more) {
             next = table[t + 1];
-            if constexpr (SNAP) s_next = pack_load<E>(snaps + (uint64_t)next.worker * stride, p);
-            if constexpr (DANA) y_next = pack_load<E>(worker_v + (uint64_t)next.worker * stride, p);
+            if constexpr (SNAP) s_next = pack_load<E>(snaps + (uint64_t)next.worker * stride, pr);
+            if constexpr (DANA) y_next = pack_load<E>(worker_v + (uint64_t)next.worker * stride, pr);
             if constexpr (!QUAD) g_next = grad_pack<E, SRC>(grads[t + 1], p, n_valid);
         }
         const uint64_t k = k0 + t + 1;
@@ -165,8 +166,8 @@ __global__ __launch_bounds__(kBlock) void persistent_kernel(float* __restrict__ 
             }
         }
 
-        if constexpr (SNAP) pack_store<E>(snaps + (uint64_t)row.worker * stride, p, out);
-        if constexpr (DANA) pack_store<E>(worker_v + (uint64_t)row.worker * stride, p, yy);
+        if constexpr (SNAP) pack_store<E>(snaps + (uint64_t)row.worker * stride, pr, out);
+        if constexpr (DANA) pack_store<E>(worker_v + (uint64_t)row.worker * stride, pr, yy);
         // same worker twice in a row: its rows are what was just written
         const bool same = (next.worker == row.worker);
 #pragma unroll

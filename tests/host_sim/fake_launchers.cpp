@@ -85,20 +85,24 @@ hipError_t launch_box_muller_raw(const uint32_t*, const uint32_t*, uint64_t, flo
 hipError_t launch_noise_fill(uint64_t, uint64_t, uint64_t, uint64_t, float*, hipStream_t) { return hipSuccess; }
 hipError_t launch_probe_streams(uint32_t, uint32_t, uint32_t, bool, uint64_t, const float* const*, float* const*, hipStream_t) { return hipSuccess; }
 hipError_t launch_probe_valu(int, uint32_t, uint32_t, uint32_t*, hipStream_t) { return hipSuccess; }
+static uint64_t tiled(int rows, uint64_t i) {
+    return rows == 4 ? state_index<1, 4>(i) : rows == 2 ? state_index<1, 2>(i) : rows == 3 ? state_index<1, 3>(i) : i;
+}
 hipError_t launch_state_get(const float* state, int rows, float* dst, uint64_t n, hipStream_t) {
-    for (uint64_t i = 0; i < n; ++i) dst[i] = state[rows == 4 ? state_index<1, 4>(i) : state_index<1, 3>(i)];
+    for (uint64_t i = 0; i < n; ++i) dst[i] = state[tiled(rows, i)];
     return hipSuccess;
 }
 hipError_t launch_state_put(float* state, int rows, const float* src, uint64_t n, hipStream_t) {
-    for (uint64_t i = 0; i < n; ++i) state[rows == 4 ? state_index<1, 4>(i) : state_index<1, 3>(i)] = src[i];
+    for (uint64_t i = 0; i < n; ++i) state[tiled(rows, i)] = src[i];
     return hipSuccess;
 }
 hipError_t launch_fill(float* dst, uint64_t n, float value, hipStream_t) {
     for (uint64_t i = 0; i < n; ++i) dst[i] = value;
     return hipSuccess;
 }
-hipError_t launch_broadcast_rows(float* dst, uint64_t stride, uint32_t rows, const float* src, uint64_t n, hipStream_t) {
-    for (uint32_t r = 0; r < rows; ++r) std::memcpy(dst + (uint64_t)r * stride, src, n * sizeof(float));
+hipError_t launch_broadcast_rows(float* dst, uint64_t stride, uint32_t rows, int snap_rows, const float* src, uint64_t n, hipStream_t) {
+    for (uint32_t r = 0; r < rows; ++r)
+        for (uint64_t i = 0; i < n; ++i) dst[(uint64_t)r * stride + tiled(snap_rows, i)] = src[i];
     return hipSuccess;
 }
 

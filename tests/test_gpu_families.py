@@ -174,8 +174,9 @@ def test_family_argument_errors():
     with pytest.raises(ga.GaError) as e:
         D.array(ga.GA_ARR_WORKER_V, 2)
     assert e.value.status == ga.GA_ERR_WORKER
+    # DANA: every worker's snapshot and momentum are a tiled pair (tiles of 8192 floats) instead of one row of 128
     assert ga.ga_workspace_bytes_ex(ga.ga_config_init(N=128, n_workers=4, family=ga.GA_FAMILY_DANA)) \
-        - ga.ga_workspace_bytes(128, 4) == 4 * 128 * 4
+        - ga.ga_workspace_bytes(128, 4) == 4 * (2 * 8192 - 128) * 4
     # Adam's second moment is a fourth array in the tile structure of theta, m1, m (tiles of 8192 floats)
     assert ga.ga_workspace_bytes_ex(ga.ga_config_init(N=128, n_workers=4, family=ga.GA_FAMILY_ADAM)) \
         - ga.ga_workspace_bytes(128, 4) == 8192 * 4
@@ -233,7 +234,7 @@ def test_export_import_state_resumes_bit_identically(family):
     for w in range(W):
         assert bits_equal(host(A.snapshot(w)), host(C2.snapshot(w))) == 0
     assert C2.k == A.k and np.array_equal(C2.iter(), A.iter())
-    other = ga.Master(N + 64, W, eta=eta, mode=ga.GA_MODE_GA, family=family)
+    other = ga.Master(N + 8192, W, eta=eta, mode=ga.GA_MODE_GA, family=family)     # one more tile of every tiled array
     with pytest.raises(ga.GaError) as e:
         ga.ga_import_state(other.ctx, ckpt, k, it)
     assert e.value.status == ga.GA_ERR_ARG
