@@ -37,8 +37,8 @@ VALU_PER_UPDATE = {"ga": 106.7, "ga_hinge": 106.7}
 # scaled by a copy of known size; profiles/apply_kernel_cfg3.md).  The counters sit in front of the memory-side
 # cache, so hits in that cache are included.  Valid for the kernel source with this hash only.
 TRAFFIC = {
-    ("cfg3", "ga", 25_557_032): {"bytes": 920040576, "read": 511127433, "written": 408913143, "kernels_sha256": "d31dfab950cc62dc"},
-    ("cfg3", "ga", 151_000_000): {"bytes": 5435414572, "read": 3019394804, "written": 2416019768, "kernels_sha256": "d31dfab950cc62dc"},
+    ("cfg3", "ga", 25_557_032): {"bytes": 920040674, "read": 511127518, "written": 408913156, "kernels_sha256": "3f185de6b5c57bdf"},
+    ("cfg3", "ga", 151_000_000): {"bytes": 5435414330, "read": 3019394769, "written": 2416019561, "kernels_sha256": "3f185de6b5c57bdf"},
 }
 BYTES_PER_UPDATE = {           # algorithmic bytes per parameter per arrival, fused update
     ("ga", "f32"): 36, ("ga", "bf16"): 34, ("ga_hinge", "f32"): 36, ("ga_hinge", "bf16"): 34,

@@ -27,7 +27,7 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 // 128-bit accesses with or without the non-temporal hint.  The MI355X has a
 // 256 MB memory-side cache in front of HBM: arrays that are touched once per
 // arrival (gradient, the arriving worker's snapshot) are streamed around it so
-// that arrays touched at every arrival (theta, and v when both fit) stay in it.
+// that a leading part of the arrays touched at every arrival (theta, then v, then m) stays in it (Residency below).
 template <bool NT>
 __device__ __forceinline__ f32x4 load4(const float* __restrict__ base, uint64_t q) {
     const f32x4* p = reinterpret_cast<const f32x4*>(base) + q;
@@ -207,8 +207,8 @@ __device__ __forceinline__ float load_g1(const void* __restrict__ g, uint64_t j)
 // hint do not displace lines brought in without it.  The arrays a kernel touches at every arrival (theta, v, m)
 // therefore keep a leading part in that cache from one arrival to the next: the blocks below a threshold access it
 // without the hint, all other accesses carry it.  Measured with the fused update on 70 M - 250 M parameters: the
-// time falls linearly with the kept bytes up to 256 MiB and is back at the all-streamed time from 288 MiB on (the
-// kept lines then evict each other), so the budget stays clear of that edge.  For the same bytes, keeping more
+// time falls linearly with the kept bytes up to about 224 MiB, is flat to 256 MiB and is back at the all-streamed
+// time from 288 MiB on (the kept lines then evict each other), so the budget stays clear of that edge.  For the same bytes, keeping more
 // of theta beats keeping the same parameters' theta and v.  The default budget is kResidentBytes (ga_internal.h): a
 // master that shares the GPU with other tenants of that cache is given a smaller one.
 
