@@ -473,7 +473,9 @@ int ga_set_bookkeeping(ga_ctx* ctx, uint64_t k, const uint64_t* host_iter);
  * buffer of at least that size, 16-byte aligned) and writes the host
  * bookkeeping: *k and host_iter[n_workers].  ga_import_state restores both into
  * a context created with the same N, n_workers, family and gap scope
- * (GA_ERR_ARG if `bytes` differs from ga_state_bytes, or an iter[i] > k).
+ * (GA_ERR_ARG if `bytes` differs from ga_state_bytes, or an iter[i] > k; the
+ * arrays are padded to whole tiles, so contexts whose N differ by less than a
+ * tile can have the same size: the caller keeps N with the checkpoint).
  * Hyper-parameters are not part of the checkpoint.  Running on after an
  * import gives bit for bit the trajectory of the uninterrupted run. */
 size_t ga_state_bytes(const ga_ctx* ctx);
